@@ -1,0 +1,423 @@
+"""Pins for the CPU oracle: hand-worked cases, closed forms, identities and brute force.
+
+None of these call the HIP library.  Expected values come from tests/golden/ (hand
+arithmetic and figures the paper states) or from the mathematics itself.
+"""
+import json
+import math
+import os
+from fractions import Fraction
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import fda_oracle as O
+
+GOLD = os.path.join(os.path.dirname(__file__), "golden")
+P = (1 << 31) - 1
+
+
+def gold(name):
+    with open(os.path.join(GOLD, name)) as f:
+        return json.load(f)
+
+
+def rand_coef(rng, l):
+    return rng.integers(0, P, size=(l, 2, 4), dtype=np.int64).astype(np.uint32)
+
+
+# --------------------------------------------------------------------------- #
+# hand case K=2, d=4
+# --------------------------------------------------------------------------- #
+def test_hand_case_k2_d4():
+    g = gold("hand_case_k2_d4.json")
+    w = np.array(g["w"], np.float32)
+    w0 = np.array(g["w_t0"], np.float32)
+    assert O.true_variance(w.astype(np.float64)) == pytest.approx(g["variance"], abs=1e-15)
+    st = O.local_state(w, "f32", w0, np.array(g["xi_axis"], np.float32), None, 0)
+    assert st["n"].tolist() == g["sq_norms"]
+    assert st["p"].tolist() == g["proj_axis"]
+    assert O.h_linear(st["n"], st["p"]) == pytest.approx(g["h_linear_axis"], abs=1e-15)
+    xi = np.array(g["xi_tight_times_sqrt2"], np.float64) / math.sqrt(2.0)
+    u = O.drift(w.astype(np.float64), w0.astype(np.float64))
+    assert O.h_linear(O.sq_norms(u), O.projections(u, xi)) == pytest.approx(g["h_linear_tight"], abs=1e-15)
+
+
+# --------------------------------------------------------------------------- #
+# hand case K=3, d=8 (integers: exact in any precision)
+# --------------------------------------------------------------------------- #
+def test_hand_case_k3_d8_scalars():
+    g = gold("hand_case_k3_d8.json")
+    w = np.array(g["w"], np.float32)
+    w0 = np.array(g["w_t0"], np.float32)
+    w64 = w.astype(np.float64)
+    u = O.drift(w64, w0.astype(np.float64))
+    assert u.tolist() == g["u"]
+    assert O.sq_norms(u).tolist() == g["sq_norms"]
+    assert (3 * u.mean(axis=0)).round(12).tolist() == g["mean_drift_times_3"]
+    assert O.true_variance(w64) == pytest.approx(g["variance"], rel=1e-14)
+    wbar = O.mean_model(w64)
+    for k in range(3):
+        dk = w64[k] - wbar
+        assert 9 * float(dk @ dk) == pytest.approx(g["eq1_terms_times_9"][k], rel=1e-13)
+    n = O.sq_norms(u)
+    pa = O.projections(u, np.array(g["xi_a"]))
+    assert pa.tolist() == g["proj_a"]
+    assert O.h_linear(n, pa) == pytest.approx(g["h_linear_a"], rel=1e-14)
+    pb = O.projections(u, np.array(g["xi_b"], np.float64))
+    assert pb.tolist() == g["proj_b"]
+    assert 9 * O.h_linear(n, pb) == pytest.approx(g["h_linear_b_times_9"], rel=1e-14)
+
+
+def test_hand_case_k3_d8_hash_and_sketch():
+    g = gold("hand_case_k3_d8.json")
+    coef = np.array(g["hash_coef"], np.uint32)
+    m = g["m"]
+    j = np.arange(8)
+    assert O.poly_hash(coef[2][0], j).tolist() == g["row2_bucket_poly_values"]
+    for i in range(3):
+        b, s = O.bucket_and_sign(coef[i], j, m)
+        assert b.tolist() == g["buckets"][i]
+        assert s.tolist() == g["signs"][i]
+    w = np.array(g["w"], np.float32)
+    w0 = np.array(g["w_t0"], np.float32)
+    st = O.local_state(w, "f32", w0, None, coef, m)
+    assert st["sk"].tolist() == g["sketches"]
+    sk_bar = st["sk"].mean(axis=0)
+    assert np.allclose(3 * sk_bar, g["mean_sketch_times_3"], rtol=0, atol=1e-14)
+    rows = np.einsum("ib,ib->i", sk_bar, sk_bar)
+    assert np.allclose(9 * rows, g["mean_sketch_row_sq_norms_times_9"], rtol=1e-14)
+    assert 3 * O.m2_estimate(sk_bar) == pytest.approx(g["m2_times_3"], rel=1e-14)
+    assert O.h_sketch(st["n"], st["sk"], g["eps"]) == pytest.approx(g["h_sketch"], rel=1e-13)
+    # the hand case was built so that the estimate equals the true variance: strict '>'
+    est = O.estimate_variance(st["n"], None, st["sk"], g["eps"], theta=10.5)
+    assert est["sync_sketch"] == 0
+    est = O.estimate_variance(st["n"], None, st["sk"], g["eps"], theta=9.5)
+    assert est["sync_sketch"] == 1
+
+
+def test_tug_of_war_m1():
+    g = gold("hand_case_k3_d8.json")
+    coef = np.array([[[123, 456, 789, 1011], [0, 1, 0, 0]]], np.uint32)   # bucket poly irrelevant
+    w = np.array(g["w"], np.float32)
+    w0 = np.array(g["w_t0"], np.float32)
+    st = O.local_state(w, "f32", w0, None, coef, 1)
+    assert st["sk"].reshape(3).tolist() == g["tug_of_war"]
+    assert 9 * O.m2_estimate(st["sk"].mean(axis=0)) == pytest.approx(g["tug_of_war_m2_times_9"], rel=1e-14)
+    assert 45 * O.h_sketch(st["n"], st["sk"], 0.25) == pytest.approx(g["tug_of_war_h_sketch_times_45"], rel=1e-14)
+
+
+# --------------------------------------------------------------------------- #
+# hash: closed forms, a structural property of cubics, big-integer brute force
+# --------------------------------------------------------------------------- #
+def test_hash_closed_forms():
+    rng = np.random.default_rng(1)
+    for _ in range(20):
+        c = [int(x) for x in rng.integers(0, P, 4)]
+        g = O.poly_hash(c, np.array([0, 1, P - 1]))
+        assert int(g[0]) == c[0]
+        assert int(g[1]) == sum(c) % P
+        assert int(g[2]) == (c[0] - c[1] + c[2] - c[3]) % P      # j = p-1 = -1 (mod p)
+    # identity polynomial: bucket = floor(j m / 2^31)
+    b, s = O.bucket_and_sign([[0, 1, 0, 0], [0, 1, 0, 0]], np.array([0, 1, 2**21, 2**30, P - 1]), 1000)
+    assert b.tolist() == [0, 0, 0, 500, 999]
+    assert s.tolist() == [1, -1, 1, 1, 1]
+
+
+def test_hash_fourth_difference_vanishes():
+    """A cubic's 4th finite difference is zero; modulo p it must be a multiple of p."""
+    rng = np.random.default_rng(2)
+    for _ in range(10):
+        c = [int(x) for x in rng.integers(0, P, 4)]
+        j0 = int(rng.integers(0, P - 10))
+        g = [int(v) for v in O.poly_hash(c, np.arange(j0, j0 + 5))]
+        assert (g[4] - 4 * g[3] + 6 * g[2] - 4 * g[1] + g[0]) % P == 0
+        # third difference is the constant 6 c3
+        assert (g[3] - 3 * g[2] + 3 * g[1] - g[0]) % P == (6 * c[3]) % P
+
+
+def test_hash_bigint_brute_force():
+    rng = np.random.default_rng(3)
+    keys = np.concatenate([np.arange(64), rng.integers(0, P, 200), [P - 1, P - 2, 349_999_999]])
+    for _ in range(5):
+        coef = rand_coef(rng, 1)[0]
+        for m in (1, 250, 500, 1000, 1024):
+            b, s = O.bucket_and_sign(coef, keys, m)
+            for t, j in enumerate(keys.tolist()):
+                gb = sum(int(coef[0][e]) * j**e for e in range(4)) % P
+                gs = sum(int(coef[1][e]) * j**e for e in range(4)) % P
+                assert b[t] == (gb * m) // 2**31
+                assert s[t] == (1 if gs % 2 == 0 else -1)
+            assert b.min() >= 0 and b.max() < m
+
+
+def test_hash_rejects_out_of_range():
+    with pytest.raises(ValueError):
+        O.poly_hash([0, 1, 0, 0], np.array([P]))
+    with pytest.raises(ValueError):
+        O.poly_hash([P, 1, 0, 0], np.array([1]))
+
+
+def test_hash_balance_statistics():
+    rng = np.random.default_rng(4)
+    coef = rand_coef(rng, 1)[0]
+    d, m = 400_000, 250
+    b, s = O.bucket_and_sign(coef, np.arange(d), m)
+    counts = np.bincount(b, minlength=m)
+    chi2 = float(((counts - d / m) ** 2 / (d / m)).sum())
+    assert chi2 < 249 + 6 * math.sqrt(2 * 249)          # ~6 sigma
+    assert abs(s.sum()) < 6 * math.sqrt(d)
+
+
+# --------------------------------------------------------------------------- #
+# sketch structure
+# --------------------------------------------------------------------------- #
+def test_sketch_injective_is_signed_permutation():
+    """m >= d with a bucket map that is the identity on [0, d): each row holds +-v, so
+    M2 equals ||v||^2 exactly (up to fp64 rounding of the sum)."""
+    d, m = 16, 16
+    c1 = -(-2**31 // m)                      # ceil(2^31 / m): bucket(j) = j for j < m
+    coef = np.array([[[0, c1, 0, 0], [5, 3, 0, 0]],
+                     [[0, c1, 0, 0], [1, 0, 1, 0]],
+                     [[0, c1, 0, 0], [7, 1, 1, 1]]], np.uint32)
+    rng = np.random.default_rng(5)
+    v = rng.normal(size=d)
+    sk = O.ams_sketch(v, coef, m)
+    assert np.array_equal(np.abs(sk), np.tile(np.abs(v), (3, 1)))
+    assert O.m2_estimate(sk) == pytest.approx(float(v @ v), rel=1e-15)
+    sign_row0 = np.array([1 if ((5 + 3 * j) % P) % 2 == 0 else -1 for j in range(d)])
+    assert np.array_equal(sk[0], sign_row0 * v)
+
+
+def test_sketch_linearity_and_column_sums():
+    rng = np.random.default_rng(6)
+    d, l, m, K = 5000, 5, 250, 4
+    coef = rand_coef(rng, l)
+    u = rng.normal(size=(K, d)) * 1e-3
+    sks = np.stack([O.ams_sketch(u[k], coef, m) for k in range(K)])
+    lhs = O.ams_sketch(u.mean(axis=0), coef, m)
+    assert np.allclose(lhs, sks.mean(axis=0), rtol=0, atol=1e-12 * np.abs(u).sum() / K)
+    a, b = 0.3, -1.7
+    assert np.allclose(O.ams_sketch(a * u[0] + b * u[1], coef, m), a * sks[0] + b * sks[1],
+                       rtol=0, atol=1e-15 * d)
+    j = np.arange(d)
+    for i in range(l):
+        _, s = O.bucket_and_sign(coef[i], j, m)
+        assert sks[0][i].sum() == pytest.approx(float((s * u[0]).sum()), abs=1e-14)
+    # the absolute-value sketch bounds every cell
+    assert (np.abs(sks[0]) <= O.ams_sketch_abs(u[0], coef, m) + 1e-18).all()
+
+
+def test_sketch_pure_python_brute_force():
+    rng = np.random.default_rng(7)
+    d, l, m = 40, 3, 7
+    coef = rand_coef(rng, l)
+    v = rng.normal(size=d)
+    want = [[0.0] * m for _ in range(l)]
+    for i in range(l):
+        for j in range(d):
+            gb = sum(int(coef[i][0][e]) * j**e for e in range(4)) % P
+            gs = sum(int(coef[i][1][e]) * j**e for e in range(4)) % P
+            want[i][(gb * m) >> 31] += (1.0 if gs % 2 == 0 else -1.0) * v[j]
+    assert np.allclose(O.ams_sketch(v, coef, m), np.array(want), rtol=0, atol=1e-14)
+
+
+def test_sketch_row_estimator_unbiased():
+    """E[ ||psi_i||^2 ] = ||v||^2 over the hash family (AMS / Fast-AGMS property)."""
+    rng = np.random.default_rng(8)
+    d, m = 3000, 250
+    v = rng.normal(size=d)
+    vv = float(v @ v)
+    rows = []
+    for _ in range(120):
+        sk = O.ams_sketch(v, rand_coef(rng, 5), m)
+        rows.extend(np.einsum("ib,ib->i", sk, sk) / vv)
+    rows = np.array(rows)
+    # std of one row is about sqrt(2/m) = 0.089; the mean of 600 rows within 4.5 sigma
+    assert abs(rows.mean() - 1.0) < 4.5 * math.sqrt(2.0 / m) / math.sqrt(len(rows))
+
+
+def test_paper_sketch_sizing():
+    g = gold("paper_sketch_sizing.json")
+    assert g["l"] * g["m"] * 4 == g["bytes"]
+    rng = np.random.default_rng(9)
+    d = 4000
+    v = rng.normal(size=d)
+    vv = float(v @ v)
+    hits, over = 0, 0
+    trials = 200
+    for _ in range(trials):
+        m2 = O.m2_estimate(O.ams_sketch(v, rand_coef(rng, g["l"]), g["m"]))
+        hits += abs(m2 / vv - 1.0) <= g["eps"]
+        over += m2 <= (1 + g["eps"]) * vv
+    # The paper's ~95 % was measured on its own training drifts.  For the median of 5
+    # rows of relative spread sqrt(2/250) the Gaussian estimate is ~0.79 two-sided and
+    # ~0.90 one-sided (the side Theorem 1 needs); both are loose sanity bands.
+    assert 0.65 <= hits / trials <= 1.0
+    assert 0.80 <= over / trials <= 1.0
+
+
+def test_median_even_rows():
+    sk = np.array([[1.0, 0], [2.0, 0], [3.0, 0], [10.0, 0]])
+    assert O.m2_estimate(sk) == pytest.approx((4.0 + 9.0) / 2)
+    assert O.m2_estimate(sk[:3]) == pytest.approx(4.0)
+
+
+# --------------------------------------------------------------------------- #
+# variance identity and the two theorems
+# --------------------------------------------------------------------------- #
+@pytest.mark.parametrize("K,d", [(1, 50), (2, 7), (5, 1000), (30, 333)])
+def test_variance_identity_eq1_eq3(K, d):
+    rng = np.random.default_rng(10 + K)
+    w0 = rng.normal(size=d).astype(np.float32)
+    w = (w0 + rng.normal(size=(K, d)) * 1e-2).astype(np.float32)
+    w64 = w.astype(np.float64)
+    u = O.drift(w64, w0.astype(np.float64))
+    ubar = u.mean(axis=0)
+    eq3 = float(O.sq_norms(u).mean() - ubar @ ubar)
+    var = O.true_variance(w64)
+    assert var == pytest.approx(eq3, rel=1e-10, abs=1e-18)
+    if K == 1:
+        assert var == 0.0
+
+
+def test_theorem2_upper_bound_and_tightness():
+    rng = np.random.default_rng(11)
+    K, d = 6, 500
+    w0 = rng.normal(size=d).astype(np.float32)
+    w = (w0 + 0.01 * rng.normal(size=d) + 0.003 * rng.normal(size=(K, d))).astype(np.float32)
+    w64 = w.astype(np.float64)
+    u = O.drift(w64, w0.astype(np.float64))
+    var = O.true_variance(w64)
+    n = O.sq_norms(u)
+    for _ in range(20):
+        xi = rng.normal(size=d)
+        xi /= np.linalg.norm(xi)
+        assert O.h_linear(n, O.projections(u, xi)) >= var * (1 - 1e-12)
+    ubar = u.mean(axis=0)
+    xi = ubar / np.linalg.norm(ubar)
+    assert O.h_linear(n, O.projections(u, xi)) == pytest.approx(var, rel=1e-9)
+    # all workers equal: zero variance, the linear estimate can still be positive
+    c = rng.normal(size=d)
+    ueq = np.tile(c, (K, 1))
+    assert O.true_variance(ueq) == pytest.approx(0.0, abs=1e-20)
+    e0 = np.zeros(d)
+    e0[0] = 1.0
+    assert O.h_linear(O.sq_norms(ueq), O.projections(ueq, e0)) == pytest.approx(c @ c - c[0] ** 2, rel=1e-12)
+
+
+def test_theorem1_overestimates_with_high_probability():
+    rng = np.random.default_rng(12)
+    K, d, l, m, eps = 5, 3000, 5, 250, 0.06
+    w0 = np.zeros(d, np.float32)
+    w = (0.01 * rng.normal(size=d) + 0.004 * rng.normal(size=(K, d))).astype(np.float32)
+    var = O.true_variance(w.astype(np.float64))
+    ok = 0
+    trials = 60
+    for _ in range(trials):
+        st = O.local_state(w, "f32", w0, None, rand_coef(rng, l), m)
+        ok += O.h_sketch(st["n"], st["sk"], eps) >= var
+    assert ok / trials >= 0.8
+
+
+# --------------------------------------------------------------------------- #
+# decision, synchronization, xi
+# --------------------------------------------------------------------------- #
+def test_decision_strict_and_flags():
+    assert O.decide(1.0, 1.0, 1.0, 0.0) == (0, 1, 0)            # tie: no sync
+    assert O.decide(np.nextafter(1.0, 2.0), 1.0, 1.0, 0.0)[0] == 1
+    assert O.decide(0.0, 0.0, 0.0, 1e-5) == (0, 1, 0)           # Theta = 0, no drift: 0 > 0 is false
+    assert O.decide(1e-30, 0.0, 1e-30, 1e-5)[0] == 1            # Theta = 0: any drift synchronizes
+    assert O.decide(float("nan"), 1.0, 1.0, 1e-5) == (1, 0, 1)
+    assert O.decide(float("inf"), 1.0, 1.0, 1e-5) == (1, 0, 1)
+    assert O.decide(1.0 + 5e-6, 1.0, 1.0, 1e-5)[1] == 1
+    assert O.decide(1.0 + 5e-5, 1.0, 1.0, 1e-5)[1] == 0
+
+
+def test_sync_f32_zero_variance_and_state():
+    rng = np.random.default_rng(13)
+    K, d = 7, 300
+    w0 = rng.normal(size=d).astype(np.float32)
+    w = (w0 + rng.normal(size=(K, d)) * 1e-2).astype(np.float32)
+    s = O.sync(w, "f32", w0)
+    assert np.array_equal(s["w_prev"], w0)
+    assert np.allclose(s["mean"], w.astype(np.float64).sum(axis=0) / K, rtol=1e-15)
+    new_w = np.tile(s["rows"], (K, 1))
+    assert O.true_variance(new_w.astype(np.float64)) == 0.0
+    coef = rand_coef(rng, 3)
+    st = O.local_state(new_w, "f32", s["rows"], rng.normal(size=d).astype(np.float32), coef, 50)
+    assert not st["n"].any() and not st["p"].any() and not st["sk"].any()
+    est = O.estimate_variance(st["n"], st["p"], st["sk"], 0.06, theta=0.0)
+    assert est["h_linear"] == 0.0 and est["h_sketch"] == 0.0
+    assert est["sync_linear"] == 0 and est["sync_sketch"] == 0
+
+
+def test_bf16_rounding_against_torch():
+    rng = np.random.default_rng(14)
+    x = np.concatenate([rng.normal(size=20000) * 0.05, rng.normal(size=2000) * 1e-30,
+                        [0.0, -0.0, 1.0, 1.00390625, 1.01171875, 3.0e38, 1e-40, -1e-40]]).astype(np.float32)
+    want = torch.from_numpy(x).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    got = O.round_to_bf16_bits(x.astype(np.float64))
+    assert np.array_equal(got, want)
+    # ties go to even: 1 + 2^-8 is halfway between 1 and 1 + 2^-7
+    assert O.round_to_bf16_bits(np.array([1.0 + 2.0**-8]))[0] == 0x3F80
+    assert O.round_to_bf16_bits(np.array([1.0 + 3 * 2.0**-8]))[0] == 0x3F82
+    # widening undoes it exactly
+    assert np.array_equal(O.widen(got[:100], "bf16").astype(np.float32),
+                          torch.from_numpy(x[:100]).to(torch.bfloat16).float().numpy())
+
+
+def test_sync_bf16_rows_equal_and_residue():
+    rng = np.random.default_rng(15)
+    K, d = 4, 200
+    w0 = (rng.normal(size=d) * 0.05).astype(np.float32)
+    wf = (w0 + rng.normal(size=(K, d)) * 1e-3).astype(np.float32)
+    wb = O.round_to_bf16_bits(wf.astype(np.float64))
+    s = O.sync(wb, "bf16", w0)
+    assert s["rows"].dtype == np.uint16
+    rows64 = O.widen(s["rows"], "bf16")
+    # nearest bf16: error at most half a bf16 spacing (2^-8 relative)
+    assert (np.abs(rows64 - s["mean"]) <= np.abs(s["mean"]) * 2.0**-8).all()
+    new_w = np.tile(s["rows"], (K, 1))
+    assert O.true_variance(O.widen(new_w, "bf16")) == 0.0
+    # the state right after a bf16 sync is the quantization residue, not zero
+    st = O.local_state(new_w, "bf16", s["mean"].astype(np.float32), None, None, 0)
+    assert st["n"][0] > 0 and np.all(st["n"] == st["n"][0])
+
+
+def test_update_xi():
+    w_prev = np.array([1, 1, 1, 1], np.float32)
+    w_t0 = np.array([4, 1, 5, 1], np.float32)               # difference (3, 0, 4, 0), norm 5
+    assert O.update_xi(w_t0, w_prev).tolist() == [0.6, 0.0, 0.8, 0.0]
+    assert O.update_xi(w_t0, w_t0).tolist() == [0, 0, 0, 0]
+    rng = np.random.default_rng(16)
+    a, b = rng.normal(size=1000).astype(np.float32), rng.normal(size=1000).astype(np.float32)
+    xi = O.update_xi(a, b)
+    assert float(xi @ xi) == pytest.approx(1.0, rel=1e-14)
+    assert np.allclose(np.cross(xi[:3], (a.astype(np.float64) - b)[:3]), 0, atol=1e-15)
+
+
+def test_state_layout_sizes():
+    """Thm 1: state in R x R^{l x m}; Thm 2: state in R x R."""
+    rng = np.random.default_rng(17)
+    w = rng.normal(size=(3, 64)).astype(np.float32)
+    st = O.local_state(w, "f32", np.zeros(64, np.float32), np.ones(64, np.float32) / 8, rand_coef(rng, 5), 25)
+    assert st["n"].shape == (3,) and st["p"].shape == (3,) and st["sk"].shape == (3, 5, 25)
+
+
+def test_exact_rational_cross_check_of_h():
+    """Eq. 3 and Thm 2 evaluated in exact rational arithmetic on a small integer case."""
+    rng = np.random.default_rng(18)
+    K, d = 3, 6
+    w0 = rng.integers(-5, 5, d)
+    w = rng.integers(-5, 5, (K, d))
+    xi_int = rng.integers(-3, 3, d)
+    u = [[Fraction(int(w[k][j] - w0[j])) for j in range(d)] for k in range(K)]
+    nbar = sum(sum(x * x for x in uk) for uk in u) / K
+    ubar = [sum(u[k][j] for k in range(K)) / K for j in range(d)]
+    var = nbar - sum(x * x for x in ubar)
+    assert O.true_variance(w.astype(np.float64)) == pytest.approx(float(var), rel=1e-13, abs=1e-13)
+    st = O.local_state(w.astype(np.float32), "f32", w0.astype(np.float32), xi_int.astype(np.float32), None, 0)
+    pbar = sum(sum(int(xi_int[j]) * u[k][j] for j in range(d)) for k in range(K)) / K
+    assert O.h_linear(st["n"], st["p"]) == pytest.approx(float(nbar - pbar * pbar), rel=1e-13, abs=1e-13)
