@@ -1,0 +1,191 @@
+/*
+ * fda.h -- C ABI of the FDA (Federated Dynamic Averaging, arxiv 2405.20988) monitor for
+ * K simulated workers held as one [K, d] parameter slab in the memory of ONE AMD
+ * MI355X (gfx950).
+ *
+ * What the library computes, per training step (Algorithm 1, lines 6-9):
+ *   line 6  fda_local_state        the K local states S_k = (||u_k||^2, <xi,u_k>, sk(u_k))
+ *                                  of the drifts u_k = w_k - w_t0 (Section 3; Thm 1; Thm 2)
+ *   line 7-8 fda_estimate_variance the averaged state, the two variance over-estimates
+ *                                  H(S) and their comparison with the threshold Theta
+ *   line 9  fda_sync               w_k <- mean_k w_k for every worker, in place
+ *           fda_update_xi          the LinearFDA direction from the last two synchronized
+ *                                  models (Section 3.2, last display)
+ *
+ * Conventions
+ *   - C99, no C++ types, nothing is thrown, nothing aborts.  Every call returns FDA_OK (0)
+ *     or a negative FDA_E* code; fda_strerror() names it and fda_last_error() gives the
+ *     detail of the most recent failure on the calling thread.
+ *   - "DEVICE" pointers are addresses in the current HIP device's memory; "HOST" pointers
+ *     are ordinary process memory.  The library allocates no device memory and frees
+ *     none: slab, vectors, states, result structs and the workspace belong to the caller
+ *     (for example torch tensors) and must stay alive until the work enqueued on `stream`
+ *     has completed.  The library keeps no caller pointer after a call returns, except
+ *     the workspace given to fda_create, which it uses until fda_destroy.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  All calls
+ *     only enqueue work, except fda_estimate_variance with a non-NULL out_host, which
+ *     also waits for the stream.
+ *   - One fda_ctx serves one stream at a time (its workspace is scratch for the kernels).
+ *   - Without a usable HIP device every call that needs one fails with FDA_EHIP; there is
+ *     no CPU fallback.
+ */
+#ifndef FDA_H_
+#define FDA_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* error codes */
+#define FDA_OK       0
+#define FDA_EINVAL  (-1)   /* NULL pointer, non-positive size, bad enum, misaligned pointer     */
+#define FDA_ERANGE  (-2)   /* d not below the hash prime, sketch too large for one CU's LDS ... */
+#define FDA_ENOMEM  (-3)   /* workspace smaller than fda_workspace_bytes() asks for             */
+#define FDA_EHIP    (-4)   /* a HIP runtime call failed (no device, bad launch, ...)            */
+
+/* storage type of the slab elements; w_t0, w_prev, xi and the states are always fp32 */
+#define FDA_F32   0
+#define FDA_BF16  1        /* bfloat16: drift and every accumulation are formed in fp32  */
+
+/* which state components / estimates to produce (bit mask) */
+#define FDA_VARIANT_LINEAR  1   /* LinearFDA, Thm 2 */
+#define FDA_VARIANT_SKETCH  2   /* SketchFDA, Thm 1 */
+
+#define FDA_MAX_SKETCH_ROWS 16
+#define FDA_HASH_PRIME      2147483647u   /* 2^31 - 1 */
+
+typedef struct fda_ctx fda_ctx;   /* opaque */
+
+/*
+ * Problem description (Section 3, "Problem formulation" and "Notation": K workers, each a
+ * model w_k in R^d; Section 3.1: an l x m AMS sketch with error parameter eps).
+ *
+ * hash_coef: HOST pointer to l*2*4 uint32 values, index [row][which][e], every value
+ * below 2^31 - 1.  Row i of the sketch uses two cubic polynomials over the prime
+ * p = 2^31 - 1,  g(j) = c3 j^3 + c2 j^2 + c1 j + c0 mod p  with c_e = hash_coef[i][which][e]:
+ * which = 0 places coordinate j in bucket floor(g(j) * m / 2^31); which = 1 gives its sign,
+ * +1 if g(j) is even and -1 otherwise.  The values are copied by fda_create.  May be NULL
+ * when FDA_VARIANT_SKETCH is not requested.
+ */
+typedef struct fda_desc {
+  int32_t K;            /* number of workers (rows of the slab), >= 1                      */
+  int32_t dtype;        /* FDA_F32 or FDA_BF16                                              */
+  int64_t d;            /* model dimension, 1 <= d < 2^31 - 1 - 64                          */
+  int64_t row_stride;   /* elements between consecutive rows of the slab, >= d              */
+  int32_t variants;     /* FDA_VARIANT_* bit mask, non-zero                                 */
+  int32_t l;            /* sketch rows,   1..FDA_MAX_SKETCH_ROWS (ignored without SKETCH)   */
+  int32_t m;            /* sketch columns, >= 1                  (ignored without SKETCH)   */
+  int32_t reserved;     /* must be 0                                                        */
+  double  eps;          /* the epsilon of Thm 1: H = mean||u||^2 - M2 / (1 + eps)           */
+  const uint32_t* hash_coef;
+} fda_desc;
+
+/* Result of fda_estimate_variance (64 bytes).  Entries of a variant that was not requested
+ * are zero. */
+typedef struct fda_estimate {
+  double  mean_sqnorm;      /* (1/K) sum_k ||u_k||^2                                        */
+  double  mean_proj;        /* (1/K) sum_k <xi,u_k>                                         */
+  double  m2;               /* M2( (1/K) sum_k sk(u_k) ): median of the squared row norms   */
+  double  h_linear;         /* Thm 2: mean_sqnorm - mean_proj^2                             */
+  double  h_sketch;         /* Thm 1: mean_sqnorm - m2 / (1 + eps)                          */
+  int32_t sync_linear;      /* 1 iff h_linear > theta (strict), or h_linear is not finite   */
+  int32_t sync_sketch;      /* 1 iff h_sketch > theta (strict), or h_sketch is not finite   */
+  int32_t near_tie_linear;  /* 1 iff |h_linear - theta| <= tie_tol * max(mean_sqnorm,|theta|) */
+  int32_t near_tie_sketch;  /* same for h_sketch                                            */
+  int32_t nonfinite;        /* 1 iff a requested estimate is NaN or infinite                */
+  int32_t reserved;
+} fda_estimate;
+
+/* How the state pass is laid out on the chip; filled by fda_plan (for inspection and for
+ * sizing the workspace without a device). */
+typedef struct fda_plan_info {
+  int32_t worker_groups;    /* the K workers are split into this many groups of workgroups  */
+  int32_t workers_per_group;/* largest group                                                */
+  int32_t partitions;       /* coordinate partitions (workgroups per worker group)          */
+  int32_t threads;          /* threads per workgroup                                        */
+  int64_t chunk;            /* coordinates per partition                                    */
+  int64_t lds_bytes;        /* LDS per workgroup                                            */
+  int64_t workspace_bytes;  /* device scratch the context needs                             */
+  int64_t state_floats;     /* floats per worker state: 2 + l*m with SKETCH, else 2         */
+} fda_plan_info;
+
+const char* fda_strerror(int code);
+/* Detail text of the last failing call on this thread (valid until the next failure). */
+const char* fda_last_error(void);
+
+/* Pure host computation: validate `desc` and lay out the state pass for a device with
+ * `compute_units` CUs and `lds_bytes_per_cu` bytes of LDS per CU.  Touches no device. */
+int fda_plan(const fda_desc* desc, int32_t compute_units, int64_t lds_bytes_per_cu,
+             fda_plan_info* out);
+
+/* Bytes of DEVICE scratch fda_create needs for `desc` on the current HIP device. */
+int fda_workspace_bytes(const fda_desc* desc, size_t* bytes);
+
+/* Create a context on the current HIP device.  `workspace` is a DEVICE pointer, 256-byte
+ * aligned, of at least fda_workspace_bytes() bytes, owned by the caller and left with the
+ * context until fda_destroy.  On failure *ctx is set to NULL. */
+int fda_create(fda_ctx** ctx, const fda_desc* desc, void* workspace, size_t workspace_bytes);
+int fda_destroy(fda_ctx* ctx);
+
+/* Floats per worker state S: state[k] = { ||u_k||^2, <xi,u_k>, sk(u_k) row-major l x m }.
+ * (Thm 1: S_k in R x R^{l x m}; Thm 2: S_k in R x R; both share the first component.) */
+int fda_state_floats(const fda_ctx* ctx, int64_t* S);
+int fda_get_plan(const fda_ctx* ctx, fda_plan_info* out);
+
+/*
+ * Algorithm 1, line 6, for all K workers at once.
+ *   w      DEVICE [K][row_stride] slab of dtype elements (row k = model of worker k)
+ *   w_t0   DEVICE [d] fp32: the model after the most recent synchronization
+ *   xi     DEVICE [d] fp32: the LinearFDA unit vector (may be NULL without LINEAR)
+ *   state  DEVICE [K][S] fp32, written:  state[k][0] = ||w_k - w_t0||^2,
+ *          state[k][1] = <xi, w_k - w_t0> (0 without LINEAR),
+ *          state[k][2 + i*m + b] = sum over coordinates j in bucket b of row i of
+ *          sign_i(j) (w_kj - w_t0_j)   (absent without SKETCH)
+ * Pointers 16-byte aligned and row_stride*sizeof(element) a multiple of 16 take the
+ * vector path; anything else is handled element by element (slow, not an error).
+ * Sketch cells are accumulated with LDS floating-point atomics, so their last bits may
+ * differ from run to run; everything across workgroups is merged in a fixed order.
+ */
+int fda_local_state(fda_ctx* ctx, const void* w, const float* w_t0, const float* xi,
+                    float* state, void* stream);
+
+/*
+ * Algorithm 1, lines 7-8: average the K states, evaluate H of Thm 1 and/or Thm 2 in
+ * fp64, compare with theta (strict '>').  tie_tol sets the near-tie flags (pass 1e-5 for
+ * the tolerance the fp32 states are good for, 0 to flag exact ties only).
+ *   state     DEVICE [K][S] as written by fda_local_state
+ *   out_dev   DEVICE fda_estimate, written (required)
+ *   out_host  HOST fda_estimate or NULL; if given the call copies the result and waits
+ *             for `stream`
+ */
+int fda_estimate_variance(fda_ctx* ctx, const float* state, double theta, double tie_tol,
+                          fda_estimate* out_dev, fda_estimate* out_host, void* stream);
+
+/*
+ * Algorithm 1, line 9 ("In-place"): every row of the slab becomes the average model.
+ *   w        DEVICE slab, rewritten: row k <- (1/K) sum_k' row k'  (fp32 sum in worker
+ *            order, divided by K; bf16 slabs store its round-to-nearest-even)
+ *   w_t0     DEVICE [d] fp32, rewritten with the fp32 average
+ *   w_prev   DEVICE [d] fp32 or NULL: receives the old w_t0 (the model after the second
+ *            most recent synchronization, Table "Notation")
+ *   pred_dev DEVICE int32 or NULL: if given and *pred_dev == 0 when the kernel runs,
+ *            nothing is written (lets a step be enqueued without reading the decision
+ *            back; point it at fda_estimate.sync_linear or .sync_sketch)
+ */
+int fda_sync(fda_ctx* ctx, void* w, float* w_t0, float* w_prev, const int32_t* pred_dev,
+             void* stream);
+
+/*
+ * Section 3.2: xi <- (w_t0 - w_prev) / ||w_t0 - w_prev||_2 (all DEVICE [d] fp32); the zero
+ * vector when the norm is zero or not finite.  pred_dev as in fda_sync.
+ */
+int fda_update_xi(fda_ctx* ctx, const float* w_t0, const float* w_prev, float* xi,
+                  const int32_t* pred_dev, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FDA_H_ */

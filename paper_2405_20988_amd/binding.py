@@ -1,0 +1,178 @@
+"""ctypes binding of include/fda.h: same names, argument marshalling only.
+
+Device pointers are plain integers (for a torch tensor: ``t.data_ptr()``); streams are the
+integer ``torch.cuda.current_stream().cuda_stream``.  Nothing here computes anything: if
+the HIP library is missing the import of a symbol fails loudly (there is no fallback).
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import numpy as np
+
+FDA_OK, FDA_EINVAL, FDA_ERANGE, FDA_ENOMEM, FDA_EHIP = 0, -1, -2, -3, -4
+FDA_F32, FDA_BF16 = 0, 1
+FDA_VARIANT_LINEAR, FDA_VARIANT_SKETCH = 1, 2
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_PKG, "lib", "libfda.so")
+_lib = None
+
+
+class FdaError(RuntimeError):
+    def __init__(self, code: int, what: str):
+        super().__init__(f"{what}: {fda_strerror(code)} ({code}): {fda_last_error()}")
+        self.code = code
+
+
+class FdaDesc(C.Structure):
+    _fields_ = [("K", C.c_int32), ("dtype", C.c_int32), ("d", C.c_int64),
+                ("row_stride", C.c_int64), ("variants", C.c_int32), ("l", C.c_int32),
+                ("m", C.c_int32), ("reserved", C.c_int32), ("eps", C.c_double),
+                ("hash_coef", C.POINTER(C.c_uint32))]
+
+
+class FdaEstimate(C.Structure):
+    _fields_ = [("mean_sqnorm", C.c_double), ("mean_proj", C.c_double), ("m2", C.c_double),
+                ("h_linear", C.c_double), ("h_sketch", C.c_double),
+                ("sync_linear", C.c_int32), ("sync_sketch", C.c_int32),
+                ("near_tie_linear", C.c_int32), ("near_tie_sketch", C.c_int32),
+                ("nonfinite", C.c_int32), ("reserved", C.c_int32)]
+
+    def as_dict(self) -> dict:
+        return {name: getattr(self, name) for name, _ in self._fields_ if name != "reserved"}
+
+
+class FdaPlanInfo(C.Structure):
+    _fields_ = [("worker_groups", C.c_int32), ("workers_per_group", C.c_int32),
+                ("partitions", C.c_int32), ("threads", C.c_int32), ("chunk", C.c_int64),
+                ("lds_bytes", C.c_int64), ("workspace_bytes", C.c_int64),
+                ("state_floats", C.c_int64)]
+
+    def as_dict(self) -> dict:
+        return {name: getattr(self, name) for name, _ in self._fields_}
+
+
+def library_path() -> str:
+    return _LIB_PATH
+
+
+def load_library():
+    """Load libfda.so (built in-tree by paper_2405_20988_amd.build).  Raises if absent."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise FileNotFoundError(
+            f"{_LIB_PATH} is missing: build it with `python -m paper_2405_20988_amd.build` "
+            "(needs hipcc); there is no CPU fallback")
+    lib = C.CDLL(_LIB_PATH)
+    vp, i32p = C.c_void_p, C.c_void_p
+    lib.fda_strerror.restype = C.c_char_p
+    lib.fda_strerror.argtypes = [C.c_int]
+    lib.fda_last_error.restype = C.c_char_p
+    lib.fda_last_error.argtypes = []
+    lib.fda_plan.argtypes = [C.POINTER(FdaDesc), C.c_int32, C.c_int64, C.POINTER(FdaPlanInfo)]
+    lib.fda_workspace_bytes.argtypes = [C.POINTER(FdaDesc), C.POINTER(C.c_size_t)]
+    lib.fda_create.argtypes = [C.POINTER(vp), C.POINTER(FdaDesc), vp, C.c_size_t]
+    lib.fda_destroy.argtypes = [vp]
+    lib.fda_state_floats.argtypes = [vp, C.POINTER(C.c_int64)]
+    lib.fda_get_plan.argtypes = [vp, C.POINTER(FdaPlanInfo)]
+    lib.fda_local_state.argtypes = [vp, vp, vp, vp, vp, vp]
+    lib.fda_estimate_variance.argtypes = [vp, vp, C.c_double, C.c_double, vp,
+                                          C.POINTER(FdaEstimate), vp]
+    lib.fda_sync.argtypes = [vp, vp, vp, vp, i32p, vp]
+    lib.fda_update_xi.argtypes = [vp, vp, vp, vp, i32p, vp]
+    for name in ("fda_plan", "fda_workspace_bytes", "fda_create", "fda_destroy",
+                 "fda_state_floats", "fda_get_plan", "fda_local_state",
+                 "fda_estimate_variance", "fda_sync", "fda_update_xi"):
+        getattr(lib, name).restype = C.c_int
+    _lib = lib
+    return lib
+
+
+def _check(rc: int, what: str) -> None:
+    if rc != FDA_OK:
+        raise FdaError(rc, what)
+
+
+def make_desc(K, d, dtype, variants, l=0, m=0, eps=0.0, hash_coef=None, row_stride=None):
+    """Fill an FdaDesc; returns (desc, keepalive) -- keepalive owns the coefficient array."""
+    desc = FdaDesc()
+    desc.K, desc.d, desc.dtype, desc.variants = int(K), int(d), int(dtype), int(variants)
+    desc.row_stride = int(d if row_stride is None else row_stride)
+    desc.l, desc.m, desc.reserved, desc.eps = int(l), int(m), 0, float(eps)
+    keep = None
+    if hash_coef is not None:
+        keep = np.ascontiguousarray(hash_coef, dtype=np.uint32)
+        desc.hash_coef = keep.ctypes.data_as(C.POINTER(C.c_uint32))
+    return desc, keep
+
+
+def fda_strerror(code: int) -> str:
+    return load_library().fda_strerror(int(code)).decode()
+
+
+def fda_last_error() -> str:
+    return load_library().fda_last_error().decode()
+
+
+def fda_plan(desc: FdaDesc, compute_units: int, lds_bytes_per_cu: int) -> FdaPlanInfo:
+    out = FdaPlanInfo()
+    _check(load_library().fda_plan(C.byref(desc), compute_units, lds_bytes_per_cu, C.byref(out)),
+           "fda_plan")
+    return out
+
+
+def fda_workspace_bytes(desc: FdaDesc) -> int:
+    n = C.c_size_t(0)
+    _check(load_library().fda_workspace_bytes(C.byref(desc), C.byref(n)), "fda_workspace_bytes")
+    return int(n.value)
+
+
+def fda_create(desc: FdaDesc, workspace_ptr: int, workspace_bytes: int) -> int:
+    ctx = C.c_void_p(None)
+    _check(load_library().fda_create(C.byref(ctx), C.byref(desc), workspace_ptr, workspace_bytes),
+           "fda_create")
+    return ctx.value
+
+
+def fda_destroy(ctx: int) -> None:
+    _check(load_library().fda_destroy(ctx), "fda_destroy")
+
+
+def fda_state_floats(ctx: int) -> int:
+    s = C.c_int64(0)
+    _check(load_library().fda_state_floats(ctx, C.byref(s)), "fda_state_floats")
+    return int(s.value)
+
+
+def fda_get_plan(ctx: int) -> FdaPlanInfo:
+    out = FdaPlanInfo()
+    _check(load_library().fda_get_plan(ctx, C.byref(out)), "fda_get_plan")
+    return out
+
+
+def fda_local_state(ctx: int, w: int, w_t0: int, xi: int | None, state: int, stream: int = 0) -> None:
+    _check(load_library().fda_local_state(ctx, w, w_t0, xi, state, stream), "fda_local_state")
+
+
+def fda_estimate_variance(ctx: int, state: int, theta: float, tie_tol: float, out_dev: int,
+                          want_host: bool = True, stream: int = 0):
+    """Returns the host copy of the result (an FdaEstimate) if want_host, else None."""
+    host = FdaEstimate() if want_host else None
+    _check(load_library().fda_estimate_variance(ctx, state, theta, tie_tol, out_dev,
+                                                C.byref(host) if want_host else None, stream),
+           "fda_estimate_variance")
+    return host
+
+
+def fda_sync(ctx: int, w: int, w_t0: int, w_prev: int | None, pred_dev: int | None = None,
+             stream: int = 0) -> None:
+    _check(load_library().fda_sync(ctx, w, w_t0, w_prev, pred_dev, stream), "fda_sync")
+
+
+def fda_update_xi(ctx: int, w_t0: int, w_prev: int, xi: int, pred_dev: int | None = None,
+                  stream: int = 0) -> None:
+    _check(load_library().fda_update_xi(ctx, w_t0, w_prev, xi, pred_dev, stream), "fda_update_xi")

@@ -1,0 +1,365 @@
+// C ABI of the FDA monitor (include/fda.h): argument checks, launch planning, kernel
+// launches.  Everything the path computes runs in the kernels of fda_kernels.hpp.
+#include <hip/hip_runtime.h>
+
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+
+#include "fda.h"
+#include "fda_kernels.hpp"
+
+namespace {
+
+thread_local char g_err[512] = "";
+
+int fail(int code, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+  return code;
+}
+
+#define FDA_HIP(call)                                                                  \
+  do {                                                                                 \
+    hipError_t e_ = (call);                                                            \
+    if (e_ != hipSuccess)                                                              \
+      return fail(FDA_EHIP, "%s failed: %s", #call, hipGetErrorString(e_));            \
+  } while (0)
+
+constexpr int64_t kLdsReserve = 4096;      // reduction scratch + slack behind the sketch
+constexpr int kXiBlocks = 1024;
+constexpr int64_t kAlign = 256;
+
+int64_t round_up(int64_t x, int64_t a) { return (x + a - 1) / a * a; }
+
+struct Plan {
+  int G, kcnt_max, KC, P, stride, vec;      // vec = elements per 16-byte slab load
+  int64_t chunk, lds_bytes, cells, S;
+  int64_t off_np, off_sk, off_xi, ws_bytes;
+};
+
+int validate(const fda_desc* d) {
+  if (d == nullptr) return fail(FDA_EINVAL, "desc is NULL");
+  if (d->K < 1) return fail(FDA_EINVAL, "K must be >= 1 (got %d)", d->K);
+  if (d->d < 1) return fail(FDA_EINVAL, "d must be >= 1");
+  if (d->d >= (int64_t)FDA_HASH_PRIME - 64)
+    return fail(FDA_ERANGE, "d must be below 2^31 - 1 - 64: coordinates are hash keys modulo 2^31 - 1");
+  if (d->row_stride < d->d) return fail(FDA_EINVAL, "row_stride must be >= d");
+  if (d->dtype != FDA_F32 && d->dtype != FDA_BF16) return fail(FDA_EINVAL, "unknown dtype %d", d->dtype);
+  if (d->reserved != 0) return fail(FDA_EINVAL, "reserved must be 0");
+  if ((d->variants & ~(FDA_VARIANT_LINEAR | FDA_VARIANT_SKETCH)) != 0 || d->variants == 0)
+    return fail(FDA_EINVAL, "variants must be a non-empty mask of FDA_VARIANT_LINEAR | FDA_VARIANT_SKETCH");
+  if (d->variants & FDA_VARIANT_SKETCH) {
+    if (d->l < 1 || d->l > FDA_MAX_SKETCH_ROWS)
+      return fail(FDA_EINVAL, "l must be in 1..%d (got %d)", FDA_MAX_SKETCH_ROWS, d->l);
+    if (d->m < 1) return fail(FDA_EINVAL, "m must be >= 1");
+    if ((int64_t)d->l * d->m > (int64_t)1 << 24) return fail(FDA_ERANGE, "l*m too large");
+    if (!(d->eps > -1.0)) return fail(FDA_EINVAL, "eps must be > -1");
+    if (d->hash_coef == nullptr) return fail(FDA_EINVAL, "hash_coef is NULL");
+    for (int t = 0; t < d->l * 8; ++t)
+      if (d->hash_coef[t] >= FDA_HASH_PRIME)
+        return fail(FDA_ERANGE, "hash_coef[%d] is not below 2^31 - 1", t);
+  }
+  return FDA_OK;
+}
+
+int make_plan(const fda_desc* d, int cus, int64_t lds_cu, Plan* pl) {
+  if (cus < 1 || lds_cu < 16384) return fail(FDA_EINVAL, "bad device description");
+  const bool sk = (d->variants & FDA_VARIANT_SKETCH) != 0;
+  pl->cells = sk ? (int64_t)d->l * d->m : 0;
+  pl->S = 2 + pl->cells;
+  pl->vec = d->dtype == FDA_F32 ? 4 : 8;
+  // fewest worker groups whose sketch (workers padded to an odd stride) fits in LDS
+  int G = 0;
+  for (int g = 1; g <= d->K; ++g) {
+    const int kc = (d->K + g - 1) / g;
+    if (kc > fda::kMaxKC) continue;
+    const int stride = kc | 1;
+    if (pl->cells * stride * 4 + kLdsReserve <= lds_cu) { G = g; break; }
+  }
+  if (G == 0) return fail(FDA_ERANGE, "an l*m = %lld sketch does not fit in %lld bytes of LDS",
+                          (long long)pl->cells, (long long)lds_cu);
+  pl->G = G;
+  pl->kcnt_max = (d->K + G - 1) / G;
+  pl->stride = pl->kcnt_max | 1;
+  int KC = 1;
+  while (KC < pl->kcnt_max) KC *= 2;
+  pl->KC = KC;
+  pl->lds_bytes = round_up(pl->cells * pl->stride * 4, 16) + kLdsReserve;
+  int occ = (int)(lds_cu / pl->lds_bytes);
+  if (occ > 2) occ = 2;
+  if (occ < 1) occ = 1;
+  const int64_t tile = (int64_t)fda::kStateThreads * pl->vec;
+  int64_t P = (int64_t)cus * occ / G / 8 * 8;
+  if (P < 8) P = 8;
+  const int64_t tiles = (d->d + tile - 1) / tile;
+  if (P > round_up(tiles, 8)) P = round_up(tiles, 8);
+  pl->P = (int)P;
+  pl->chunk = round_up((d->d + P - 1) / P, tile);
+  pl->off_np = 0;
+  pl->off_sk = round_up(pl->off_np + P * d->K * 2 * 8, kAlign);
+  pl->off_xi = round_up(pl->off_sk + P * d->K * pl->cells * 4, kAlign);
+  pl->ws_bytes = round_up(pl->off_xi + kXiBlocks * 8, kAlign);
+  return FDA_OK;
+}
+
+void export_plan(const Plan& pl, fda_plan_info* out) {
+  out->worker_groups = pl.G;
+  out->workers_per_group = pl.kcnt_max;
+  out->partitions = pl.P;
+  out->threads = fda::kStateThreads;
+  out->chunk = pl.chunk;
+  out->lds_bytes = pl.lds_bytes;
+  out->workspace_bytes = pl.ws_bytes;
+  out->state_floats = pl.S;
+}
+
+int device_shape(int* cus, int64_t* lds) {
+  int dev = 0;
+  FDA_HIP(hipGetDevice(&dev));
+  int v = 0;
+  FDA_HIP(hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev));
+  *cus = v;
+  FDA_HIP(hipDeviceGetAttribute(&v, hipDeviceAttributeMaxSharedMemoryPerBlock, dev));
+  *lds = v;
+  return FDA_OK;
+}
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
+
+template <typename T, int KC>
+int launch_state(const fda::StateParams& prm, const fda::HashCoef& hc, size_t lds, hipStream_t st) {
+  auto kern = fda::state_kernel<T, KC>;
+  FDA_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+  hipLaunchKernelGGL(kern, dim3(prm.G * prm.P), dim3(fda::kStateThreads), lds, st, prm, hc);
+  FDA_HIP(hipGetLastError());
+  return FDA_OK;
+}
+
+template <typename T>
+int dispatch_state(int KC, const fda::StateParams& prm, const fda::HashCoef& hc, size_t lds,
+                   hipStream_t st) {
+  switch (KC) {
+    case 1: return launch_state<T, 1>(prm, hc, lds, st);
+    case 2: return launch_state<T, 2>(prm, hc, lds, st);
+    case 4: return launch_state<T, 4>(prm, hc, lds, st);
+    case 8: return launch_state<T, 8>(prm, hc, lds, st);
+    case 16: return launch_state<T, 16>(prm, hc, lds, st);
+  }
+  return fail(FDA_EINVAL, "internal: no kernel for %d workers per group", KC);
+}
+
+}  // namespace
+
+struct fda_ctx {
+  fda_desc desc;
+  fda::HashCoef coef;
+  Plan plan;
+  unsigned char* ws;
+  int device;
+  int cus;
+};
+
+extern "C" {
+
+const char* fda_strerror(int code) {
+  switch (code) {
+    case FDA_OK: return "success";
+    case FDA_EINVAL: return "invalid argument";
+    case FDA_ERANGE: return "value out of the supported range";
+    case FDA_ENOMEM: return "workspace too small";
+    case FDA_EHIP: return "HIP runtime error";
+  }
+  return "unknown error code";
+}
+
+const char* fda_last_error(void) { return g_err; }
+
+int fda_plan(const fda_desc* desc, int32_t compute_units, int64_t lds_bytes_per_cu,
+             fda_plan_info* out) {
+  if (out == nullptr) return fail(FDA_EINVAL, "out is NULL");
+  int rc = validate(desc);
+  if (rc != FDA_OK) return rc;
+  Plan pl;
+  rc = make_plan(desc, compute_units, lds_bytes_per_cu, &pl);
+  if (rc != FDA_OK) return rc;
+  export_plan(pl, out);
+  return FDA_OK;
+}
+
+int fda_workspace_bytes(const fda_desc* desc, size_t* bytes) {
+  if (bytes == nullptr) return fail(FDA_EINVAL, "bytes is NULL");
+  int rc = validate(desc);
+  if (rc != FDA_OK) return rc;
+  int cus = 0;
+  int64_t lds = 0;
+  rc = device_shape(&cus, &lds);
+  if (rc != FDA_OK) return rc;
+  Plan pl;
+  rc = make_plan(desc, cus, lds, &pl);
+  if (rc != FDA_OK) return rc;
+  *bytes = (size_t)pl.ws_bytes;
+  return FDA_OK;
+}
+
+int fda_create(fda_ctx** ctx, const fda_desc* desc, void* workspace, size_t workspace_bytes) {
+  if (ctx == nullptr) return fail(FDA_EINVAL, "ctx is NULL");
+  *ctx = nullptr;
+  int rc = validate(desc);
+  if (rc != FDA_OK) return rc;
+  if (workspace == nullptr) return fail(FDA_EINVAL, "workspace is NULL");
+  if (reinterpret_cast<uintptr_t>(workspace) % kAlign != 0)
+    return fail(FDA_EINVAL, "workspace must be 256-byte aligned");
+  int cus = 0;
+  int64_t lds = 0;
+  rc = device_shape(&cus, &lds);
+  if (rc != FDA_OK) return rc;
+  Plan pl;
+  rc = make_plan(desc, cus, lds, &pl);
+  if (rc != FDA_OK) return rc;
+  if ((int64_t)workspace_bytes < pl.ws_bytes)
+    return fail(FDA_ENOMEM, "workspace has %zu bytes, %lld needed", workspace_bytes, (long long)pl.ws_bytes);
+  fda_ctx* c = new (std::nothrow) fda_ctx;
+  if (c == nullptr) return fail(FDA_ENOMEM, "out of host memory");
+  c->desc = *desc;
+  c->desc.hash_coef = nullptr;
+  std::memset(&c->coef, 0, sizeof(c->coef));
+  if (desc->variants & FDA_VARIANT_SKETCH)
+    std::memcpy(&c->coef, desc->hash_coef, sizeof(uint32_t) * 8 * desc->l);
+  c->plan = pl;
+  c->ws = static_cast<unsigned char*>(workspace);
+  c->cus = cus;
+  if (hipGetDevice(&c->device) != hipSuccess) {
+    delete c;
+    return fail(FDA_EHIP, "hipGetDevice failed");
+  }
+  *ctx = c;
+  return FDA_OK;
+}
+
+int fda_destroy(fda_ctx* ctx) {
+  delete ctx;
+  return FDA_OK;
+}
+
+int fda_state_floats(const fda_ctx* ctx, int64_t* S) {
+  if (ctx == nullptr || S == nullptr) return fail(FDA_EINVAL, "NULL argument");
+  *S = ctx->plan.S;
+  return FDA_OK;
+}
+
+int fda_get_plan(const fda_ctx* ctx, fda_plan_info* out) {
+  if (ctx == nullptr || out == nullptr) return fail(FDA_EINVAL, "NULL argument");
+  export_plan(ctx->plan, out);
+  return FDA_OK;
+}
+
+int fda_local_state(fda_ctx* ctx, const void* w, const float* w_t0, const float* xi,
+                    float* state, void* stream) {
+  if (ctx == nullptr || w == nullptr || w_t0 == nullptr || state == nullptr)
+    return fail(FDA_EINVAL, "NULL argument");
+  const fda_desc& d = ctx->desc;
+  const Plan& pl = ctx->plan;
+  const bool lin = (d.variants & FDA_VARIANT_LINEAR) != 0;
+  const bool sk = (d.variants & FDA_VARIANT_SKETCH) != 0;
+  if (lin && xi == nullptr) return fail(FDA_EINVAL, "xi is NULL but FDA_VARIANT_LINEAR is requested");
+  const int esz = d.dtype == FDA_F32 ? 4 : 2;
+  if (reinterpret_cast<uintptr_t>(w) % esz != 0 || reinterpret_cast<uintptr_t>(w_t0) % 4 != 0 ||
+      reinterpret_cast<uintptr_t>(state) % 4 != 0 || (xi && reinterpret_cast<uintptr_t>(xi) % 4 != 0))
+    return fail(FDA_EINVAL, "pointer not aligned to its element type");
+  hipStream_t st = static_cast<hipStream_t>(stream);
+
+  fda::StateParams prm;
+  prm.w = w; prm.w_t0 = w_t0; prm.xi = xi;
+  prm.row_stride = d.row_stride; prm.d = d.d; prm.chunk = pl.chunk;
+  prm.K = d.K; prm.l = sk ? d.l : 0; prm.m = sk ? d.m : 0;
+  prm.G = pl.G; prm.P = pl.P; prm.stride = pl.stride;
+  prm.do_lin = lin; prm.do_sk = sk;
+  prm.vec_ok = aligned16(w) && aligned16(w_t0) && (!lin || aligned16(xi)) &&
+               (d.row_stride * esz) % 16 == 0;
+  prm.part_np = reinterpret_cast<double*>(ctx->ws + pl.off_np);
+  prm.part_sk = reinterpret_cast<float*>(ctx->ws + pl.off_sk);
+
+  int rc = d.dtype == FDA_F32
+               ? dispatch_state<float>(pl.KC, prm, ctx->coef, (size_t)pl.lds_bytes, st)
+               : dispatch_state<fda::bf16_t>(pl.KC, prm, ctx->coef, (size_t)pl.lds_bytes, st);
+  if (rc != FDA_OK) return rc;
+
+  const long long total = (long long)d.K * pl.S;
+  const int blocks = (int)((total + fda::kSmallThreads - 1) / fda::kSmallThreads);
+  hipLaunchKernelGGL(fda::merge_kernel, dim3(blocks), dim3(fda::kSmallThreads), 0, st,
+                     prm.part_np, prm.part_sk, state, d.K, (int)pl.cells, pl.P);
+  FDA_HIP(hipGetLastError());
+  return FDA_OK;
+}
+
+int fda_estimate_variance(fda_ctx* ctx, const float* state, double theta, double tie_tol,
+                          fda_estimate* out_dev, fda_estimate* out_host, void* stream) {
+  if (ctx == nullptr || state == nullptr || out_dev == nullptr)
+    return fail(FDA_EINVAL, "NULL argument");
+  if (reinterpret_cast<uintptr_t>(out_dev) % 8 != 0) return fail(FDA_EINVAL, "out_dev must be 8-byte aligned");
+  if (!(tie_tol >= 0.0)) return fail(FDA_EINVAL, "tie_tol must be >= 0");
+  const fda_desc& d = ctx->desc;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  hipLaunchKernelGGL(fda::estimate_kernel, dim3(1), dim3(1024), 0, st, state, d.K, d.l, d.m,
+                     d.variants, d.eps, theta, tie_tol, out_dev);
+  FDA_HIP(hipGetLastError());
+  if (out_host != nullptr) {
+    FDA_HIP(hipMemcpyAsync(out_host, out_dev, sizeof(fda_estimate), hipMemcpyDeviceToHost, st));
+    FDA_HIP(hipStreamSynchronize(st));
+  }
+  return FDA_OK;
+}
+
+int fda_sync(fda_ctx* ctx, void* w, float* w_t0, float* w_prev, const int32_t* pred_dev,
+             void* stream) {
+  if (ctx == nullptr || w == nullptr || w_t0 == nullptr) return fail(FDA_EINVAL, "NULL argument");
+  const fda_desc& d = ctx->desc;
+  const int esz = d.dtype == FDA_F32 ? 4 : 2;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const int vec_ok = aligned16(w) && aligned16(w_t0) && (w_prev == nullptr || aligned16(w_prev)) &&
+                     (d.row_stride * esz) % 16 == 0;
+  const int V = ctx->plan.vec;
+  const long long nvec = (d.d + V - 1) / V;
+  long long blocks = (nvec + fda::kSmallThreads - 1) / fda::kSmallThreads;
+  const long long cap = (long long)ctx->cus * 16;
+  if (blocks > cap) blocks = cap;
+  if (d.dtype == FDA_F32)
+    hipLaunchKernelGGL(fda::sync_kernel<float>, dim3((unsigned)blocks), dim3(fda::kSmallThreads), 0, st,
+                       static_cast<float*>(w), w_t0, w_prev, pred_dev, d.K, (long long)d.d,
+                       (long long)d.row_stride, vec_ok);
+  else
+    hipLaunchKernelGGL(fda::sync_kernel<fda::bf16_t>, dim3((unsigned)blocks), dim3(fda::kSmallThreads), 0,
+                       st, static_cast<fda::bf16_t*>(w), w_t0, w_prev, pred_dev, d.K, (long long)d.d,
+                       (long long)d.row_stride, vec_ok);
+  FDA_HIP(hipGetLastError());
+  return FDA_OK;
+}
+
+int fda_update_xi(fda_ctx* ctx, const float* w_t0, const float* w_prev, float* xi,
+                  const int32_t* pred_dev, void* stream) {
+  if (ctx == nullptr || w_t0 == nullptr || w_prev == nullptr || xi == nullptr)
+    return fail(FDA_EINVAL, "NULL argument");
+  const fda_desc& d = ctx->desc;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  double* partial = reinterpret_cast<double*>(ctx->ws + ctx->plan.off_xi);
+  long long blocks = (d.d + fda::kSmallThreads * 8 - 1) / (fda::kSmallThreads * 8);
+  if (blocks > kXiBlocks) blocks = kXiBlocks;
+  if (blocks < 1) blocks = 1;
+  hipLaunchKernelGGL(fda::xi_norm_kernel, dim3((unsigned)blocks), dim3(fda::kSmallThreads), 0, st,
+                     w_t0, w_prev, pred_dev, (long long)d.d, partial);
+  FDA_HIP(hipGetLastError());
+  long long sblocks = (d.d + fda::kSmallThreads - 1) / fda::kSmallThreads;
+  const long long cap = (long long)ctx->cus * 16;
+  if (sblocks > cap) sblocks = cap;
+  hipLaunchKernelGGL(fda::xi_scale_kernel, dim3((unsigned)sblocks), dim3(fda::kSmallThreads), 0, st,
+                     w_t0, w_prev, xi, pred_dev, (long long)d.d, partial, (int)blocks);
+  FDA_HIP(hipGetLastError());
+  return FDA_OK;
+}
+
+}  // extern "C"

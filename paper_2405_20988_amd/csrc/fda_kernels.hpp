@@ -1,0 +1,474 @@
+// Device code of the FDA monitor for gfx950 (wave64).  Included by fda_api.hip only.
+//
+// Kernels
+//   state_kernel     Algorithm 1 line 6: one streaming pass over the [K,d] slab that forms
+//                    the drifts in registers and reduces them to per-workgroup partial
+//                    states (squared norm, <xi,u>, AMS sketch in LDS).
+//   merge_kernel     fixed-order fp64 sum of the per-workgroup partials -> state[K][S].
+//   estimate_kernel  Algorithm 1 lines 7-8: mean state, M2, H (Thm 1, Thm 2), decision.
+//   sync_kernel      Algorithm 1 line 9: fused mean over workers + broadcast to all rows.
+//   xi_norm_kernel / xi_scale_kernel   Section 3.2: the normalized model difference.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "fda.h"
+
+namespace fda {
+
+constexpr uint32_t kPrime = 0x7fffffffu;     // 2^31 - 1
+constexpr int kStateThreads = 512;           // 8 waves per workgroup
+constexpr int kMaxKC = 16;                   // workers handled by one workgroup
+constexpr int kSmallThreads = 256;
+
+struct HashCoef {
+  uint32_t c[FDA_MAX_SKETCH_ROWS][2][4];     // [row][bucket|sign][power of j]
+};
+
+struct StateParams {
+  const void* w;
+  const float* w_t0;
+  const float* xi;
+  long long row_stride;
+  long long d;
+  long long chunk;        // coordinates per partition (multiple of the tile)
+  int K;
+  int l;
+  int m;
+  int G;                  // worker groups
+  int P;                  // coordinate partitions, multiple of 8
+  int stride;             // LDS floats per sketch cell (odd, >= workers of the group)
+  int do_lin;
+  int do_sk;
+  int vec_ok;             // all pointers / strides allow 16-byte loads
+  double* part_np;        // [P][K][2]
+  float* part_sk;         // [P][K][l*m]
+};
+
+struct bf16_t { uint16_t bits; };
+
+// ---- arithmetic modulo the Mersenne prime 2^31 - 1 (operands already reduced) --------
+__device__ __forceinline__ uint32_t addmod(uint32_t a, uint32_t b) {
+  uint32_t s = a + b;                        // < 2^32
+  return min(s, s - kPrime);                 // s - p wraps to a huge value when s < p
+}
+__device__ __forceinline__ uint32_t mulmod(uint32_t a, uint32_t b) {
+  uint64_t t = (uint64_t)a * b;              // < 2^62
+  uint32_t lo = (uint32_t)t & kPrime;
+  uint32_t hi = (uint32_t)(t >> 31);         // 2^31 = 1 (mod p)
+  uint32_t s = lo + hi;                      // <= 2p - 1
+  return min(s, s - kPrime);
+}
+// c[3] j^3 + c[2] j^2 + c[1] j + c[0] mod p
+__device__ __forceinline__ uint32_t poly3(const uint32_t* c, uint32_t j) {
+  uint32_t g = c[3];
+  g = addmod(mulmod(g, j), c[2]);
+  g = addmod(mulmod(g, j), c[1]);
+  g = addmod(mulmod(g, j), c[0]);
+  return g;
+}
+
+// ---- slab element access ---------------------------------------------------------------
+template <typename T> struct Slab;
+template <> struct Slab<float> {
+  static constexpr int V = 4;                // elements per 16-byte load
+  static __device__ __forceinline__ void load_vec(const float* p, float (&x)[4]) {
+    float4 t = *reinterpret_cast<const float4*>(p);
+    x[0] = t.x; x[1] = t.y; x[2] = t.z; x[3] = t.w;
+  }
+  static __device__ __forceinline__ float load_one(const float* p) { return *p; }
+  static __device__ __forceinline__ void store_vec(float* p, const float (&x)[4]) {
+    *reinterpret_cast<float4*>(p) = make_float4(x[0], x[1], x[2], x[3]);
+  }
+  static __device__ __forceinline__ void store_one(float* p, float x) { *p = x; }
+};
+__device__ __forceinline__ uint32_t f32_to_bf16_rne(float x) {
+  uint32_t u = __float_as_uint(x);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x40u;   // NaN stays NaN
+  return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;                   // ties to even
+}
+template <> struct Slab<bf16_t> {
+  static constexpr int V = 8;
+  static __device__ __forceinline__ void load_vec(const bf16_t* p, float (&x)[8]) {
+    uint4 t = *reinterpret_cast<const uint4*>(p);
+    x[0] = __uint_as_float(t.x << 16); x[1] = __uint_as_float(t.x & 0xffff0000u);
+    x[2] = __uint_as_float(t.y << 16); x[3] = __uint_as_float(t.y & 0xffff0000u);
+    x[4] = __uint_as_float(t.z << 16); x[5] = __uint_as_float(t.z & 0xffff0000u);
+    x[6] = __uint_as_float(t.w << 16); x[7] = __uint_as_float(t.w & 0xffff0000u);
+  }
+  static __device__ __forceinline__ float load_one(const bf16_t* p) {
+    return __uint_as_float((uint32_t)p->bits << 16);
+  }
+  static __device__ __forceinline__ void store_vec(bf16_t* p, const float (&x)[8]) {
+    uint4 t;
+    t.x = f32_to_bf16_rne(x[0]) | (f32_to_bf16_rne(x[1]) << 16);
+    t.y = f32_to_bf16_rne(x[2]) | (f32_to_bf16_rne(x[3]) << 16);
+    t.z = f32_to_bf16_rne(x[4]) | (f32_to_bf16_rne(x[5]) << 16);
+    t.w = f32_to_bf16_rne(x[6]) | (f32_to_bf16_rne(x[7]) << 16);
+    *reinterpret_cast<uint4*>(p) = t;
+  }
+  static __device__ __forceinline__ void store_one(bf16_t* p, float x) {
+    p->bits = (uint16_t)f32_to_bf16_rne(x);
+  }
+};
+
+template <int V>
+__device__ __forceinline__ void load_f32_vec(const float* p, float (&x)[V]) {
+#pragma unroll
+  for (int q = 0; q < V; q += 4) {
+    float4 t = *reinterpret_cast<const float4*>(p + q);
+    x[q] = t.x; x[q + 1] = t.y; x[q + 2] = t.z; x[q + 3] = t.w;
+  }
+}
+template <int V>
+__device__ __forceinline__ void store_f32_vec(float* p, const float (&x)[V]) {
+#pragma unroll
+  for (int q = 0; q < V; q += 4)
+    *reinterpret_cast<float4*>(p + q) = make_float4(x[q], x[q + 1], x[q + 2], x[q + 3]);
+}
+
+__device__ __forceinline__ double wave_sum(double v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_down(v, o, 64);
+  return v;                                   // valid in lane 0
+}
+
+// Sum over the workgroup in a fixed shape; result valid in thread 0.  `scratch` holds one
+// double per wave.  Ends with a barrier so scratch can be reused.
+__device__ __forceinline__ double block_sum(double v, double* scratch) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nw = (blockDim.x + 63) >> 6;
+  v = wave_sum(v);
+  if (lane == 0) scratch[wave] = v;
+  __syncthreads();
+  double r = 0.0;
+  if (threadIdx.x == 0)
+    for (int t = 0; t < nw; ++t) r += scratch[t];
+  __syncthreads();
+  return r;
+}
+
+// Split of K workers into G nearly equal groups.
+__device__ __host__ inline void group_range(int K, int G, int g, int* start, int* count) {
+  int base = K / G, rem = K % G;
+  *count = base + (g < rem ? 1 : 0);
+  *start = g * base + (g < rem ? g : rem);
+}
+
+// ----------------------------------------------------------------------------------------
+// Algorithm 1 line 6.  Workgroup (p, g) streams coordinates [p*chunk, (p+1)*chunk) of the
+// workers of group g exactly once.  Per tile every lane owns V consecutive coordinates:
+// it loads w_t0 (and xi) once, then the V elements of each of its <= KC workers, forms the
+// drifts in registers, accumulates ||u||^2 and <xi,u> (fp32 within the tile, fp64 across
+// tiles) and adds sign*u into the workgroup's private LDS sketch, laid out
+// [row][bucket][worker] with an odd worker stride so that random buckets spread over all
+// LDS banks.  The hash of a coordinate is evaluated once and reused by all workers.
+// ----------------------------------------------------------------------------------------
+template <typename T, int KC>
+__global__ void __launch_bounds__(kStateThreads)
+state_kernel(const StateParams prm, const HashCoef hc) {
+  constexpr int V = Slab<T>::V;
+  extern __shared__ __align__(16) unsigned char lds_raw[];
+  const int cells = prm.do_sk ? prm.l * prm.m : 0;
+  float* sk = reinterpret_cast<float*>(lds_raw);
+  // reduction scratch sits behind the sketch, 8-byte aligned
+  const size_t sk_bytes = ((size_t)cells * prm.stride * sizeof(float) + 15) & ~(size_t)15;
+  double* red = reinterpret_cast<double*>(lds_raw + sk_bytes);     // [waves][KC][2]
+
+  // XCD-aware placement: consecutive workgroup ids go round-robin over the 8 XCDs, so the
+  // G groups that read the same coordinates (and share w_t0 / xi) are given ids that land
+  // on one XCD and its L2.
+  const int b = blockIdx.x;
+  const int xcd = b & 7, slot = b >> 3;
+  const int g = slot % prm.G;
+  const int p = (slot / prm.G) * 8 + xcd;
+  int kstart, kcnt;
+  group_range(prm.K, prm.G, g, &kstart, &kcnt);
+
+  const int tid = threadIdx.x;
+  for (int t = tid; t < cells * prm.stride; t += kStateThreads) sk[t] = 0.0f;
+  __syncthreads();
+
+  double dn[KC], dp[KC];
+#pragma unroll
+  for (int k = 0; k < KC; ++k) { dn[k] = 0.0; dp[k] = 0.0; }
+
+  const T* wbase = reinterpret_cast<const T*>(prm.w) + (long long)kstart * prm.row_stride;
+  const long long cbeg = (long long)p * prm.chunk;
+  long long cend = cbeg + prm.chunk;
+  if (cend > prm.d) cend = prm.d;
+
+  for (long long j0 = cbeg + (long long)tid * V; j0 < cend; j0 += (long long)kStateThreads * V) {
+    float w0[V], x[V], u[KC][V];
+    const bool full = prm.vec_ok && (j0 + V <= prm.d);
+    if (full) {
+      load_f32_vec<V>(prm.w_t0 + j0, w0);
+      if (prm.do_lin) load_f32_vec<V>(prm.xi + j0, x);
+#pragma unroll
+      for (int k = 0; k < KC; ++k)
+        if (k < kcnt) Slab<T>::load_vec(wbase + (long long)k * prm.row_stride + j0, u[k]);
+    } else {
+#pragma unroll
+      for (int v = 0; v < V; ++v) {
+        const bool in = (j0 + v < prm.d);
+        w0[v] = in ? prm.w_t0[j0 + v] : 0.0f;
+        if (prm.do_lin) x[v] = in ? prm.xi[j0 + v] : 0.0f;
+#pragma unroll
+        for (int k = 0; k < KC; ++k)
+          if (k < kcnt)
+            u[k][v] = in ? Slab<T>::load_one(wbase + (long long)k * prm.row_stride + j0 + v) : 0.0f;
+      }
+    }
+    if (!prm.do_lin) {
+#pragma unroll
+      for (int v = 0; v < V; ++v) x[v] = 0.0f;
+    }
+#pragma unroll
+    for (int k = 0; k < KC; ++k) {
+      if (k < kcnt) {
+        float sn = 0.0f, sp = 0.0f;
+#pragma unroll
+        for (int v = 0; v < V; ++v) {
+          u[k][v] -= w0[v];
+          sn = fmaf(u[k][v], u[k][v], sn);
+          sp = fmaf(x[v], u[k][v], sp);
+        }
+        dn[k] += (double)sn;
+        dp[k] += (double)sp;
+      }
+    }
+    if (prm.do_sk) {
+      for (int i = 0; i < prm.l; ++i) {
+        const int rowoff = i * prm.m;
+#pragma unroll
+        for (int v = 0; v < V; ++v) {
+          const uint32_t j = (uint32_t)(j0 + v);
+          const uint32_t gb = poly3(hc.c[i][0], j);
+          const uint32_t gs = poly3(hc.c[i][1], j);
+          const uint32_t bucket = __umulhi(gb << 1, (uint32_t)prm.m);   // floor(gb*m/2^31)
+          const uint32_t smask = gs << 31;                              // odd -> negative
+          float* cell = sk + (size_t)(rowoff + bucket) * prm.stride;
+#pragma unroll
+          for (int k = 0; k < KC; ++k)
+            if (k < kcnt)
+              atomicAdd(cell + k, __uint_as_float(__float_as_uint(u[k][v]) ^ smask));
+        }
+      }
+    }
+  }
+
+  // ---- workgroup reduction of the scalar components (fixed shape) ---------------------
+  const int lane = tid & 63, wave = tid >> 6;
+  constexpr int kWaves = kStateThreads / 64;
+#pragma unroll
+  for (int k = 0; k < KC; ++k) {
+    double a = wave_sum(dn[k]);
+    double c = wave_sum(dp[k]);
+    if (lane == 0) { red[(wave * KC + k) * 2] = a; red[(wave * KC + k) * 2 + 1] = c; }
+  }
+  __syncthreads();
+  if (p < prm.P) {
+    if (tid < 2 * kcnt) {
+      const int k = tid >> 1, q = tid & 1;
+      double s = 0.0;
+      for (int wv = 0; wv < kWaves; ++wv) s += red[(wv * KC + k) * 2 + q];
+      prm.part_np[((size_t)p * prm.K + kstart + k) * 2 + q] = s;
+    }
+    // ---- flush the LDS sketch to this workgroup's slice of the partial buffer ---------
+    for (int t = tid; t < kcnt * cells; t += kStateThreads) {
+      const int k = t / cells, c = t - k * cells;
+      prm.part_sk[((size_t)p * prm.K + kstart + k) * cells + c] = sk[(size_t)c * prm.stride + k];
+    }
+  }
+}
+
+// state[k][s] = sum over partitions, in partition order, in fp64.
+__global__ void __launch_bounds__(kSmallThreads)
+merge_kernel(const double* __restrict__ part_np, const float* __restrict__ part_sk,
+             float* __restrict__ state, int K, int cells, int P) {
+  const int S = 2 + cells;
+  const long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= (long long)K * S) return;
+  const int k = (int)(idx / S), s = (int)(idx - (long long)k * S);
+  double acc = 0.0;
+  if (s < 2) {
+    for (int p = 0; p < P; ++p) acc += part_np[((size_t)p * K + k) * 2 + s];
+  } else {
+    const int c = s - 2;
+    for (int p = 0; p < P; ++p) acc += (double)part_sk[((size_t)p * K + k) * cells + c];
+  }
+  state[idx] = (float)acc;
+}
+
+// ----------------------------------------------------------------------------------------
+// Algorithm 1 lines 7-8, one workgroup, all in fp64:
+//   mean_k of the states;  row norms of the mean sketch;  M2 = their median (Section 3.1);
+//   H_sketch = n - M2/(1+eps) (Thm 1);  H_linear = n - p^2 (Thm 2);  sync = H > theta.
+// ----------------------------------------------------------------------------------------
+__global__ void __launch_bounds__(1024)
+estimate_kernel(const float* __restrict__ state, int K, int l, int m, int variants, double eps,
+                double theta, double tie_tol, fda_estimate* __restrict__ out) {
+  __shared__ double scratch[16];
+  __shared__ double rows[FDA_MAX_SKETCH_ROWS];
+  const int cells = (variants & FDA_VARIANT_SKETCH) ? l * m : 0;
+  const int S = 2 + cells;
+  const int tid = threadIdx.x;
+  double vn = 0.0, vp = 0.0;
+  for (int k = tid; k < K; k += blockDim.x) {
+    vn += (double)state[(size_t)k * S];
+    vp += (double)state[(size_t)k * S + 1];
+  }
+  const double sn = block_sum(vn, scratch);
+  const double sp = block_sum(vp, scratch);
+  if (cells) {
+    for (int i = 0; i < l; ++i) {
+      double acc = 0.0;
+      for (int bkt = tid; bkt < m; bkt += blockDim.x) {
+        double c = 0.0;
+        for (int k = 0; k < K; ++k) c += (double)state[(size_t)k * S + 2 + i * m + bkt];
+        c /= (double)K;
+        acc += c * c;
+      }
+      const double r = block_sum(acc, scratch);
+      if (tid == 0) rows[i] = r;
+    }
+  }
+  if (tid == 0) {
+    fda_estimate e;
+    e.mean_sqnorm = sn / (double)K;
+    e.mean_proj = 0.0; e.m2 = 0.0; e.h_linear = 0.0; e.h_sketch = 0.0;
+    e.sync_linear = 0; e.sync_sketch = 0; e.near_tie_linear = 0; e.near_tie_sketch = 0;
+    e.nonfinite = 0; e.reserved = 0;
+    const double band = tie_tol * fmax(e.mean_sqnorm, fabs(theta));
+    if (variants & FDA_VARIANT_LINEAR) {
+      e.mean_proj = sp / (double)K;
+      e.h_linear = e.mean_sqnorm - e.mean_proj * e.mean_proj;
+      if (isfinite(e.h_linear)) {
+        e.sync_linear = e.h_linear > theta ? 1 : 0;
+        e.near_tie_linear = fabs(e.h_linear - theta) <= band ? 1 : 0;
+      } else {
+        e.sync_linear = 1; e.nonfinite = 1;
+      }
+    }
+    if (cells) {
+      // median of l values: insertion sort, then middle (even l: mean of the two middle)
+      double r[FDA_MAX_SKETCH_ROWS];
+      for (int i = 0; i < l; ++i) {
+        double v = rows[i];
+        int q = i;
+        while (q > 0 && !(r[q - 1] <= v)) { r[q] = r[q - 1]; --q; }
+        r[q] = v;
+      }
+      e.m2 = (l & 1) ? r[l / 2] : 0.5 * (r[l / 2 - 1] + r[l / 2]);
+      e.h_sketch = e.mean_sqnorm - e.m2 / (1.0 + eps);
+      if (isfinite(e.h_sketch)) {
+        e.sync_sketch = e.h_sketch > theta ? 1 : 0;
+        e.near_tie_sketch = fabs(e.h_sketch - theta) <= band ? 1 : 0;
+      } else {
+        e.sync_sketch = 1; e.nonfinite = 1;
+      }
+    }
+    *out = e;
+  }
+}
+
+// ----------------------------------------------------------------------------------------
+// Algorithm 1 line 9: read the K rows once, average in fp32 in worker order, write the
+// average to every row, to w_t0, and the old w_t0 to w_prev.
+// ----------------------------------------------------------------------------------------
+template <typename T>
+__global__ void __launch_bounds__(kSmallThreads)
+sync_kernel(T* __restrict__ w, float* __restrict__ w_t0, float* __restrict__ w_prev,
+            const int32_t* __restrict__ pred, int K, long long d, long long row_stride, int vec_ok) {
+  constexpr int V = Slab<T>::V;
+  if (pred != nullptr && *pred == 0) return;
+  const float kf = (float)K;
+  const long long nvec = (d + V - 1) / V;
+  for (long long vi = (long long)blockIdx.x * blockDim.x + threadIdx.x; vi < nvec;
+       vi += (long long)gridDim.x * blockDim.x) {
+    const long long j0 = vi * V;
+    float acc[V];
+#pragma unroll
+    for (int v = 0; v < V; ++v) acc[v] = 0.0f;
+    if (vec_ok && j0 + V <= d) {
+#pragma unroll 4
+      for (int k = 0; k < K; ++k) {
+        float x[V];
+        Slab<T>::load_vec(w + (long long)k * row_stride + j0, x);
+#pragma unroll
+        for (int v = 0; v < V; ++v) acc[v] += x[v];
+      }
+#pragma unroll
+      for (int v = 0; v < V; ++v) acc[v] = acc[v] / kf;
+      if (w_prev != nullptr) {
+        float old[V];
+        load_f32_vec<V>(w_t0 + j0, old);
+        store_f32_vec<V>(w_prev + j0, old);
+      }
+      store_f32_vec<V>(w_t0 + j0, acc);
+#pragma unroll 4
+      for (int k = 0; k < K; ++k) Slab<T>::store_vec(w + (long long)k * row_stride + j0, acc);
+    } else {
+      for (int v = 0; v < V; ++v) {
+        const long long j = j0 + v;
+        if (j >= d) break;
+        float a = 0.0f;
+        for (int k = 0; k < K; ++k) a += Slab<T>::load_one(w + (long long)k * row_stride + j);
+        a = a / kf;
+        if (w_prev != nullptr) w_prev[j] = w_t0[j];
+        w_t0[j] = a;
+        for (int k = 0; k < K; ++k) Slab<T>::store_one(w + (long long)k * row_stride + j, a);
+      }
+    }
+  }
+}
+
+// ----------------------------------------------------------------------------------------
+// Section 3.2: xi = (w_t0 - w_prev) / ||w_t0 - w_prev||.  Pass 1: per-workgroup partial of
+// the squared norm; pass 2: every workgroup re-sums the partials in the same fixed order
+// and scales its share of the difference.
+// ----------------------------------------------------------------------------------------
+__global__ void __launch_bounds__(kSmallThreads)
+xi_norm_kernel(const float* __restrict__ w_t0, const float* __restrict__ w_prev,
+               const int32_t* __restrict__ pred, long long d, double* __restrict__ partial) {
+  __shared__ double scratch[kSmallThreads / 64];
+  if (pred != nullptr && *pred == 0) return;
+  double acc = 0.0;
+  const long long step = (long long)gridDim.x * blockDim.x;
+  long long j = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  while (j < d) {
+    float part = 0.0f;                       // a short fp32 run, then fp64
+#pragma unroll
+    for (int t = 0; t < 8; ++t) {
+      if (j < d) { const float df = w_t0[j] - w_prev[j]; part = fmaf(df, df, part); }
+      j += step;
+    }
+    acc += (double)part;
+  }
+  const double s = block_sum(acc, scratch);
+  if (threadIdx.x == 0) partial[blockIdx.x] = s;
+}
+
+__global__ void __launch_bounds__(kSmallThreads)
+xi_scale_kernel(const float* __restrict__ w_t0, const float* __restrict__ w_prev,
+                float* __restrict__ xi, const int32_t* __restrict__ pred, long long d,
+                const double* __restrict__ partial, int npartial) {
+  __shared__ double scratch[kSmallThreads / 64];
+  __shared__ float scale_sh;
+  if (pred != nullptr && *pred == 0) return;
+  double acc = 0.0;
+  for (int t = threadIdx.x; t < npartial; t += blockDim.x) acc += partial[t];
+  const double tot = block_sum(acc, scratch);
+  if (threadIdx.x == 0) {
+    const double nrm = sqrt(tot);
+    scale_sh = (nrm > 0.0 && isfinite(nrm)) ? (float)(1.0 / nrm) : 0.0f;
+  }
+  __syncthreads();
+  const float scale = scale_sh;
+  for (long long j = (long long)blockIdx.x * blockDim.x + threadIdx.x; j < d;
+       j += (long long)gridDim.x * blockDim.x) {
+    const float df = w_t0[j] - w_prev[j];
+    xi[j] = (scale == 0.0f) ? 0.0f : df * scale;
+  }
+}
+
+}  // namespace fda

@@ -1,0 +1,77 @@
+"""FdaMonitor: owns the device buffers one FDA context needs (workspace, state, result
+struct) as torch tensors and forwards to the C ABI.  No arithmetic happens here."""
+from __future__ import annotations
+
+import ctypes as C
+
+import numpy as np
+import torch
+
+from . import binding as B
+
+_EST_OFFSETS = {"linear": B.FdaEstimate.sync_linear.offset, "sketch": B.FdaEstimate.sync_sketch.offset}
+
+
+class FdaMonitor:
+    def __init__(self, K, d, dtype, variants, l=0, m=0, eps=0.0, hash_coef=None,
+                 row_stride=None, device="cuda:0"):
+        if not torch.cuda.is_available():
+            raise RuntimeError("FdaMonitor needs a HIP device (no CPU fallback exists)")
+        self.device = torch.device(device)
+        torch.cuda.set_device(self.device)
+        self.K, self.d = int(K), int(d)
+        self.dtype = {"f32": B.FDA_F32, "bf16": B.FDA_BF16}.get(dtype, dtype)
+        self.variants = int(variants)
+        self.desc, self._keep = B.make_desc(K, d, self.dtype, variants, l, m, eps, hash_coef, row_stride)
+        nbytes = B.fda_workspace_bytes(self.desc)
+        self.workspace = torch.empty(nbytes, dtype=torch.uint8, device=self.device)
+        self.ctx = B.fda_create(self.desc, self.workspace.data_ptr(), nbytes)
+        self.S = B.fda_state_floats(self.ctx)
+        self.plan = B.fda_get_plan(self.ctx).as_dict()
+        self.state = torch.empty((self.K, self.S), dtype=torch.float32, device=self.device)
+        self.est_dev = torch.zeros(C.sizeof(B.FdaEstimate), dtype=torch.uint8, device=self.device)
+
+    def close(self):
+        if getattr(self, "ctx", None):
+            B.fda_destroy(self.ctx)
+            self.ctx = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    @staticmethod
+    def _stream():
+        return torch.cuda.current_stream().cuda_stream
+
+    def pred_ptr(self, which):
+        """Device address of the sync decision of a variant inside the result struct."""
+        return None if which is None else self.est_dev.data_ptr() + _EST_OFFSETS[which]
+
+    def local_state(self, w, w_t0, xi=None):
+        B.fda_local_state(self.ctx, w.data_ptr(), w_t0.data_ptr(),
+                          None if xi is None else xi.data_ptr(), self.state.data_ptr(), self._stream())
+        return self.state
+
+    def estimate_variance(self, theta, tie_tol=1e-5, want_host=True, state=None):
+        st = self.state if state is None else state
+        return B.fda_estimate_variance(self.ctx, st.data_ptr(), float(theta), float(tie_tol),
+                                       self.est_dev.data_ptr(), want_host, self._stream())
+
+    def sync(self, w, w_t0, w_prev=None, pred=None):
+        B.fda_sync(self.ctx, w.data_ptr(), w_t0.data_ptr(),
+                   None if w_prev is None else w_prev.data_ptr(), self.pred_ptr(pred), self._stream())
+
+    def update_xi(self, w_t0, w_prev, xi, pred=None):
+        B.fda_update_xi(self.ctx, w_t0.data_ptr(), w_prev.data_ptr(), xi.data_ptr(),
+                        self.pred_ptr(pred), self._stream())
+
+    def state_numpy(self):
+        """(n[K], p[K], sk[K,l,m] or None) as float32 host arrays."""
+        s = self.state.cpu().numpy()
+        sk = None
+        if self.variants & B.FDA_VARIANT_SKETCH:
+            sk = s[:, 2:].reshape(self.K, self.desc.l, self.desc.m)
+        return s[:, 0].copy(), s[:, 1].copy(), sk

@@ -1,0 +1,109 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every symbol
+include/fda.h declares, validates arguments and plans launches."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+import fda_synth as S
+import paper_2405_20988_amd as F
+from paper_2405_20988_amd.binding import make_desc
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "fda.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(fda_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = F.load_library()
+    names = declared_functions()
+    assert {"fda_local_state", "fda_estimate_variance", "fda_sync", "fda_update_xi"} <= set(names)
+    for n in names:
+        assert hasattr(lib, n), n
+    # the binding offers the same names
+    for n in names:
+        assert hasattr(F, n), n
+
+
+def test_struct_layouts_match_header():
+    assert C.sizeof(F.FdaEstimate) == 64
+    assert F.FdaEstimate.sync_linear.offset == 40 and F.FdaEstimate.sync_sketch.offset == 44
+    assert C.sizeof(F.FdaDesc) == 56
+    assert C.sizeof(F.FdaPlanInfo) == 48
+
+
+def test_strerror():
+    assert F.fda_strerror(0) == "success"
+    assert "invalid" in F.fda_strerror(-1)
+    assert "unknown" in F.fda_strerror(-99)
+
+
+def _desc(**kw):
+    args = dict(K=5, d=61706, dtype=F.FDA_F32, variants=3, l=5, m=250, eps=0.06,
+                hash_coef=S.hash_coefficients(0, kw.get("l", 5) if kw.get("l", 5) > 0 else 1))
+    args.update(kw)
+    return make_desc(**args)
+
+
+@pytest.mark.parametrize("kw,code", [
+    (dict(K=0), -1), (dict(d=0), -1), (dict(d=2**31 - 1), -2), (dict(dtype=7), -1),
+    (dict(variants=0), -1), (dict(variants=8), -1), (dict(l=0), -1), (dict(l=17), -1),
+    (dict(m=0), -1), (dict(row_stride=100), -1), (dict(eps=-1.0), -1),
+    (dict(hash_coef=None), -1), (dict(l=1, m=60000), -2),
+])
+def test_plan_rejects_bad_descriptions(kw, code):
+    desc, keep = _desc(**kw)
+    with pytest.raises(F.FdaError) as e:
+        F.fda_plan(desc, 256, 163840)
+    assert e.value.code == code
+    assert F.fda_last_error() != ""
+
+
+def test_plan_rejects_large_coefficient():
+    coef = S.hash_coefficients(0, 5)
+    coef[2, 1, 3] = 2**31 - 1
+    desc, keep = _desc(hash_coef=coef)
+    with pytest.raises(F.FdaError) as e:
+        F.fda_plan(desc, 256, 163840)
+    assert e.value.code == -2
+
+
+def test_create_rejects_before_touching_the_device():
+    desc, keep = _desc(K=-3)
+    with pytest.raises(F.FdaError) as e:
+        F.fda_create(desc, 256, 1 << 20)
+    assert e.value.code == -1
+
+
+@pytest.mark.parametrize("name", list(S.CONFIGS))
+def test_plan_of_the_five_configs(name):
+    c = S.CONFIGS[name]
+    dt = F.FDA_F32 if c["dtype"] == "f32" else F.FDA_BF16
+    desc, keep = make_desc(c["K"], c["d"], dt, 3, c["l"], c["m"], 0.06, S.hash_coefficients(0, c["l"]))
+    p = F.fda_plan(desc, 256, 163840)
+    assert p.state_floats == 2 + c["l"] * c["m"]
+    assert p.worker_groups * p.workers_per_group >= c["K"]
+    assert p.workers_per_group <= 16
+    assert p.partitions % 8 == 0 and p.partitions >= 8
+    assert p.lds_bytes <= 163840
+    assert p.partitions * p.chunk >= c["d"]
+    tile = p.threads * (4 if dt == F.FDA_F32 else 8)
+    assert p.chunk % tile == 0
+    # the partial buffers fit in the workspace
+    need = p.partitions * c["K"] * (16 + 4 * c["l"] * c["m"])
+    assert p.workspace_bytes >= need
+    # sketch bytes the paper quotes for 5 x 250: l * m * 4 = 5 kB (Section 3.3)
+    if (c["l"], c["m"]) == (5, 250):
+        assert (p.state_floats - 2) * 4 == 5000
+
+
+def test_plan_linear_only_needs_no_sketch():
+    desc, keep = make_desc(60, 10**6, F.FDA_F32, F.FDA_VARIANT_LINEAR)
+    p = F.fda_plan(desc, 256, 163840)
+    assert p.state_floats == 2 and p.worker_groups == 4
