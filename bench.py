@@ -1,0 +1,186 @@
+#!/usr/bin/env python3
+"""Benchmark of the FDA local-state + variance-check path on one MI355X.
+
+A step is one pass of Algorithm 1 lines 6-9 over a synthetic [K, d] slab that is already
+resident in HBM: fda_local_state, fda_estimate_variance, then fda_sync and fda_update_xi
+predicated on the device-side decision (no host round trip inside a step).  The threshold
+is set above the estimate, so in the timed steps the decision is "no synchronization" --
+the case the method is built for -- and the metric is the cost of the state + check.  The
+forced synchronization (fused mean + broadcast, then xi) is timed separately and reported
+in the "sync" object.
+
+Prints ONE JSON line.  `roofline` describes the streaming state kernel, timed live with HIP
+events inside the library (fda_profile_*); `cpu_baseline` is the CPU oracle timed on a
+bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published peak
+
+
+def algorithmic_bytes(K, d, elem_bytes, variants):
+    """Bytes one state pass must move: the slab once, w_t0 once, xi once if LinearFDA runs."""
+    return K * d * elem_bytes + 4 * d + (4 * d if variants & 1 else 0)
+
+
+def traffic_from_profile(workload):
+    """HBM bytes per state-kernel launch measured with rocprofv3 --pmc (FETCH_SIZE and
+    WRITE_SIZE runs, scaled by a copy kernel), if a summary for this workload is committed."""
+    path = os.path.join(ROOT, "profiles", f"state_kernel_{workload}_traffic.txt")
+    try:
+        for line in open(path):
+            if line.startswith("traffic_bytes_per_launch="):
+                return float(line.split("=", 1)[1])
+    except OSError:
+        pass
+    return None
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", default="cfg5", help="cfg1..cfg5 (default: the largest, cfg5)")
+    ap.add_argument("--variants", type=int, default=3, help="1 linear, 2 sketch, 3 both")
+    ap.add_argument("--d", type=int, default=None, help="override d (for quick checks)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample", type=int, default=2_000_000,
+                    help="coordinates of the workload the CPU oracle is timed on")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (K workers are simulated as a [K,d] slab on one "
+              "device; there are no collectives). Run with --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import fda_synth as S
+    import paper_2405_20988_amd as F
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
+        sys.exit(2)
+    F.load_library()
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+
+    wl = S.make(args.config, device=dev, seed=0, d=args.d)
+    K, d = wl.K, wl.d
+    esz = 4 if wl.dtype == "f32" else 2
+    mon = F.FdaMonitor(K, d, wl.dtype, args.variants, wl.l, wl.m, wl.eps, wl.hash_coef, device=dev)
+    w_prev = wl.w_t0.clone()
+    xi = wl.xi if args.variants & 1 else None
+    pred = "sketch" if args.variants & 2 else "linear"
+
+    # threshold above the current estimate: timed steps take the no-synchronization branch
+    mon.local_state(wl.w, wl.w_t0, xi)
+    est0 = mon.estimate_variance(0.0)
+    h0 = est0.h_sketch if args.variants & 2 else est0.h_linear
+    theta = 4.0 * max(h0, est0.mean_sqnorm)
+
+    def step():
+        mon.local_state(wl.w, wl.w_t0, xi)
+        mon.estimate_variance(theta, want_host=False)
+        mon.sync(wl.w, wl.w_t0, w_prev, pred=pred)
+        if args.variants & 1:
+            mon.update_xi(wl.w_t0, w_prev, wl.xi, pred=pred)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    F.fda_profile_enable(mon.ctx, True)
+    F.fda_profile_read(mon.ctx, reset=True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    kernel_ms, launches = F.fda_profile_read(mon.ctx, reset=True)
+    F.fda_profile_enable(mon.ctx, False)
+    est = mon.estimate_variance(theta)
+    assert (est.sync_sketch if args.variants & 2 else est.sync_linear) == 0
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    value = K * d / (ms_per_step * 1e-3)
+
+    abytes = algorithmic_bytes(K, d, esz, args.variants)
+    kern_ms_avg = kernel_ms / max(launches, 1)
+    achieved = abytes / (kern_ms_avg * 1e-3) / 1e9
+    workload = args.config if args.d is None else f"{args.config}-d{d}"
+    roofline = {"bound": "hbm", "kernel": "state_kernel", "achieved": round(achieved, 1),
+                "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
+                "traffic": traffic_from_profile(workload), "algorithmic_bytes": abytes,
+                "kernel_ms": round(kern_ms_avg, 4), "launches": launches}
+
+    # forced synchronization + xi refresh, timed separately (it rewrites the slab, so last)
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    reps = 3
+    mon.sync(wl.w, wl.w_t0, w_prev, pred=None)
+    torch.cuda.synchronize()
+    ev0.record()
+    for _ in range(reps):
+        mon.sync(wl.w, wl.w_t0, w_prev, pred=None)
+    ev1.record()
+    torch.cuda.synchronize()
+    sync_ms = ev0.elapsed_time(ev1) / reps
+    sync_bytes = 2 * K * d * esz + 4 * d * (3 if w_prev is not None else 1)
+    ev0.record()
+    for _ in range(reps):
+        mon.update_xi(wl.w_t0, w_prev, wl.xi, pred=None)
+    ev1.record()
+    torch.cuda.synchronize()
+    xi_ms = ev0.elapsed_time(ev1) / reps
+    sync_info = {"sync_ms": round(sync_ms, 4), "sync_GBps": round(sync_bytes / sync_ms / 1e6, 1),
+                 "sync_algorithmic_bytes": sync_bytes, "update_xi_ms": round(xi_ms, 4),
+                 "update_xi_GBps": round(20 * d / xi_ms / 1e6, 1)}
+
+    out = {
+        "metric": "worker-params/s (K*d per step) for local-state+variance check",
+        "value": value, "unit": "worker-params/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32" if wl.dtype == "f32" else "bf16-storage/f32-arithmetic",
+        "data": "synthetic",
+        "config": {"workload": workload, "K": K, "d": d, "slab_dtype": wl.dtype,
+                   "sketch": f"{wl.l}x{wl.m}", "variants": args.variants,
+                   "slab_bytes": K * d * esz, "plan": mon.plan,
+                   "step": "fda_local_state + fda_estimate_variance + predicated fda_sync/fda_update_xi "
+                           "(decision: no sync)"},
+        "roofline": roofline,
+        "sync": sync_info,
+    }
+
+    if not args.no_cpu_baseline:
+        from oracle import fda_oracle as O
+        ds = min(args.cpu_sample, d)
+        # regenerate a small slab of the same recipe on the CPU for the sample (same distributions)
+        wls = S.make(args.config, device="cpu", seed=0, d=ds)
+        w_host = S.slab_to_numpy(wls.w)
+        w0_host, xi_host = wls.w_t0.numpy(), wls.xi.numpy()
+        c0 = time.perf_counter()
+        st = O.local_state(w_host, wls.dtype, w0_host, xi_host if args.variants & 1 else None,
+                           wls.hash_coef if args.variants & 2 else None, wls.m)
+        O.estimate_variance(st["n"], st["p"], st["sk"], wls.eps, theta)
+        c1 = time.perf_counter()
+        out["cpu_baseline"] = {"value": K * ds / (c1 - c0), "unit": "worker-params/s", "cores": 1,
+                               "kind": "oracle",
+                               "sample": f"first-principles fp64 numpy oracle (state + estimate) on a "
+                                         f"{K} x {ds} slab of the same recipe, {c1 - c0:.1f} s"}
+    print(json.dumps(out))
+    mon.close()
+
+
+if __name__ == "__main__":
+    main()

@@ -185,6 +185,16 @@ int fda_sync(fda_ctx* ctx, void* w, float* w_t0, float* w_prev, const int32_t* p
 int fda_update_xi(fda_ctx* ctx, const float* w_t0, const float* w_prev, float* xi,
                   const int32_t* pred_dev, void* stream);
 
+/*
+ * Measurement aid (no part of the method): when enabled, fda_local_state brackets its
+ * streaming state kernel -- the pass over the slab, Algorithm 1 line 6 -- with HIP events
+ * on the caller's stream.  fda_profile_read waits for the recorded events and returns the
+ * accumulated kernel time in milliseconds and the number of launches it covers since the
+ * last reset.  Events are created on first enable and destroyed with the context.
+ */
+int fda_profile_enable(fda_ctx* ctx, int on);
+int fda_profile_read(fda_ctx* ctx, double* state_kernel_ms, int64_t* launches, int reset);
+
 #ifdef __cplusplus
 }
 #endif

@@ -84,7 +84,9 @@ def load_library():
                                           C.POINTER(FdaEstimate), vp]
     lib.fda_sync.argtypes = [vp, vp, vp, vp, i32p, vp]
     lib.fda_update_xi.argtypes = [vp, vp, vp, vp, i32p, vp]
-    for name in ("fda_plan", "fda_workspace_bytes", "fda_create", "fda_destroy",
+    lib.fda_profile_enable.argtypes = [vp, C.c_int]
+    lib.fda_profile_read.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(C.c_int64), C.c_int]
+    for name in ("fda_profile_enable", "fda_profile_read", "fda_plan", "fda_workspace_bytes", "fda_create", "fda_destroy",
                  "fda_state_floats", "fda_get_plan", "fda_local_state",
                  "fda_estimate_variance", "fda_sync", "fda_update_xi"):
         getattr(lib, name).restype = C.c_int
@@ -176,3 +178,15 @@ def fda_sync(ctx: int, w: int, w_t0: int, w_prev: int | None, pred_dev: int | No
 def fda_update_xi(ctx: int, w_t0: int, w_prev: int, xi: int, pred_dev: int | None = None,
                   stream: int = 0) -> None:
     _check(load_library().fda_update_xi(ctx, w_t0, w_prev, xi, pred_dev, stream), "fda_update_xi")
+
+
+def fda_profile_enable(ctx: int, on: bool) -> None:
+    _check(load_library().fda_profile_enable(ctx, 1 if on else 0), "fda_profile_enable")
+
+
+def fda_profile_read(ctx: int, reset: bool = True):
+    """(total state-kernel milliseconds, launches) since the last reset."""
+    ms, n = C.c_double(0.0), C.c_int64(0)
+    _check(load_library().fda_profile_read(ctx, C.byref(ms), C.byref(n), 1 if reset else 0),
+           "fda_profile_read")
+    return float(ms.value), int(n.value)

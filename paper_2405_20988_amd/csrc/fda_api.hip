@@ -130,18 +130,22 @@ int device_shape(int* cus, int64_t* lds) {
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
 
+// prm == nullptr: only raise the kernel's dynamic-LDS limit (done once, at fda_create).
 template <typename T, int KC>
-int launch_state(const fda::StateParams& prm, const fda::HashCoef& hc, size_t lds, hipStream_t st) {
+int launch_state(const fda::StateParams* prm, const fda::HashCoef& hc, size_t lds, hipStream_t st) {
   auto kern = fda::state_kernel<T, KC>;
-  FDA_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-  hipLaunchKernelGGL(kern, dim3(prm.G * prm.P), dim3(fda::kStateThreads), lds, st, prm, hc);
+  if (prm == nullptr) {
+    FDA_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    return FDA_OK;
+  }
+  hipLaunchKernelGGL(kern, dim3(prm->G * prm->P), dim3(fda::kStateThreads), lds, st, *prm, hc);
   FDA_HIP(hipGetLastError());
   return FDA_OK;
 }
 
 template <typename T>
-int dispatch_state(int KC, const fda::StateParams& prm, const fda::HashCoef& hc, size_t lds,
+int dispatch_state(int KC, const fda::StateParams* prm, const fda::HashCoef& hc, size_t lds,
                    hipStream_t st) {
   switch (KC) {
     case 1: return launch_state<T, 1>(prm, hc, lds, st);
@@ -153,6 +157,8 @@ int dispatch_state(int KC, const fda::StateParams& prm, const fda::HashCoef& hc,
   return fail(FDA_EINVAL, "internal: no kernel for %d workers per group", KC);
 }
 
+constexpr int kProfSlots = 64;
+
 }  // namespace
 
 struct fda_ctx {
@@ -162,7 +168,29 @@ struct fda_ctx {
   unsigned char* ws;
   int device;
   int cus;
+  // optional timing of the state kernel (fda_profile_enable)
+  bool prof_on = false;
+  hipEvent_t prof_start[kProfSlots] = {};
+  hipEvent_t prof_stop[kProfSlots] = {};
+  int prof_pending = 0;       // recorded pairs not yet read
+  double prof_ms = 0.0;
+  int64_t prof_launches = 0;
 };
+
+namespace {
+// Fold the recorded event pairs into the running totals (waits for them).
+int prof_drain(fda_ctx* c) {
+  for (int t = 0; t < c->prof_pending; ++t) {
+    FDA_HIP(hipEventSynchronize(c->prof_stop[t]));
+    float ms = 0.0f;
+    FDA_HIP(hipEventElapsedTime(&ms, c->prof_start[t], c->prof_stop[t]));
+    c->prof_ms += ms;
+    c->prof_launches += 1;
+  }
+  c->prof_pending = 0;
+  return FDA_OK;
+}
+}  // namespace
 
 extern "C" {
 
@@ -237,12 +265,51 @@ int fda_create(fda_ctx** ctx, const fda_desc* desc, void* workspace, size_t work
     delete c;
     return fail(FDA_EHIP, "hipGetDevice failed");
   }
+  rc = desc->dtype == FDA_F32
+           ? dispatch_state<float>(pl.KC, nullptr, c->coef, (size_t)pl.lds_bytes, nullptr)
+           : dispatch_state<fda::bf16_t>(pl.KC, nullptr, c->coef, (size_t)pl.lds_bytes, nullptr);
+  if (rc != FDA_OK) {
+    delete c;
+    return rc;
+  }
   *ctx = c;
   return FDA_OK;
 }
 
 int fda_destroy(fda_ctx* ctx) {
+  if (ctx == nullptr) return FDA_OK;
+  for (int t = 0; t < kProfSlots; ++t) {
+    if (ctx->prof_start[t]) (void)hipEventDestroy(ctx->prof_start[t]);
+    if (ctx->prof_stop[t]) (void)hipEventDestroy(ctx->prof_stop[t]);
+  }
   delete ctx;
+  return FDA_OK;
+}
+
+int fda_profile_enable(fda_ctx* ctx, int on) {
+  if (ctx == nullptr) return fail(FDA_EINVAL, "ctx is NULL");
+  if (on && ctx->prof_start[0] == nullptr) {
+    for (int t = 0; t < kProfSlots; ++t) {
+      FDA_HIP(hipEventCreate(&ctx->prof_start[t]));
+      FDA_HIP(hipEventCreate(&ctx->prof_stop[t]));
+    }
+  }
+  if (!on) {
+    int rc = prof_drain(ctx);
+    if (rc != FDA_OK) return rc;
+  }
+  ctx->prof_on = on != 0;
+  return FDA_OK;
+}
+
+int fda_profile_read(fda_ctx* ctx, double* state_kernel_ms, int64_t* launches, int reset) {
+  if (ctx == nullptr || state_kernel_ms == nullptr || launches == nullptr)
+    return fail(FDA_EINVAL, "NULL argument");
+  int rc = prof_drain(ctx);
+  if (rc != FDA_OK) return rc;
+  *state_kernel_ms = ctx->prof_ms;
+  *launches = ctx->prof_launches;
+  if (reset) { ctx->prof_ms = 0.0; ctx->prof_launches = 0; }
   return FDA_OK;
 }
 
@@ -284,10 +351,23 @@ int fda_local_state(fda_ctx* ctx, const void* w, const float* w_t0, const float*
   prm.part_np = reinterpret_cast<double*>(ctx->ws + pl.off_np);
   prm.part_sk = reinterpret_cast<float*>(ctx->ws + pl.off_sk);
 
+  int slot = -1;
+  if (ctx->prof_on) {
+    if (ctx->prof_pending == kProfSlots) {
+      int rc0 = prof_drain(ctx);
+      if (rc0 != FDA_OK) return rc0;
+    }
+    slot = ctx->prof_pending;
+    FDA_HIP(hipEventRecord(ctx->prof_start[slot], st));
+  }
   int rc = d.dtype == FDA_F32
-               ? dispatch_state<float>(pl.KC, prm, ctx->coef, (size_t)pl.lds_bytes, st)
-               : dispatch_state<fda::bf16_t>(pl.KC, prm, ctx->coef, (size_t)pl.lds_bytes, st);
+               ? dispatch_state<float>(pl.KC, &prm, ctx->coef, (size_t)pl.lds_bytes, st)
+               : dispatch_state<fda::bf16_t>(pl.KC, &prm, ctx->coef, (size_t)pl.lds_bytes, st);
   if (rc != FDA_OK) return rc;
+  if (slot >= 0) {
+    FDA_HIP(hipEventRecord(ctx->prof_stop[slot], st));
+    ctx->prof_pending = slot + 1;
+  }
 
   const long long total = (long long)d.K * pl.S;
   const int blocks = (int)((total + fda::kSmallThreads - 1) / fda::kSmallThreads);
