@@ -104,6 +104,8 @@ typedef struct fda_estimate {
 typedef struct fda_plan_info {
   int32_t worker_groups;    /* the K workers are split into this many groups of workgroups  */
   int32_t workers_per_group;/* largest group                                                */
+  int32_t row_groups;       /* the l sketch rows are split into this many groups            */
+  int32_t rows_per_group;   /* largest group                                                */
   int32_t partitions;       /* coordinate partitions (workgroups per worker group)          */
   int32_t threads;          /* threads per workgroup                                        */
   int64_t chunk;            /* coordinates per partition                                    */

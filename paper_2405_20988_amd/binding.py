@@ -46,6 +46,7 @@ class FdaEstimate(C.Structure):
 
 class FdaPlanInfo(C.Structure):
     _fields_ = [("worker_groups", C.c_int32), ("workers_per_group", C.c_int32),
+                ("row_groups", C.c_int32), ("rows_per_group", C.c_int32),
                 ("partitions", C.c_int32), ("threads", C.c_int32), ("chunk", C.c_int64),
                 ("lds_bytes", C.c_int64), ("workspace_bytes", C.c_int64),
                 ("state_floats", C.c_int64)]

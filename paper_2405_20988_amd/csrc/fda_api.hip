@@ -29,14 +29,17 @@ int fail(int code, const char* fmt, ...) {
       return fail(FDA_EHIP, "%s failed: %s", #call, hipGetErrorString(e_));            \
   } while (0)
 
-constexpr int64_t kLdsReserve = 4096;      // reduction scratch + slack behind the sketch
+constexpr int64_t kLdsReserve = 2560;      // reduction scratch (8 waves x 16 workers x 2 doubles) + slack
+constexpr int kOversubscribe = 4;          // workgroups launched per resident workgroup slot
+constexpr double kHashOpsPerRow = 60.0;    // rough vector-ALU cost of hashing one coordinate for one row
+constexpr double kLoadOpsPerElement = 4.0; // rough cost of loading / widening / differencing one element
 constexpr int kXiBlocks = 1024;
 constexpr int64_t kAlign = 256;
 
 int64_t round_up(int64_t x, int64_t a) { return (x + a - 1) / a * a; }
 
 struct Plan {
-  int G, kcnt_max, KC, P, stride, vec;      // vec = elements per 16-byte slab load
+  int G, R, kcnt_max, rcnt_max, KC, P, stride, vec;   // vec = elements per 16-byte slab load
   int64_t chunk, lds_bytes, cells, S;
   int64_t off_np, off_sk, off_xi, ws_bytes;
 };
@@ -72,28 +75,45 @@ int make_plan(const fda_desc* d, int cus, int64_t lds_cu, Plan* pl) {
   pl->cells = sk ? (int64_t)d->l * d->m : 0;
   pl->S = 2 + pl->cells;
   pl->vec = d->dtype == FDA_F32 ? 4 : 8;
-  // fewest worker groups whose sketch (workers padded to an odd stride) fits in LDS
-  int G = 0;
-  for (int g = 1; g <= d->K; ++g) {
-    const int kc = (d->K + g - 1) / g;
+  // Split the K workers into G groups and the l sketch rows into R groups so that one
+  // workgroup's fp64 sketch (rows x m cells x workers) fits in LDS.  More worker groups repeat
+  // the hash evaluation, more row groups re-read the slab rows through L2; pick the split
+  // with the least estimated vector-ALU work per coordinate.
+  const int l = sk ? d->l : 1;
+  double best = -1.0;
+  int bestG = 0, bestR = 0;
+  for (int G = 1; G <= d->K; ++G) {
+    const int kc = (d->K + G - 1) / G;
     if (kc > fda::kMaxKC) continue;
-    const int stride = kc | 1;
-    if (pl->cells * stride * 4 + kLdsReserve <= lds_cu) { G = g; break; }
+    const int stride = (kc == 1) ? 1 : (kc | 1);
+    for (int R = 1; R <= l; ++R) {
+      const int rc = (l + R - 1) / R;
+      if (pl->cells && (int64_t)rc * d->m * stride * 8 + kLdsReserve > lds_cu) continue;
+      const double cost = (double)G * l * kHashOpsPerRow + (double)R * d->K * kLoadOpsPerElement +
+                          1e-3 * G * R;
+      if (best < 0.0 || cost < best) { best = cost; bestG = G; bestR = R; }
+      break;   // a larger R only costs more for this G
+    }
   }
-  if (G == 0) return fail(FDA_ERANGE, "an l*m = %lld sketch does not fit in %lld bytes of LDS",
-                          (long long)pl->cells, (long long)lds_cu);
-  pl->G = G;
-  pl->kcnt_max = (d->K + G - 1) / G;
-  pl->stride = pl->kcnt_max | 1;
+  if (bestG == 0)
+    return fail(FDA_ERANGE, "one row of an m = %d sketch does not fit in %lld bytes of LDS", d->m,
+                (long long)lds_cu);
+  pl->G = bestG;
+  pl->R = bestR;
+  pl->kcnt_max = (d->K + bestG - 1) / bestG;
+  pl->rcnt_max = (l + bestR - 1) / bestR;
+  pl->stride = (pl->kcnt_max == 1) ? 1 : (pl->kcnt_max | 1);
   int KC = 1;
   while (KC < pl->kcnt_max) KC *= 2;
   pl->KC = KC;
-  pl->lds_bytes = round_up(pl->cells * pl->stride * 4, 16) + kLdsReserve;
+  const int64_t sk_bytes = pl->cells ? (int64_t)pl->rcnt_max * d->m * pl->stride * 8 : 0;
+  pl->lds_bytes = round_up(sk_bytes, 16) + kLdsReserve;
   int occ = (int)(lds_cu / pl->lds_bytes);
   if (occ > 2) occ = 2;
   if (occ < 1) occ = 1;
   const int64_t tile = (int64_t)fda::kStateThreads * pl->vec;
-  int64_t P = (int64_t)cus * occ / G / 8 * 8;
+  // a few workgroups per CU slot, so that the last wave of workgroups costs little
+  int64_t P = round_up(((int64_t)cus * occ * kOversubscribe + bestG * bestR - 1) / (bestG * bestR), 8);
   if (P < 8) P = 8;
   const int64_t tiles = (d->d + tile - 1) / tile;
   if (P > round_up(tiles, 8)) P = round_up(tiles, 8);
@@ -101,13 +121,15 @@ int make_plan(const fda_desc* d, int cus, int64_t lds_cu, Plan* pl) {
   pl->chunk = round_up((d->d + P - 1) / P, tile);
   pl->off_np = 0;
   pl->off_sk = round_up(pl->off_np + P * d->K * 2 * 8, kAlign);
-  pl->off_xi = round_up(pl->off_sk + P * d->K * pl->cells * 4, kAlign);
+  pl->off_xi = round_up(pl->off_sk + P * d->K * pl->cells * 8, kAlign);
   pl->ws_bytes = round_up(pl->off_xi + kXiBlocks * 8, kAlign);
   return FDA_OK;
 }
 
 void export_plan(const Plan& pl, fda_plan_info* out) {
   out->worker_groups = pl.G;
+  out->row_groups = pl.R;
+  out->rows_per_group = pl.rcnt_max;
   out->workers_per_group = pl.kcnt_max;
   out->partitions = pl.P;
   out->threads = fda::kStateThreads;
@@ -139,7 +161,7 @@ int launch_state(const fda::StateParams* prm, const fda::HashCoef& hc, size_t ld
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
     return FDA_OK;
   }
-  hipLaunchKernelGGL(kern, dim3(prm->G * prm->P), dim3(fda::kStateThreads), lds, st, *prm, hc);
+  hipLaunchKernelGGL(kern, dim3(prm->G * prm->R * prm->P), dim3(fda::kStateThreads), lds, st, *prm, hc);
   FDA_HIP(hipGetLastError());
   return FDA_OK;
 }
@@ -344,12 +366,12 @@ int fda_local_state(fda_ctx* ctx, const void* w, const float* w_t0, const float*
   prm.w = w; prm.w_t0 = w_t0; prm.xi = xi;
   prm.row_stride = d.row_stride; prm.d = d.d; prm.chunk = pl.chunk;
   prm.K = d.K; prm.l = sk ? d.l : 0; prm.m = sk ? d.m : 0;
-  prm.G = pl.G; prm.P = pl.P; prm.stride = pl.stride;
+  prm.G = pl.G; prm.R = pl.R; prm.P = pl.P; prm.stride = pl.stride;
   prm.do_lin = lin; prm.do_sk = sk;
   prm.vec_ok = aligned16(w) && aligned16(w_t0) && (!lin || aligned16(xi)) &&
                (d.row_stride * esz) % 16 == 0;
   prm.part_np = reinterpret_cast<double*>(ctx->ws + pl.off_np);
-  prm.part_sk = reinterpret_cast<float*>(ctx->ws + pl.off_sk);
+  prm.part_sk = reinterpret_cast<double*>(ctx->ws + pl.off_sk);
 
   int slot = -1;
   if (ctx->prof_on) {

@@ -36,13 +36,14 @@ struct StateParams {
   int l;
   int m;
   int G;                  // worker groups
+  int R;                  // sketch-row groups (workgroups of one worker group share the data)
   int P;                  // coordinate partitions, multiple of 8
-  int stride;             // LDS floats per sketch cell (odd, >= workers of the group)
+  int stride;             // LDS doubles per sketch cell (>= workers of the group)
   int do_lin;
   int do_sk;
   int vec_ok;             // all pointers / strides allow 16-byte loads
   double* part_np;        // [P][K][2]
-  float* part_sk;         // [P][K][l*m]
+  double* part_sk;        // [P][K][l*m]
 };
 
 struct bf16_t { uint16_t bits; };
@@ -155,37 +156,46 @@ __device__ __host__ inline void group_range(int K, int G, int g, int* start, int
 }
 
 // ----------------------------------------------------------------------------------------
-// Algorithm 1 line 6.  Workgroup (p, g) streams coordinates [p*chunk, (p+1)*chunk) of the
-// workers of group g exactly once.  Per tile every lane owns V consecutive coordinates:
-// it loads w_t0 (and xi) once, then the V elements of each of its <= KC workers, forms the
-// drifts in registers, accumulates ||u||^2 and <xi,u> (fp32 within the tile, fp64 across
-// tiles) and adds sign*u into the workgroup's private LDS sketch, laid out
-// [row][bucket][worker] with an odd worker stride so that random buckets spread over all
-// LDS banks.  The hash of a coordinate is evaluated once and reused by all workers.
+// Algorithm 1 line 6.  Workgroup (p, g, r) streams coordinates [p*chunk, (p+1)*chunk) of the
+// workers of group g exactly once and owns the sketch rows of row group r.  Per tile every
+// lane owns V consecutive coordinates: it loads w_t0 (and xi) once, then the V elements of
+// each of its <= KC workers, forms the drifts in registers, accumulates ||u||^2 and <xi,u>
+// (fp32 within the tile, fp64 across tiles; row group 0 only) and adds sign*u into the
+// workgroup's private LDS sketch.  The hash of a coordinate is evaluated once and reused by
+// all workers of the group.
+//
+// The LDS sketch is fp64, [row][bucket][worker]: on gfx950 the LDS executes a
+// double-precision atomic add (ds_add_f64) roughly nine times faster than a
+// single-precision one, and fp64 cells make the accumulation order immaterial to the fp32
+// result in all but a vanishing fraction of cells.
 // ----------------------------------------------------------------------------------------
 template <typename T, int KC>
 __global__ void __launch_bounds__(kStateThreads)
 state_kernel(const StateParams prm, const HashCoef hc) {
   constexpr int V = Slab<T>::V;
   extern __shared__ __align__(16) unsigned char lds_raw[];
-  const int cells = prm.do_sk ? prm.l * prm.m : 0;
-  float* sk = reinterpret_cast<float*>(lds_raw);
-  // reduction scratch sits behind the sketch, 8-byte aligned
-  const size_t sk_bytes = ((size_t)cells * prm.stride * sizeof(float) + 15) & ~(size_t)15;
-  double* red = reinterpret_cast<double*>(lds_raw + sk_bytes);     // [waves][KC][2]
 
   // XCD-aware placement: consecutive workgroup ids go round-robin over the 8 XCDs, so the
-  // G groups that read the same coordinates (and share w_t0 / xi) are given ids that land
-  // on one XCD and its L2.
+  // G*R workgroups that read the same coordinates (and share w_t0 / xi / slab rows) get ids
+  // that land on one XCD and its L2.
   const int b = blockIdx.x;
   const int xcd = b & 7, slot = b >> 3;
-  const int g = slot % prm.G;
-  const int p = (slot / prm.G) * 8 + xcd;
-  int kstart, kcnt;
+  const int GR = prm.G * prm.R;
+  const int gr = slot % GR;
+  const int p = (slot / GR) * 8 + xcd;
+  const int g = gr / prm.R, r = gr - g * prm.R;
+  int kstart, kcnt, rstart = 0, rcnt = 0;
   group_range(prm.K, prm.G, g, &kstart, &kcnt);
+  if (prm.do_sk) group_range(prm.l, prm.R, r, &rstart, &rcnt);
+  const bool scalars = (r == 0);
+
+  const int cells = rcnt * prm.m;                      // cells this workgroup owns
+  double* sk = reinterpret_cast<double*>(lds_raw);
+  const size_t sk_bytes = ((size_t)cells * prm.stride * sizeof(double) + 15) & ~(size_t)15;
+  double* red = reinterpret_cast<double*>(lds_raw + sk_bytes);     // [waves][KC][2]
 
   const int tid = threadIdx.x;
-  for (int t = tid; t < cells * prm.stride; t += kStateThreads) sk[t] = 0.0f;
+  for (int t = tid; t < cells * prm.stride; t += kStateThreads) sk[t] = 0.0;
   __syncthreads();
 
   double dn[KC], dp[KC];
@@ -196,13 +206,14 @@ state_kernel(const StateParams prm, const HashCoef hc) {
   const long long cbeg = (long long)p * prm.chunk;
   long long cend = cbeg + prm.chunk;
   if (cend > prm.d) cend = prm.d;
+  const bool lin = prm.do_lin && scalars;
 
   for (long long j0 = cbeg + (long long)tid * V; j0 < cend; j0 += (long long)kStateThreads * V) {
     float w0[V], x[V], u[KC][V];
     const bool full = prm.vec_ok && (j0 + V <= prm.d);
     if (full) {
       load_f32_vec<V>(prm.w_t0 + j0, w0);
-      if (prm.do_lin) load_f32_vec<V>(prm.xi + j0, x);
+      if (lin) load_f32_vec<V>(prm.xi + j0, x);
 #pragma unroll
       for (int k = 0; k < KC; ++k)
         if (k < kcnt) Slab<T>::load_vec(wbase + (long long)k * prm.row_stride + j0, u[k]);
@@ -211,14 +222,14 @@ state_kernel(const StateParams prm, const HashCoef hc) {
       for (int v = 0; v < V; ++v) {
         const bool in = (j0 + v < prm.d);
         w0[v] = in ? prm.w_t0[j0 + v] : 0.0f;
-        if (prm.do_lin) x[v] = in ? prm.xi[j0 + v] : 0.0f;
+        if (lin) x[v] = in ? prm.xi[j0 + v] : 0.0f;
 #pragma unroll
         for (int k = 0; k < KC; ++k)
           if (k < kcnt)
             u[k][v] = in ? Slab<T>::load_one(wbase + (long long)k * prm.row_stride + j0 + v) : 0.0f;
       }
     }
-    if (!prm.do_lin) {
+    if (!lin) {
 #pragma unroll
       for (int v = 0; v < V; ++v) x[v] = 0.0f;
     }
@@ -232,26 +243,30 @@ state_kernel(const StateParams prm, const HashCoef hc) {
           sn = fmaf(u[k][v], u[k][v], sn);
           sp = fmaf(x[v], u[k][v], sp);
         }
-        dn[k] += (double)sn;
-        dp[k] += (double)sp;
+        if (scalars) {
+          dn[k] += (double)sn;
+          dp[k] += (double)sp;
+        }
       }
     }
-    if (prm.do_sk) {
-      for (int i = 0; i < prm.l; ++i) {
-        const int rowoff = i * prm.m;
+    for (int i = 0; i < rcnt; ++i) {
+      const uint32_t* cb = hc.c[rstart + i][0];
+      const uint32_t* cs = hc.c[rstart + i][1];
+      const int rowoff = i * prm.m;
 #pragma unroll
-        for (int v = 0; v < V; ++v) {
-          const uint32_t j = (uint32_t)(j0 + v);
-          const uint32_t gb = poly3(hc.c[i][0], j);
-          const uint32_t gs = poly3(hc.c[i][1], j);
-          const uint32_t bucket = __umulhi(gb << 1, (uint32_t)prm.m);   // floor(gb*m/2^31)
-          const uint32_t smask = gs << 31;                              // odd -> negative
-          float* cell = sk + (size_t)(rowoff + bucket) * prm.stride;
+      for (int v = 0; v < V; ++v) {
+        const uint32_t j = (uint32_t)(j0 + v);
+        const uint32_t gb = poly3(cb, j);
+        const uint32_t gs = poly3(cs, j);
+        const uint32_t bucket = __umulhi(gb << 1, (uint32_t)prm.m);   // floor(gb*m/2^31)
+        const bool neg = (gs & 1u) != 0;                              // odd -> -1
+        double* cell = sk + (size_t)(rowoff + bucket) * prm.stride;
 #pragma unroll
-          for (int k = 0; k < KC; ++k)
-            if (k < kcnt)
-              atomicAdd(cell + k, __uint_as_float(__float_as_uint(u[k][v]) ^ smask));
-        }
+        for (int k = 0; k < KC; ++k)
+          if (k < kcnt) {
+            const float sv = neg ? -u[k][v] : u[k][v];
+            atomicAdd(cell + k, (double)sv);
+          }
       }
     }
   }
@@ -259,31 +274,33 @@ state_kernel(const StateParams prm, const HashCoef hc) {
   // ---- workgroup reduction of the scalar components (fixed shape) ---------------------
   const int lane = tid & 63, wave = tid >> 6;
   constexpr int kWaves = kStateThreads / 64;
+  if (scalars) {
 #pragma unroll
-  for (int k = 0; k < KC; ++k) {
-    double a = wave_sum(dn[k]);
-    double c = wave_sum(dp[k]);
-    if (lane == 0) { red[(wave * KC + k) * 2] = a; red[(wave * KC + k) * 2 + 1] = c; }
+    for (int k = 0; k < KC; ++k) {
+      double a = wave_sum(dn[k]);
+      double c = wave_sum(dp[k]);
+      if (lane == 0) { red[(wave * KC + k) * 2] = a; red[(wave * KC + k) * 2 + 1] = c; }
+    }
   }
   __syncthreads();
-  if (p < prm.P) {
-    if (tid < 2 * kcnt) {
-      const int k = tid >> 1, q = tid & 1;
-      double s = 0.0;
-      for (int wv = 0; wv < kWaves; ++wv) s += red[(wv * KC + k) * 2 + q];
-      prm.part_np[((size_t)p * prm.K + kstart + k) * 2 + q] = s;
-    }
-    // ---- flush the LDS sketch to this workgroup's slice of the partial buffer ---------
-    for (int t = tid; t < kcnt * cells; t += kStateThreads) {
-      const int k = t / cells, c = t - k * cells;
-      prm.part_sk[((size_t)p * prm.K + kstart + k) * cells + c] = sk[(size_t)c * prm.stride + k];
-    }
+  if (scalars && tid < 2 * kcnt) {
+    const int k = tid >> 1, q = tid & 1;
+    double s = 0.0;
+    for (int wv = 0; wv < kWaves; ++wv) s += red[(wv * KC + k) * 2 + q];
+    prm.part_np[((size_t)p * prm.K + kstart + k) * 2 + q] = s;
+  }
+  // ---- flush the LDS sketch to this workgroup's slice of the partial buffer -----------
+  const int allcells = prm.l * prm.m;
+  for (int t = tid; t < kcnt * cells; t += kStateThreads) {
+    const int k = t / cells, c = t - k * cells;
+    prm.part_sk[((size_t)p * prm.K + kstart + k) * allcells + (size_t)rstart * prm.m + c] =
+        sk[(size_t)c * prm.stride + k];
   }
 }
 
 // state[k][s] = sum over partitions, in partition order, in fp64.
 __global__ void __launch_bounds__(kSmallThreads)
-merge_kernel(const double* __restrict__ part_np, const float* __restrict__ part_sk,
+merge_kernel(const double* __restrict__ part_np, const double* __restrict__ part_sk,
              float* __restrict__ state, int K, int cells, int P) {
   const int S = 2 + cells;
   const long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
@@ -294,7 +311,7 @@ merge_kernel(const double* __restrict__ part_np, const float* __restrict__ part_
     for (int p = 0; p < P; ++p) acc += part_np[((size_t)p * K + k) * 2 + s];
   } else {
     const int c = s - 2;
-    for (int p = 0; p < P; ++p) acc += (double)part_sk[((size_t)p * K + k) * cells + c];
+    for (int p = 0; p < P; ++p) acc += part_sk[((size_t)p * K + k) * cells + c];
   }
   state[idx] = (float)acc;
 }

@@ -35,7 +35,7 @@ def test_struct_layouts_match_header():
     assert C.sizeof(F.FdaEstimate) == 64
     assert F.FdaEstimate.sync_linear.offset == 40 and F.FdaEstimate.sync_sketch.offset == 44
     assert C.sizeof(F.FdaDesc) == 56
-    assert C.sizeof(F.FdaPlanInfo) == 48
+    assert C.sizeof(F.FdaPlanInfo) == 56
 
 
 def test_strerror():
@@ -96,7 +96,7 @@ def test_plan_of_the_five_configs(name):
     tile = p.threads * (4 if dt == F.FDA_F32 else 8)
     assert p.chunk % tile == 0
     # the partial buffers fit in the workspace
-    need = p.partitions * c["K"] * (16 + 4 * c["l"] * c["m"])
+    need = p.partitions * c["K"] * (16 + 8 * c["l"] * c["m"])
     assert p.workspace_bytes >= need
     # sketch bytes the paper quotes for 5 x 250: l * m * 4 = 5 kB (Section 3.3)
     if (c["l"], c["m"]) == (5, 250):
@@ -106,4 +106,4 @@ def test_plan_of_the_five_configs(name):
 def test_plan_linear_only_needs_no_sketch():
     desc, keep = make_desc(60, 10**6, F.FDA_F32, F.FDA_VARIANT_LINEAR)
     p = F.fda_plan(desc, 256, 163840)
-    assert p.state_floats == 2 and p.worker_groups == 4
+    assert p.state_floats == 2 and p.worker_groups == 4 and p.row_groups == 1

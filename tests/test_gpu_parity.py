@@ -87,7 +87,7 @@ STATE_CASES = [
     ("cfg4", 40_003, {"K": 33, "l": 4}),      # even number of rows
     ("cfg1", 30_001, {"l": 16, "m": 64}),
     ("cfg1", 30_001, {"l": 1, "m": 1}),
-    ("cfg2", 20_000, {"K": 3, "l": 1, "m": 30_000}),   # one worker per group: sketch fills LDS
+    ("cfg2", 20_000, {"K": 3, "l": 1, "m": 19_000}),   # one worker per group: sketch fills LDS
 ]
 
 
