@@ -55,6 +55,9 @@ def main():
     ap.add_argument("--variants", type=int, default=3, help="1 linear, 2 sketch, 3 both")
     ap.add_argument("--d", type=int, default=None, help="override d (for quick checks)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", type=int, default=0, metavar="MiB",
+                    help="instead of the benchmark, run a plain device copy of this many MiB five "
+                         "times (a kernel of known traffic, to scale rocprofv3's FETCH_SIZE / WRITE_SIZE)")
     ap.add_argument("--cpu-sample", type=int, default=2_000_000,
                     help="coordinates of the workload the CPU oracle is timed on")
     args = ap.parse_args()
@@ -75,6 +78,18 @@ def main():
     F.load_library()
     dev = "cuda:0"
     torch.cuda.set_device(0)
+
+    if args.copy_calibration:
+        n = args.copy_calibration << 20
+        src = torch.full((n // 4,), 1.0, dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_calibration_bytes_read": n, "copy_calibration_bytes_written": n,
+                          "launches": 5}))
+        return
 
     wl = S.make(args.config, device=dev, seed=0, d=args.d)
     K, d = wl.K, wl.d
