@@ -31,17 +31,20 @@ int fail(int code, const char* fmt, ...) {
 
 constexpr int64_t kLdsReserve = 2560;      // reduction scratch (8 waves x 16 workers x 2 doubles) + slack
 constexpr int kOversubscribe = 4;          // workgroups launched per resident workgroup slot
-constexpr double kHashOpsPerRow = 60.0;    // rough vector-ALU cost of hashing one coordinate for one row
-constexpr double kLoadOpsPerElement = 4.0; // rough cost of loading / widening / differencing one element
+constexpr double kHashOpsPerRow = 26.0;    // rough vector-ALU cost of hashing one coordinate for one row
+constexpr double kLoadOpsPerElement = 10.0;// rough cost of loading / differencing / converting one element
+constexpr int kMaxRowsPerGroup = 8;        // sketch rows one workgroup can own (register budget)
+constexpr int kScaleBlocks = 256;
+constexpr int kScaleSamples = 65536;       // sampled coordinates per worker for the scale
 constexpr int kXiBlocks = 1024;
 constexpr int64_t kAlign = 256;
 
 int64_t round_up(int64_t x, int64_t a) { return (x + a - 1) / a * a; }
 
 struct Plan {
-  int G, R, kcnt_max, rcnt_max, KC, P, stride, vec;   // vec = elements per 16-byte slab load
+  int G, R, kcnt_max, rcnt_max, KC, LR, P, stride, vec;   // vec = elements per 16-byte slab load
   int64_t chunk, lds_bytes, cells, S;
-  int64_t off_np, off_sk, off_xi, ws_bytes;
+  int64_t off_np, off_sk, off_xi, off_scale, off_smax, off_ssum, off_nmax, ws_bytes;
 };
 
 int validate(const fda_desc* d) {
@@ -88,6 +91,7 @@ int make_plan(const fda_desc* d, int cus, int64_t lds_cu, Plan* pl) {
     const int stride = (kc == 1) ? 1 : (kc | 1);
     for (int R = 1; R <= l; ++R) {
       const int rc = (l + R - 1) / R;
+      if (rc > kMaxRowsPerGroup) continue;
       if (pl->cells && (int64_t)rc * d->m * stride * 8 + kLdsReserve > lds_cu) continue;
       const double cost = (double)G * l * kHashOpsPerRow + (double)R * d->K * kLoadOpsPerElement +
                           1e-3 * G * R;
@@ -106,6 +110,7 @@ int make_plan(const fda_desc* d, int cus, int64_t lds_cu, Plan* pl) {
   int KC = 1;
   while (KC < pl->kcnt_max) KC *= 2;
   pl->KC = KC;
+  pl->LR = pl->rcnt_max <= 2 ? 2 : (pl->rcnt_max <= 5 ? 5 : 8);
   const int64_t sk_bytes = pl->cells ? (int64_t)pl->rcnt_max * d->m * pl->stride * 8 : 0;
   pl->lds_bytes = round_up(sk_bytes, 16) + kLdsReserve;
   int occ = (int)(lds_cu / pl->lds_bytes);
@@ -122,7 +127,11 @@ int make_plan(const fda_desc* d, int cus, int64_t lds_cu, Plan* pl) {
   pl->off_np = 0;
   pl->off_sk = round_up(pl->off_np + P * d->K * 2 * 8, kAlign);
   pl->off_xi = round_up(pl->off_sk + P * d->K * pl->cells * 8, kAlign);
-  pl->ws_bytes = round_up(pl->off_xi + kXiBlocks * 8, kAlign);
+  pl->off_scale = round_up(pl->off_xi + kXiBlocks * 8, kAlign);
+  pl->off_smax = round_up(pl->off_scale + (int64_t)sizeof(fda::ScaleInfo), kAlign);
+  pl->off_ssum = round_up(pl->off_smax + kScaleBlocks * 4, kAlign);
+  pl->off_nmax = round_up(pl->off_ssum + kScaleBlocks * 8, kAlign);
+  pl->ws_bytes = round_up(pl->off_nmax + 4, kAlign);
   return FDA_OK;
 }
 
@@ -153,9 +162,9 @@ int device_shape(int* cus, int64_t* lds) {
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
 
 // prm == nullptr: only raise the kernel's dynamic-LDS limit (done once, at fda_create).
-template <typename T, int KC>
+template <typename T, int KC, int LR, bool FX>
 int launch_state(const fda::StateParams* prm, const fda::HashCoef& hc, size_t lds, hipStream_t st) {
-  auto kern = fda::state_kernel<T, KC>;
+  auto kern = fda::state_kernel<T, KC, LR, FX>;
   if (prm == nullptr) {
     FDA_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
@@ -166,17 +175,35 @@ int launch_state(const fda::StateParams* prm, const fda::HashCoef& hc, size_t ld
   return FDA_OK;
 }
 
+template <typename T, int KC>
+int dispatch_rows(int LR, bool fx, const fda::StateParams* prm, const fda::HashCoef& hc, size_t lds,
+                  hipStream_t st) {
+  if (!fx) return launch_state<T, KC, 1, false>(prm, hc, lds, st);
+  switch (LR) {
+    case 2: return launch_state<T, KC, 2, true>(prm, hc, lds, st);
+    case 5: return launch_state<T, KC, 5, true>(prm, hc, lds, st);
+    case 8: return launch_state<T, KC, 8, true>(prm, hc, lds, st);
+  }
+  return fail(FDA_EINVAL, "internal: no kernel for %d rows per group", LR);
+}
+
 template <typename T>
-int dispatch_state(int KC, const fda::StateParams* prm, const fda::HashCoef& hc, size_t lds,
-                   hipStream_t st) {
+int dispatch_state(int KC, int LR, bool fx, const fda::StateParams* prm, const fda::HashCoef& hc,
+                   size_t lds, hipStream_t st) {
   switch (KC) {
-    case 1: return launch_state<T, 1>(prm, hc, lds, st);
-    case 2: return launch_state<T, 2>(prm, hc, lds, st);
-    case 4: return launch_state<T, 4>(prm, hc, lds, st);
-    case 8: return launch_state<T, 8>(prm, hc, lds, st);
-    case 16: return launch_state<T, 16>(prm, hc, lds, st);
+    case 1: return dispatch_rows<T, 1>(LR, fx, prm, hc, lds, st);
+    case 2: return dispatch_rows<T, 2>(LR, fx, prm, hc, lds, st);
+    case 4: return dispatch_rows<T, 4>(LR, fx, prm, hc, lds, st);
+    case 8: return dispatch_rows<T, 8>(LR, fx, prm, hc, lds, st);
+    case 16: return dispatch_rows<T, 16>(LR, fx, prm, hc, lds, st);
   }
   return fail(FDA_EINVAL, "internal: no kernel for %d workers per group", KC);
+}
+
+int dispatch_any(int dtype, int KC, int LR, bool fx, const fda::StateParams* prm,
+                 const fda::HashCoef& hc, size_t lds, hipStream_t st) {
+  return dtype == FDA_F32 ? dispatch_state<float>(KC, LR, fx, prm, hc, lds, st)
+                          : dispatch_state<fda::bf16_t>(KC, LR, fx, prm, hc, lds, st);
 }
 
 constexpr int kProfSlots = 64;
@@ -190,6 +217,7 @@ struct fda_ctx {
   unsigned char* ws;
   int device;
   int cus;
+  bool counted = false;       // cell_count_kernel has been enqueued for this context
   // optional timing of the state kernel (fda_profile_enable)
   bool prof_on = false;
   hipEvent_t prof_start[kProfSlots] = {};
@@ -287,9 +315,14 @@ int fda_create(fda_ctx** ctx, const fda_desc* desc, void* workspace, size_t work
     delete c;
     return fail(FDA_EHIP, "hipGetDevice failed");
   }
-  rc = desc->dtype == FDA_F32
-           ? dispatch_state<float>(pl.KC, nullptr, c->coef, (size_t)pl.lds_bytes, nullptr)
-           : dispatch_state<fda::bf16_t>(pl.KC, nullptr, c->coef, (size_t)pl.lds_bytes, nullptr);
+  rc = dispatch_any(desc->dtype, pl.KC, pl.LR, true, nullptr, c->coef, (size_t)pl.lds_bytes, nullptr);
+  if (rc == FDA_OK && (desc->variants & FDA_VARIANT_SKETCH)) {
+    rc = dispatch_any(desc->dtype, pl.KC, pl.LR, false, nullptr, c->coef, (size_t)pl.lds_bytes, nullptr);
+    if (rc == FDA_OK &&
+        hipFuncSetAttribute(reinterpret_cast<const void*>(fda::cell_count_kernel),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, desc->m * 4) != hipSuccess)
+      rc = fail(FDA_EHIP, "hipFuncSetAttribute(cell_count_kernel) failed");
+  }
   if (rc != FDA_OK) {
     delete c;
     return rc;
@@ -371,7 +404,38 @@ int fda_local_state(fda_ctx* ctx, const void* w, const float* w_t0, const float*
   prm.vec_ok = aligned16(w) && aligned16(w_t0) && (!lin || aligned16(xi)) &&
                (d.row_stride * esz) % 16 == 0;
   prm.part_np = reinterpret_cast<double*>(ctx->ws + pl.off_np);
-  prm.part_sk = reinterpret_cast<double*>(ctx->ws + pl.off_sk);
+  prm.part_sk = ctx->ws + pl.off_sk;
+  prm.scale = reinterpret_cast<fda::ScaleInfo*>(ctx->ws + pl.off_scale);
+
+  if (sk) {
+    // fixed-point unit for this call, from a sample of the drifts; also clears the overflow flag
+    float* smax = reinterpret_cast<float*>(ctx->ws + pl.off_smax);
+    double* ssum = reinterpret_cast<double*>(ctx->ws + pl.off_ssum);
+    unsigned int* nmax = reinterpret_cast<unsigned int*>(ctx->ws + pl.off_nmax);
+    if (!ctx->counted) {
+      // once per context: the largest number of coordinates any workgroup puts in one cell
+      hipLaunchKernelGGL(fda::clear_u32_kernel, dim3(1), dim3(64), 0, st, nmax);
+      FDA_HIP(hipGetLastError());
+      hipLaunchKernelGGL(fda::cell_count_kernel, dim3(pl.P * d.l), dim3(fda::kStateThreads),
+                         (size_t)d.m * 4, st, ctx->coef, d.l, d.m, (long long)d.d, (long long)pl.chunk,
+                         nmax);
+      FDA_HIP(hipGetLastError());
+      ctx->counted = true;
+    }
+    const int samples = (int)(d.d < kScaleSamples ? d.d : kScaleSamples);
+    if (d.dtype == FDA_F32)
+      hipLaunchKernelGGL(fda::scale_sample_kernel<float>, dim3(kScaleBlocks), dim3(fda::kSmallThreads), 0,
+                         st, static_cast<const float*>(w), w_t0, d.K, (long long)d.d,
+                         (long long)d.row_stride, samples, smax, ssum);
+    else
+      hipLaunchKernelGGL(fda::scale_sample_kernel<fda::bf16_t>, dim3(kScaleBlocks),
+                         dim3(fda::kSmallThreads), 0, st, static_cast<const fda::bf16_t*>(w), w_t0, d.K,
+                         (long long)d.d, (long long)d.row_stride, samples, smax, ssum);
+    FDA_HIP(hipGetLastError());
+    hipLaunchKernelGGL(fda::scale_finalize_kernel, dim3(1), dim3(64), 0, st, smax, ssum, kScaleBlocks,
+                       (long long)samples * d.K, nmax, prm.scale);
+    FDA_HIP(hipGetLastError());
+  }
 
   int slot = -1;
   if (ctx->prof_on) {
@@ -382,19 +446,22 @@ int fda_local_state(fda_ctx* ctx, const void* w, const float* w_t0, const float*
     slot = ctx->prof_pending;
     FDA_HIP(hipEventRecord(ctx->prof_start[slot], st));
   }
-  int rc = d.dtype == FDA_F32
-               ? dispatch_state<float>(pl.KC, &prm, ctx->coef, (size_t)pl.lds_bytes, st)
-               : dispatch_state<fda::bf16_t>(pl.KC, &prm, ctx->coef, (size_t)pl.lds_bytes, st);
+  int rc = dispatch_any(d.dtype, pl.KC, pl.LR, true, &prm, ctx->coef, (size_t)pl.lds_bytes, st);
   if (rc != FDA_OK) return rc;
   if (slot >= 0) {
     FDA_HIP(hipEventRecord(ctx->prof_stop[slot], st));
     ctx->prof_pending = slot + 1;
   }
+  if (sk) {
+    // runs to completion only if the integer path met a drift it could not represent
+    rc = dispatch_any(d.dtype, pl.KC, pl.LR, false, &prm, ctx->coef, (size_t)pl.lds_bytes, st);
+    if (rc != FDA_OK) return rc;
+  }
 
   const long long total = (long long)d.K * pl.S;
   const int blocks = (int)((total + fda::kSmallThreads - 1) / fda::kSmallThreads);
   hipLaunchKernelGGL(fda::merge_kernel, dim3(blocks), dim3(fda::kSmallThreads), 0, st,
-                     prm.part_np, prm.part_sk, state, d.K, (int)pl.cells, pl.P);
+                     prm.part_np, prm.part_sk, prm.scale, state, d.K, (int)pl.cells, pl.P);
   FDA_HIP(hipGetLastError());
   return FDA_OK;
 }

@@ -446,3 +446,53 @@ def _apply_noise(w, latent, noise, dtype):
         latent = latent + noise
         return O.round_to_bf16_bits(latent.astype(np.float64)), latent
     return w + noise, None
+
+
+def test_state_is_bit_reproducible():
+    """The sketch cells are accumulated as integers and merged in a fixed order, the scalar
+    components are reduced in a fixed shape: two runs must agree bit for bit."""
+    say("[case] run-to-run reproducibility")
+    wl = S.make("cfg3", device=DEV, seed=9, d=400_003)
+    mon = monitor_for(wl)
+    mon.local_state(wl.w, wl.w_t0, wl.xi)
+    first = mon.state.clone()
+    for _ in range(3):
+        mon.local_state(wl.w, wl.w_t0, wl.xi)
+        assert torch.equal(first.view(torch.int32), mon.state.view(torch.int32))
+    mon.close()
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_drifts_outside_the_sampled_range(dtype):
+    """Drifts the sampled scale cannot represent -- isolated spikes 2^20 times larger than
+    everything the sample sees, or a drift that is zero at every sampled coordinate -- must
+    still give the oracle's sketch (the fp64 pass takes over)."""
+    say(f"[case] out-of-range drifts {dtype}")
+    import paper_2405_20988_amd as F
+    K, d, l, m = 6, 300_000, 5, 250
+    g = torch.Generator(device=DEV)
+    g.manual_seed(10)
+    coef = S.hash_coefficients(10, l)
+    w_t0 = torch.randn(d, generator=g, device=DEV) * 0.05
+    xi = torch.randn(d, generator=g, device=DEV) / d ** 0.5
+    tdt = torch.float32 if dtype == "f32" else torch.bfloat16
+    for kind in ("spikes", "sparse"):
+        if kind == "spikes":
+            u = torch.randn((K, d), generator=g, device=DEV) * 1e-6
+            u[1, 12_345] = 3.0
+            u[4, 299_999] = -2.5
+        else:
+            u = torch.zeros((K, d), device=DEV)
+            u[0, 7] = 1.0
+            u[3, 100_001] = -0.25
+            u[5, 250_003] = 0.5
+        w = (w_t0 + u).to(tdt)
+        if dtype == "bf16":
+            w_t0_used = w_t0.to(torch.bfloat16).float() if kind == "sparse" else w_t0
+        else:
+            w_t0_used = w_t0
+        mon = F.FdaMonitor(K, d, dtype, 3, l, m, 0.06, coef, device=DEV)
+        mon.local_state(w, w_t0_used, xi)
+        ref = O.local_state(S.slab_to_numpy(w), dtype, w_t0_used.cpu().numpy(), xi.cpu().numpy(), coef, m)
+        check_state(mon, ref)
+        mon.close()
