@@ -1,17 +1,25 @@
-"""Compile the HIP library for gfx950, in-tree (paper_2405_20988_amd/lib/libfda.so)."""
+"""Compile the HIP library for gfx950, in-tree (paper_2405_20988_amd/lib/libfda.so).
+
+The translation units are compiled in parallel and linked into one shared library."""
 from __future__ import annotations
 
 import os
 import shutil
 import subprocess
+from concurrent.futures import ThreadPoolExecutor
 
 PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
+CSRC = os.path.join(PKG, "csrc")
 LIB_DIR = os.path.join(PKG, "lib")
+OBJ_DIR = os.path.join(PKG, "_build")
 LIB_PATH = os.path.join(LIB_DIR, "libfda.so")
-SOURCES = [os.path.join(PKG, "csrc", "fda_api.hip")]
-DEPENDS = SOURCES + [os.path.join(PKG, "csrc", "fda_kernels.hpp"),
-                     os.path.join(ROOT, "include", "fda.h")]
+UNITS = ["fda_api"] + ["fda_state_%s_%s_%s" % (t, c, h) for t in ("f32", "bf16")
+                       for c in ("fx", "f64") for h in ("lo", "hi")]
+SOURCES = [os.path.join(CSRC, u + ".hip") for u in UNITS]
+DEPENDS = SOURCES + [os.path.join(CSRC, n) for n in
+                     ("fda_kernels.hpp", "fda_small_kernels.hpp", "fda_state_launch.hpp", "fda_state_tu.inc")] + \
+    [os.path.join(ROOT, "include", "fda.h")]
 
 
 def hipcc() -> str:
@@ -21,23 +29,32 @@ def hipcc() -> str:
     return exe
 
 
-def command() -> list[str]:
-    return [hipcc(), "-O3", "--offload-arch=gfx950", "-std=c++17", "-shared", "-fPIC",
+def flags() -> list[str]:
+    return ["-O3", "--offload-arch=gfx950", "-std=c++17", "-fPIC",
             # packed fp32 instructions are kept off for all device code
             "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-            "-I" + os.path.join(ROOT, "include"), "-I" + os.path.join(PKG, "csrc"),
-            "-o", LIB_PATH] + SOURCES
+            "-I" + os.path.join(ROOT, "include"), "-I" + CSRC]
+
+
+def _run(cmd):
+    proc = subprocess.run(cmd, capture_output=True, text=True)
+    if proc.returncode != 0:
+        raise RuntimeError("hipcc failed:\n" + " ".join(cmd) + "\n" + proc.stdout + proc.stderr)
 
 
 def build_library(verbose: bool = False) -> str:
     """Always compiles; returns the path of the shared library."""
     os.makedirs(LIB_DIR, exist_ok=True)
-    cmd = command()
-    proc = subprocess.run(cmd, capture_output=True, text=True)
-    if proc.returncode != 0:
-        raise RuntimeError("hipcc failed:\n" + " ".join(cmd) + "\n" + proc.stdout + proc.stderr)
+    os.makedirs(OBJ_DIR, exist_ok=True)
+    objs = [os.path.join(OBJ_DIR, u + ".o") for u in UNITS]
+    cmds = [[hipcc()] + flags() + ["-c", src, "-o", obj] for src, obj in zip(SOURCES, objs)]
+    with ThreadPoolExecutor(max_workers=min(len(cmds), os.cpu_count() or 4)) as pool:
+        list(pool.map(_run, cmds))
+    link = [hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB_PATH] + objs
+    _run(link)
     if verbose:
-        print(" ".join(cmd))
+        for c in cmds + [link]:
+            print(" ".join(c))
     return LIB_PATH
 
 
@@ -49,4 +66,4 @@ def is_stale() -> bool:
 
 
 if __name__ == "__main__":
-    print(build_library(verbose=True))
+    print(build_library(verbose=False))

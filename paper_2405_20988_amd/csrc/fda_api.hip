@@ -8,7 +8,8 @@
 #include <new>
 
 #include "fda.h"
-#include "fda_kernels.hpp"
+#include "fda_small_kernels.hpp"
+#include "fda_state_launch.hpp"
 
 namespace {
 
@@ -29,11 +30,12 @@ int fail(int code, const char* fmt, ...) {
       return fail(FDA_EHIP, "%s failed: %s", #call, hipGetErrorString(e_));            \
   } while (0)
 
-constexpr int64_t kLdsReserve = 2560;      // reduction scratch (8 waves x 16 workers x 2 doubles) + slack
-constexpr int kOversubscribe = 4;          // workgroups launched per resident workgroup slot
-constexpr double kHashOpsPerRow = 26.0;    // rough vector-ALU cost of hashing one coordinate for one row
-constexpr double kLoadOpsPerElement = 10.0;// rough cost of loading / differencing / converting one element
-constexpr int kMaxRowsPerGroup = 8;        // sketch rows one workgroup can own (register budget)
+constexpr int64_t kLdsReserve = 1536;      // reduction scratch (8 waves x 8 worker slots x 2 doubles) + slack
+constexpr int kMaxRounds = 4;              // at most this many rounds of resident workgroups per launch
+constexpr double kElementCost = 10.0;      // rough cost of loading / differencing / converting one slab element
+constexpr double kAtomicCost = 3.0;        // select the signed value, issue the LDS atomic
+constexpr double kDecodeCost = 5.0;        // unpack one table entry into an LDS address and a sign
+constexpr double kSharedByteCost = 0.5;    // per byte of w_t0 / xi / table re-read by another workgroup
 constexpr int kScaleBlocks = 256;
 constexpr int kScaleSamples = 65536;       // sampled coordinates per worker for the scale
 constexpr int kXiBlocks = 1024;
@@ -44,7 +46,7 @@ int64_t round_up(int64_t x, int64_t a) { return (x + a - 1) / a * a; }
 struct Plan {
   int G, R, kcnt_max, rcnt_max, KC, LR, P, stride, vec;   // vec = elements per 16-byte slab load
   int64_t chunk, lds_bytes, cells, S;
-  int64_t off_np, off_sk, off_xi, off_scale, off_smax, off_ssum, off_nmax, ws_bytes;
+  int64_t off_np, off_sk, off_xi, off_scale, off_smax, off_ssum, off_nmax, off_table, dpad, ws_bytes;
 };
 
 int validate(const fda_desc* d) {
@@ -62,6 +64,7 @@ int validate(const fda_desc* d) {
     if (d->l < 1 || d->l > FDA_MAX_SKETCH_ROWS)
       return fail(FDA_EINVAL, "l must be in 1..%d (got %d)", FDA_MAX_SKETCH_ROWS, d->l);
     if (d->m < 1) return fail(FDA_EINVAL, "m must be >= 1");
+    if (d->m > 32767) return fail(FDA_ERANGE, "m must be below 32768 (bucket indices are tabulated in 15 bits)");
     if ((int64_t)d->l * d->m > (int64_t)1 << 24) return fail(FDA_ERANGE, "l*m too large");
     if (!(d->eps > -1.0)) return fail(FDA_EINVAL, "eps must be > -1");
     if (d->hash_coef == nullptr) return fail(FDA_EINVAL, "hash_coef is NULL");
@@ -79,23 +82,31 @@ int make_plan(const fda_desc* d, int cus, int64_t lds_cu, Plan* pl) {
   pl->S = 2 + pl->cells;
   pl->vec = d->dtype == FDA_F32 ? 4 : 8;
   // Split the K workers into G groups and the l sketch rows into R groups so that one
-  // workgroup's fp64 sketch (rows x m cells x workers) fits in LDS.  More worker groups repeat
-  // the hash evaluation, more row groups re-read the slab rows through L2; pick the split
-  // with the least estimated vector-ALU work per coordinate.
+  // workgroup's sketch (rows x m cells x worker slots, 8 bytes each) fits in LDS.  The kernel
+  // has KC worker slots and LR row slots (compile-time); slots a group does not fill still
+  // execute.  Every row group repeats the loads and the fixed-point conversion of its workers'
+  // elements; every workgroup decodes its rows' table entries and re-reads w_t0 / xi / table
+  // (through L2).  Pick the split with the least estimated vector-ALU work per coordinate.
   const int l = sk ? d->l : 1;
   double best = -1.0;
-  int bestG = 0, bestR = 0;
+  int bestG = 0, bestR = 0, bestKC = 0;
   for (int G = 1; G <= d->K; ++G) {
     const int kc = (d->K + G - 1) / G;
-    if (kc > fda::kMaxKC) continue;
-    const int stride = (kc == 1) ? 1 : (kc | 1);
+    int KC = 0;
+    for (int c : fda::kKCSet)
+      if (c >= kc) { KC = c; break; }
+    if (KC == 0) continue;
+    const int stride = (KC == 1) ? 1 : (KC | 1);
     for (int R = 1; R <= l; ++R) {
       const int rc = (l + R - 1) / R;
-      if (rc > kMaxRowsPerGroup) continue;
-      if (pl->cells && (int64_t)rc * d->m * stride * 8 + kLdsReserve > lds_cu) continue;
-      const double cost = (double)G * l * kHashOpsPerRow + (double)R * d->K * kLoadOpsPerElement +
-                          1e-3 * G * R;
-      if (best < 0.0 || cost < best) { best = cost; bestG = G; bestR = R; }
+      if (rc > fda::kMaxLR) continue;
+      const int64_t dummy = fda::kDummyCells;
+      if (pl->cells && ((int64_t)rc * d->m + dummy) * stride * 8 + kLdsReserve > lds_cu) continue;
+      const double slots = (double)G * R * KC;           // element slots per coordinate
+      const double cost = slots * kElementCost + slots * rc * kAtomicCost +
+                          (double)G * R * rc * kDecodeCost +
+                          (double)G * R * (8 + 2 * rc) * kSharedByteCost + 1e-3 * G * R;
+      if (best < 0.0 || cost < best) { best = cost; bestG = G; bestR = R; bestKC = KC; }
       break;   // a larger R only costs more for this G
     }
   }
@@ -106,20 +117,28 @@ int make_plan(const fda_desc* d, int cus, int64_t lds_cu, Plan* pl) {
   pl->R = bestR;
   pl->kcnt_max = (d->K + bestG - 1) / bestG;
   pl->rcnt_max = (l + bestR - 1) / bestR;
-  pl->stride = (pl->kcnt_max == 1) ? 1 : (pl->kcnt_max | 1);
-  int KC = 1;
-  while (KC < pl->kcnt_max) KC *= 2;
-  pl->KC = KC;
-  pl->LR = pl->rcnt_max <= 2 ? 2 : (pl->rcnt_max <= 5 ? 5 : 8);
-  const int64_t sk_bytes = pl->cells ? (int64_t)pl->rcnt_max * d->m * pl->stride * 8 : 0;
+  pl->KC = bestKC;
+  pl->LR = pl->rcnt_max;
+  pl->stride = (pl->KC == 1) ? 1 : (pl->KC | 1);
+  const int64_t dummy_cells = pl->cells ? fda::kDummyCells : 0;
+  const int64_t sk_bytes = pl->cells ? ((int64_t)pl->rcnt_max * d->m + dummy_cells) * pl->stride * 8 : 0;
   pl->lds_bytes = round_up(sk_bytes, 16) + kLdsReserve;
   int occ = (int)(lds_cu / pl->lds_bytes);
   if (occ > 2) occ = 2;
   if (occ < 1) occ = 1;
   const int64_t tile = (int64_t)fda::kStateThreads * pl->vec;
-  // a few workgroups per CU slot, so that the last wave of workgroups costs little
-  int64_t P = round_up(((int64_t)cus * occ * kOversubscribe + bestG * bestR - 1) / (bestG * bestR), 8);
-  if (P < 8) P = 8;
+  // Partitions: all workgroups do the same amount of work, so the launch should fill the
+  // resident slots a whole number of times.  Try 1..4 rounds and keep the best-filled one.
+  const int64_t slots = (int64_t)cus * occ, gr = (int64_t)bestG * bestR;
+  int64_t P = 8;
+  double best_fill = -1.0;
+  for (int rounds = 1; rounds <= kMaxRounds; ++rounds) {
+    int64_t cand = slots * rounds / gr / 8 * 8;
+    if (cand < 8) cand = 8;
+    const int64_t wgs = cand * gr;
+    const double fill = (double)wgs / (double)((wgs + slots - 1) / slots * slots);
+    if (fill > best_fill + 0.02) { best_fill = fill; P = cand; }
+  }
   const int64_t tiles = (d->d + tile - 1) / tile;
   if (P > round_up(tiles, 8)) P = round_up(tiles, 8);
   pl->P = (int)P;
@@ -131,7 +150,9 @@ int make_plan(const fda_desc* d, int cus, int64_t lds_cu, Plan* pl) {
   pl->off_smax = round_up(pl->off_scale + (int64_t)sizeof(fda::ScaleInfo), kAlign);
   pl->off_ssum = round_up(pl->off_smax + kScaleBlocks * 4, kAlign);
   pl->off_nmax = round_up(pl->off_ssum + kScaleBlocks * 8, kAlign);
-  pl->ws_bytes = round_up(pl->off_nmax + 4, kAlign);
+  pl->off_table = round_up(pl->off_nmax + 4, kAlign);
+  pl->dpad = round_up(d->d, 64);
+  pl->ws_bytes = round_up(pl->off_table + (sk ? (int64_t)d->l * pl->dpad * 2 : 0), kAlign);
   return FDA_OK;
 }
 
@@ -161,49 +182,23 @@ int device_shape(int* cus, int64_t* lds) {
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
 
-// prm == nullptr: only raise the kernel's dynamic-LDS limit (done once, at fda_create).
-template <typename T, int KC, int LR, bool FX>
-int launch_state(const fda::StateParams* prm, const fda::HashCoef& hc, size_t lds, hipStream_t st) {
-  auto kern = fda::state_kernel<T, KC, LR, FX>;
-  if (prm == nullptr) {
-    FDA_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-    return FDA_OK;
+// The state kernels are instantiated in eight translation units (fda_state_*.hip), by slab
+// type, cell type and worker-slot count, so that they compile in parallel.
+int dispatch_any(int dtype, int KC, int LR, bool fx, const fda::StateParams* prm, size_t lds,
+                 hipStream_t st) {
+  const bool hi = KC > 4;
+  hipError_t e;
+  if (dtype == FDA_F32) {
+    if (fx) e = hi ? fda::launch_state_f32_fx_hi(KC, LR, prm, lds, st) : fda::launch_state_f32_fx_lo(KC, LR, prm, lds, st);
+    else e = hi ? fda::launch_state_f32_f64_hi(KC, LR, prm, lds, st) : fda::launch_state_f32_f64_lo(KC, LR, prm, lds, st);
+  } else {
+    if (fx) e = hi ? fda::launch_state_bf16_fx_hi(KC, LR, prm, lds, st) : fda::launch_state_bf16_fx_lo(KC, LR, prm, lds, st);
+    else e = hi ? fda::launch_state_bf16_f64_hi(KC, LR, prm, lds, st) : fda::launch_state_bf16_f64_lo(KC, LR, prm, lds, st);
   }
-  hipLaunchKernelGGL(kern, dim3(prm->G * prm->R * prm->P), dim3(fda::kStateThreads), lds, st, *prm, hc);
-  FDA_HIP(hipGetLastError());
+  if (e == hipErrorInvalidValue)
+    return fail(FDA_EINVAL, "internal: no state kernel for %d workers x %d rows per workgroup", KC, LR);
+  if (e != hipSuccess) return fail(FDA_EHIP, "state kernel launch failed: %s", hipGetErrorString(e));
   return FDA_OK;
-}
-
-template <typename T, int KC>
-int dispatch_rows(int LR, bool fx, const fda::StateParams* prm, const fda::HashCoef& hc, size_t lds,
-                  hipStream_t st) {
-  if (!fx) return launch_state<T, KC, 1, false>(prm, hc, lds, st);
-  switch (LR) {
-    case 2: return launch_state<T, KC, 2, true>(prm, hc, lds, st);
-    case 5: return launch_state<T, KC, 5, true>(prm, hc, lds, st);
-    case 8: return launch_state<T, KC, 8, true>(prm, hc, lds, st);
-  }
-  return fail(FDA_EINVAL, "internal: no kernel for %d rows per group", LR);
-}
-
-template <typename T>
-int dispatch_state(int KC, int LR, bool fx, const fda::StateParams* prm, const fda::HashCoef& hc,
-                   size_t lds, hipStream_t st) {
-  switch (KC) {
-    case 1: return dispatch_rows<T, 1>(LR, fx, prm, hc, lds, st);
-    case 2: return dispatch_rows<T, 2>(LR, fx, prm, hc, lds, st);
-    case 4: return dispatch_rows<T, 4>(LR, fx, prm, hc, lds, st);
-    case 8: return dispatch_rows<T, 8>(LR, fx, prm, hc, lds, st);
-    case 16: return dispatch_rows<T, 16>(LR, fx, prm, hc, lds, st);
-  }
-  return fail(FDA_EINVAL, "internal: no kernel for %d workers per group", KC);
-}
-
-int dispatch_any(int dtype, int KC, int LR, bool fx, const fda::StateParams* prm,
-                 const fda::HashCoef& hc, size_t lds, hipStream_t st) {
-  return dtype == FDA_F32 ? dispatch_state<float>(KC, LR, fx, prm, hc, lds, st)
-                          : dispatch_state<fda::bf16_t>(KC, LR, fx, prm, hc, lds, st);
 }
 
 constexpr int kProfSlots = 64;
@@ -315,9 +310,9 @@ int fda_create(fda_ctx** ctx, const fda_desc* desc, void* workspace, size_t work
     delete c;
     return fail(FDA_EHIP, "hipGetDevice failed");
   }
-  rc = dispatch_any(desc->dtype, pl.KC, pl.LR, true, nullptr, c->coef, (size_t)pl.lds_bytes, nullptr);
+  rc = dispatch_any(desc->dtype, pl.KC, pl.LR, true, nullptr, (size_t)pl.lds_bytes, nullptr);
   if (rc == FDA_OK && (desc->variants & FDA_VARIANT_SKETCH)) {
-    rc = dispatch_any(desc->dtype, pl.KC, pl.LR, false, nullptr, c->coef, (size_t)pl.lds_bytes, nullptr);
+    rc = dispatch_any(desc->dtype, pl.KC, pl.LR, false, nullptr, (size_t)pl.lds_bytes, nullptr);
     if (rc == FDA_OK &&
         hipFuncSetAttribute(reinterpret_cast<const void*>(fda::cell_count_kernel),
                             hipFuncAttributeMaxDynamicSharedMemorySize, desc->m * 4) != hipSuccess)
@@ -406,6 +401,8 @@ int fda_local_state(fda_ctx* ctx, const void* w, const float* w_t0, const float*
   prm.part_np = reinterpret_cast<double*>(ctx->ws + pl.off_np);
   prm.part_sk = ctx->ws + pl.off_sk;
   prm.scale = reinterpret_cast<fda::ScaleInfo*>(ctx->ws + pl.off_scale);
+  prm.table = reinterpret_cast<const uint16_t*>(ctx->ws + pl.off_table);
+  prm.dpad = pl.dpad;
 
   if (sk) {
     // fixed-point unit for this call, from a sample of the drifts; also clears the overflow flag
@@ -419,6 +416,13 @@ int fda_local_state(fda_ctx* ctx, const void* w, const float* w_t0, const float*
       hipLaunchKernelGGL(fda::cell_count_kernel, dim3(pl.P * d.l), dim3(fda::kStateThreads),
                          (size_t)d.m * 4, st, ctx->coef, d.l, d.m, (long long)d.d, (long long)pl.chunk,
                          nmax);
+      FDA_HIP(hipGetLastError());
+      // ... and the hash of every (row, coordinate), tabulated
+      const long long groups = pl.dpad / 8;
+      hipLaunchKernelGGL(fda::hash_table_kernel,
+                         dim3((unsigned)((groups + fda::kSmallThreads - 1) / fda::kSmallThreads), d.l),
+                         dim3(fda::kSmallThreads), 0, st, ctx->coef, d.m, (long long)d.d,
+                         (long long)pl.dpad, reinterpret_cast<uint16_t*>(ctx->ws + pl.off_table));
       FDA_HIP(hipGetLastError());
       ctx->counted = true;
     }
@@ -446,7 +450,7 @@ int fda_local_state(fda_ctx* ctx, const void* w, const float* w_t0, const float*
     slot = ctx->prof_pending;
     FDA_HIP(hipEventRecord(ctx->prof_start[slot], st));
   }
-  int rc = dispatch_any(d.dtype, pl.KC, pl.LR, true, &prm, ctx->coef, (size_t)pl.lds_bytes, st);
+  int rc = dispatch_any(d.dtype, pl.KC, pl.LR, true, &prm, (size_t)pl.lds_bytes, st);
   if (rc != FDA_OK) return rc;
   if (slot >= 0) {
     FDA_HIP(hipEventRecord(ctx->prof_stop[slot], st));
@@ -454,12 +458,12 @@ int fda_local_state(fda_ctx* ctx, const void* w, const float* w_t0, const float*
   }
   if (sk) {
     // runs to completion only if the integer path met a drift it could not represent
-    rc = dispatch_any(d.dtype, pl.KC, pl.LR, false, &prm, ctx->coef, (size_t)pl.lds_bytes, st);
+    rc = dispatch_any(d.dtype, pl.KC, pl.LR, false, &prm, (size_t)pl.lds_bytes, st);
     if (rc != FDA_OK) return rc;
   }
 
   const long long total = (long long)d.K * pl.S;
-  const int blocks = (int)((total + fda::kSmallThreads - 1) / fda::kSmallThreads);
+  const int blocks = (int)((total + 31) / 32);
   hipLaunchKernelGGL(fda::merge_kernel, dim3(blocks), dim3(fda::kSmallThreads), 0, st,
                      prm.part_np, prm.part_sk, prm.scale, state, d.K, (int)pl.cells, pl.P);
   FDA_HIP(hipGetLastError());

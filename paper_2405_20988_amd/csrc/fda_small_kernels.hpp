@@ -1,0 +1,373 @@
+// Device code of the FDA monitor for gfx950 (wave64): everything except the state kernel.
+// Included by fda_api.hip only.
+//
+//   hash_table_kernel, cell_count_kernel   once per context: the tabulated hash and the largest
+//                    number of coordinates a workgroup can put into one sketch cell
+//   scale_*_kernel   per call: the fixed-point unit of the integer sketch cells
+//   merge_kernel     fixed-order fp64 sum of the per-workgroup partials -> state[K][S]
+//   estimate_kernel  Algorithm 1 lines 7-8: mean state, M2, H (Thm 1, Thm 2), decision
+//   sync_kernel      Algorithm 1 line 9: fused mean over workers + broadcast to all rows
+//   xi_norm_kernel / xi_scale_kernel   Section 3.2: the normalized model difference
+#pragma once
+#include "fda_kernels.hpp"
+
+namespace fda {
+
+// ---- arithmetic modulo the Mersenne prime 2^31 - 1 (operands already reduced) --------
+__device__ __forceinline__ uint32_t addmod(uint32_t a, uint32_t b) {
+  uint32_t s = a + b;                        // < 2^32
+  return min(s, s - kPrime);                 // s - p wraps to a huge value when s < p
+}
+__device__ __forceinline__ uint32_t mulmod(uint32_t a, uint32_t b) {
+  uint64_t t = (uint64_t)a * b;              // < 2^62
+  uint32_t lo = (uint32_t)t & kPrime;
+  uint32_t hi = (uint32_t)(t >> 31);         // 2^31 = 1 (mod p)
+  uint32_t s = lo + hi;                      // <= 2p - 1
+  return min(s, s - kPrime);
+}
+// c[3] j^3 + c[2] j^2 + c[1] j + c[0] mod p
+__device__ __forceinline__ uint32_t poly3(const uint32_t* c, uint32_t j) {
+  uint32_t g = c[3];
+  g = addmod(mulmod(g, j), c[2]);
+  g = addmod(mulmod(g, j), c[1]);
+  g = addmod(mulmod(g, j), c[0]);
+  return g;
+}
+
+// ---- the hash, tabulated once per context: [row][dpad] 16-bit words, bits 0..14 bucket,
+// bit 15 set for sign -1 (Section 3.1 sketch; hash family: two cubics mod 2^31 - 1 per row)
+__global__ void __launch_bounds__(kSmallThreads)
+hash_table_kernel(const HashCoef hc, int m, long long d, long long dpad,
+                  uint16_t* __restrict__ table) {
+  const int i = blockIdx.y;
+  const long long j8 = ((long long)blockIdx.x * blockDim.x + threadIdx.x) * 8;
+  if (j8 >= dpad) return;
+  uint32_t h[8];
+#pragma unroll
+  for (int q = 0; q < 8; ++q) {
+    const long long j = j8 + q;
+    h[q] = 0u;
+    if (j < d) {
+      const uint32_t gb = poly3(hc.c[i][0], (uint32_t)j);
+      const uint32_t gs = poly3(hc.c[i][1], (uint32_t)j);
+      h[q] = __umulhi(gb << 1, (uint32_t)m) | ((gs & 1u) << 15);   // floor(gb*m/2^31); odd -> -1
+    }
+  }
+  uint4 o;
+  o.x = h[0] | (h[1] << 16); o.y = h[2] | (h[3] << 16);
+  o.z = h[4] | (h[5] << 16); o.w = h[6] | (h[7] << 16);
+  *reinterpret_cast<uint4*>(table + (size_t)i * dpad + j8) = o;
+}
+
+// ---- how many coordinates can meet in one cell of one workgroup ------------------------
+// Depends only on the hash, d and the partitioning, so it is counted once per context: the
+// exact maximum, over workgroups, rows and buckets, of the number of coordinates of the
+// workgroup's chunk that fall into the bucket.  It bounds the number of terms of any LDS cell.
+__global__ void __launch_bounds__(kStateThreads)
+cell_count_kernel(const HashCoef hc, int l, int m, long long d, long long chunk,
+                  unsigned int* __restrict__ nmax) {
+  extern __shared__ __align__(16) unsigned char lds_raw[];
+  unsigned int* cnt = reinterpret_cast<unsigned int*>(lds_raw);
+  __shared__ unsigned int shmax[kStateThreads / 64];
+  const int p = blockIdx.x / l, i = blockIdx.x - p * l;
+  for (int t = threadIdx.x; t < m; t += kStateThreads) cnt[t] = 0u;
+  __syncthreads();
+  const long long cbeg = (long long)p * chunk;
+  long long cend = cbeg + chunk;
+  if (cend > d) cend = d;
+  for (long long j = cbeg + threadIdx.x; j < cend; j += kStateThreads) {
+    const uint32_t gb = poly3(hc.c[i][0], (uint32_t)j);
+    atomicAdd(cnt + __umulhi(gb << 1, (uint32_t)m), 1u);
+  }
+  __syncthreads();
+  unsigned int mx = 0u;
+  for (int t = threadIdx.x; t < m; t += kStateThreads) mx = max(mx, cnt[t]);
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) mx = max(mx, (unsigned int)__shfl_down((int)mx, o, 64));
+  if ((threadIdx.x & 63) == 0) shmax[threadIdx.x >> 6] = mx;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    for (int t = 1; t < kStateThreads / 64; ++t) mx = max(mx, shmax[t]);
+    atomicMax(nmax, mx);
+  }
+}
+__global__ void clear_u32_kernel(unsigned int* p) { if (threadIdx.x == 0 && blockIdx.x == 0) *p = 0u; }
+
+// ---- the per-call fixed-point scale ----------------------------------------------------
+// Largest and mean |w_kj - w_t0_j| over an evenly spaced sample of coordinates of every worker.
+template <typename T>
+__global__ void __launch_bounds__(kSmallThreads)
+scale_sample_kernel(const T* __restrict__ w, const float* __restrict__ w_t0, int K, long long d,
+                    long long row_stride, int samples, float* __restrict__ part_max,
+                    double* __restrict__ part_sum) {
+  __shared__ float sh[kSmallThreads / 64];
+  __shared__ double scratch[kSmallThreads / 64];
+  float m = 0.0f;
+  double sum = 0.0;
+  const long long total = (long long)K * samples;
+  for (long long t = (long long)blockIdx.x * blockDim.x + threadIdx.x; t < total;
+       t += (long long)gridDim.x * blockDim.x) {
+    const int k = (int)(t / samples);
+    const long long j = (t - (long long)k * samples) * d / samples;
+    const float u = fabsf(Slab<T>::load_one(w + (long long)k * row_stride + j) - w_t0[j]);
+    m = fmaxf(m, u);                           // fmaxf drops NaN
+    if (u == u && u < 3.0e38f) sum += (double)u;
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) m = fmaxf(m, __shfl_down(m, o, 64));
+  if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = m;
+  const double tot = block_sum(sum, scratch);  // has the barriers sh needs
+  if (threadIdx.x == 0) {
+    for (int t = 1; t < kSmallThreads / 64; ++t) m = fmaxf(m, sh[t]);
+    part_max[blockIdx.x] = m;
+    part_sum[blockIdx.x] = tot;
+  }
+}
+
+// The unit 2^-e of the integer cells.  With at most nmax terms per cell, |q| < 2^qbits keeps
+// every cell below 2^62.  Drifts up to 2^12..2^13 times the sampled maximum are allowed for
+// (the sample can miss the tail), which leaves qbits - 13 bits below the sampled maximum.  If
+// the mean sampled magnitude would still get fewer than 17 of them, or the sample saw nothing
+// usable, the call is sent down the fp64 path right away.
+__global__ void scale_finalize_kernel(const float* __restrict__ part_max,
+                                      const double* __restrict__ part_sum, int n, long long nsamples,
+                                      const unsigned int* __restrict__ nmax,
+                                      ScaleInfo* __restrict__ out) {
+  if (threadIdx.x != 0 || blockIdx.x != 0) return;
+  float amax = 0.0f;
+  double sum = 0.0;
+  for (int t = 0; t < n; ++t) { amax = fmaxf(amax, part_max[t]); sum += part_sum[t]; }
+  ScaleInfo s;
+  s.S = 1.0; s.invS = 1.0; s.bound = 0.0f; s.overflow = 0; s.pad[0] = 0; s.pad[1] = 0;
+  if (amax > 0.0f && isfinite(amax)) {
+    unsigned int terms = *nmax;
+    int cb = 0;
+    while (cb < 32 && (1ull << cb) <= (unsigned long long)terms) ++cb;    // terms < 2^cb
+    int qbits = 62 - cb;
+    if (qbits > 50) qbits = 50;                // the rounding trick needs |u * 2^e| < 2^51
+    const int head = 13;
+    const int ex = ilogbf(amax);               // 2^ex <= amax < 2^(ex+1)
+    const int e = qbits - (ex + head);         // |u| < 2^(ex+head)  =>  |u * 2^e| < 2^qbits
+    s.S = ldexp(1.0, e);
+    s.invS = ldexp(1.0, -e);
+    s.bound = (ex + head > 127) ? 3.0e38f : ldexpf(1.0f, ex + head);
+    const double mean = sum / (double)nsamples;
+    if (!(mean * s.S >= 131072.0)) s.overflow = 1;     // fewer than 17 bits for a typical drift
+  }
+  *out = s;
+}
+
+// state[k][s] = sum over the P partitions in fp64.  A workgroup handles 32 consecutive state
+// entries; eight lanes per entry each sum every eighth partition and the eight sums are added
+// in slice order: a fixed shape (and the integer partials are exact anyway).
+__global__ void __launch_bounds__(kSmallThreads)
+merge_kernel(const double* __restrict__ part_np, const void* __restrict__ part_sk,
+             const ScaleInfo* __restrict__ scale, float* __restrict__ state, int K, int cells,
+             int P) {
+  __shared__ double sh[8][32];
+  const int S = 2 + cells;
+  const int o = threadIdx.x & 31, slice = threadIdx.x >> 5;
+  const long long idx = (long long)blockIdx.x * 32 + o;
+  const bool live = idx < (long long)K * S;
+  double acc = 0.0;
+  bool integer = false;
+  if (live) {
+    const int k = (int)(idx / S), s = (int)(idx - (long long)k * S);
+    if (s < 2) {
+      for (int p = slice; p < P; p += 8) acc += part_np[((size_t)p * K + k) * 2 + s];
+    } else {
+      const int c = s - 2;
+      integer = scale->overflow == 0;
+      if (integer) {
+        const long long* pi = reinterpret_cast<const long long*>(part_sk);
+        for (int p = slice; p < P; p += 8) acc += (double)pi[((size_t)p * K + k) * cells + c];
+      } else {
+        const double* pd = reinterpret_cast<const double*>(part_sk);
+        for (int p = slice; p < P; p += 8) acc += pd[((size_t)p * K + k) * cells + c];
+      }
+    }
+  }
+  sh[slice][o] = acc;
+  __syncthreads();
+  if (live && slice == 0) {
+    double t = 0.0;
+#pragma unroll
+    for (int q = 0; q < 8; ++q) t += sh[q][o];
+    if (integer) t *= scale->invS;
+    state[idx] = (float)t;
+  }
+}
+
+// ----------------------------------------------------------------------------------------
+// Algorithm 1 lines 7-8, one workgroup, all in fp64:
+//   mean_k of the states;  row norms of the mean sketch;  M2 = their median (Section 3.1);
+//   H_sketch = n - M2/(1+eps) (Thm 1);  H_linear = n - p^2 (Thm 2);  sync = H > theta.
+// ----------------------------------------------------------------------------------------
+__global__ void __launch_bounds__(1024)
+estimate_kernel(const float* __restrict__ state, int K, int l, int m, int variants, double eps,
+                double theta, double tie_tol, fda_estimate* __restrict__ out) {
+  __shared__ double scratch[16];
+  __shared__ double rows[FDA_MAX_SKETCH_ROWS];
+  const int cells = (variants & FDA_VARIANT_SKETCH) ? l * m : 0;
+  const int S = 2 + cells;
+  const int tid = threadIdx.x;
+  double vn = 0.0, vp = 0.0;
+  for (int k = tid; k < K; k += blockDim.x) {
+    vn += (double)state[(size_t)k * S];
+    vp += (double)state[(size_t)k * S + 1];
+  }
+  const double sn = block_sum(vn, scratch);
+  const double sp = block_sum(vp, scratch);
+  if (cells) {
+    for (int i = 0; i < l; ++i) {
+      double acc = 0.0;
+      for (int bkt = tid; bkt < m; bkt += blockDim.x) {
+        double c = 0.0;
+        for (int k = 0; k < K; ++k) c += (double)state[(size_t)k * S + 2 + i * m + bkt];
+        c /= (double)K;
+        acc += c * c;
+      }
+      const double r = block_sum(acc, scratch);
+      if (tid == 0) rows[i] = r;
+    }
+  }
+  if (tid == 0) {
+    fda_estimate e;
+    e.mean_sqnorm = sn / (double)K;
+    e.mean_proj = 0.0; e.m2 = 0.0; e.h_linear = 0.0; e.h_sketch = 0.0;
+    e.sync_linear = 0; e.sync_sketch = 0; e.near_tie_linear = 0; e.near_tie_sketch = 0;
+    e.nonfinite = 0; e.reserved = 0;
+    const double band = tie_tol * fmax(e.mean_sqnorm, fabs(theta));
+    if (variants & FDA_VARIANT_LINEAR) {
+      e.mean_proj = sp / (double)K;
+      e.h_linear = e.mean_sqnorm - e.mean_proj * e.mean_proj;
+      if (isfinite(e.h_linear)) {
+        e.sync_linear = e.h_linear > theta ? 1 : 0;
+        e.near_tie_linear = fabs(e.h_linear - theta) <= band ? 1 : 0;
+      } else {
+        e.sync_linear = 1; e.nonfinite = 1;
+      }
+    }
+    if (cells) {
+      // median of l values: insertion sort, then middle (even l: mean of the two middle)
+      double r[FDA_MAX_SKETCH_ROWS];
+      for (int i = 0; i < l; ++i) {
+        double v = rows[i];
+        int q = i;
+        while (q > 0 && !(r[q - 1] <= v)) { r[q] = r[q - 1]; --q; }
+        r[q] = v;
+      }
+      e.m2 = (l & 1) ? r[l / 2] : 0.5 * (r[l / 2 - 1] + r[l / 2]);
+      e.h_sketch = e.mean_sqnorm - e.m2 / (1.0 + eps);
+      if (isfinite(e.h_sketch)) {
+        e.sync_sketch = e.h_sketch > theta ? 1 : 0;
+        e.near_tie_sketch = fabs(e.h_sketch - theta) <= band ? 1 : 0;
+      } else {
+        e.sync_sketch = 1; e.nonfinite = 1;
+      }
+    }
+    *out = e;
+  }
+}
+
+// ----------------------------------------------------------------------------------------
+// Algorithm 1 line 9: read the K rows once, average in fp32 in worker order, write the
+// average to every row, to w_t0, and the old w_t0 to w_prev.
+// ----------------------------------------------------------------------------------------
+template <typename T>
+__global__ void __launch_bounds__(kSmallThreads)
+sync_kernel(T* __restrict__ w, float* __restrict__ w_t0, float* __restrict__ w_prev,
+            const int32_t* __restrict__ pred, int K, long long d, long long row_stride, int vec_ok) {
+  constexpr int V = Slab<T>::V;
+  if (pred != nullptr && *pred == 0) return;
+  const float kf = (float)K;
+  const long long nvec = (d + V - 1) / V;
+  for (long long vi = (long long)blockIdx.x * blockDim.x + threadIdx.x; vi < nvec;
+       vi += (long long)gridDim.x * blockDim.x) {
+    const long long j0 = vi * V;
+    float acc[V];
+#pragma unroll
+    for (int v = 0; v < V; ++v) acc[v] = 0.0f;
+    if (vec_ok && j0 + V <= d) {
+#pragma unroll 4
+      for (int k = 0; k < K; ++k) {
+        float x[V];
+        Slab<T>::load_vec(w + (long long)k * row_stride + j0, x);
+#pragma unroll
+        for (int v = 0; v < V; ++v) acc[v] += x[v];
+      }
+#pragma unroll
+      for (int v = 0; v < V; ++v) acc[v] = acc[v] / kf;
+      if (w_prev != nullptr) {
+        float old[V];
+        load_f32_vec<V>(w_t0 + j0, old);
+        store_f32_vec<V>(w_prev + j0, old);
+      }
+      store_f32_vec<V>(w_t0 + j0, acc);
+#pragma unroll 4
+      for (int k = 0; k < K; ++k) Slab<T>::store_vec(w + (long long)k * row_stride + j0, acc);
+    } else {
+      for (int v = 0; v < V; ++v) {
+        const long long j = j0 + v;
+        if (j >= d) break;
+        float a = 0.0f;
+        for (int k = 0; k < K; ++k) a += Slab<T>::load_one(w + (long long)k * row_stride + j);
+        a = a / kf;
+        if (w_prev != nullptr) w_prev[j] = w_t0[j];
+        w_t0[j] = a;
+        for (int k = 0; k < K; ++k) Slab<T>::store_one(w + (long long)k * row_stride + j, a);
+      }
+    }
+  }
+}
+
+// ----------------------------------------------------------------------------------------
+// Section 3.2: xi = (w_t0 - w_prev) / ||w_t0 - w_prev||.  Pass 1: per-workgroup partial of
+// the squared norm; pass 2: every workgroup re-sums the partials in the same fixed order
+// and scales its share of the difference.
+// ----------------------------------------------------------------------------------------
+__global__ void __launch_bounds__(kSmallThreads)
+xi_norm_kernel(const float* __restrict__ w_t0, const float* __restrict__ w_prev,
+               const int32_t* __restrict__ pred, long long d, double* __restrict__ partial) {
+  __shared__ double scratch[kSmallThreads / 64];
+  if (pred != nullptr && *pred == 0) return;
+  double acc = 0.0;
+  const long long step = (long long)gridDim.x * blockDim.x;
+  long long j = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  while (j < d) {
+    float part = 0.0f;                       // a short fp32 run, then fp64
+#pragma unroll
+    for (int t = 0; t < 8; ++t) {
+      if (j < d) { const float df = w_t0[j] - w_prev[j]; part = fmaf(df, df, part); }
+      j += step;
+    }
+    acc += (double)part;
+  }
+  const double s = block_sum(acc, scratch);
+  if (threadIdx.x == 0) partial[blockIdx.x] = s;
+}
+
+__global__ void __launch_bounds__(kSmallThreads)
+xi_scale_kernel(const float* __restrict__ w_t0, const float* __restrict__ w_prev,
+                float* __restrict__ xi, const int32_t* __restrict__ pred, long long d,
+                const double* __restrict__ partial, int npartial) {
+  __shared__ double scratch[kSmallThreads / 64];
+  __shared__ float scale_sh;
+  if (pred != nullptr && *pred == 0) return;
+  double acc = 0.0;
+  for (int t = threadIdx.x; t < npartial; t += blockDim.x) acc += partial[t];
+  const double tot = block_sum(acc, scratch);
+  if (threadIdx.x == 0) {
+    const double nrm = sqrt(tot);
+    scale_sh = (nrm > 0.0 && isfinite(nrm)) ? (float)(1.0 / nrm) : 0.0f;
+  }
+  __syncthreads();
+  const float scale = scale_sh;
+  for (long long j = (long long)blockIdx.x * blockDim.x + threadIdx.x; j < d;
+       j += (long long)gridDim.x * blockDim.x) {
+    const float df = w_t0[j] - w_prev[j];
+    xi[j] = (scale == 0.0f) ? 0.0f : df * scale;
+  }
+}
+
+}  // namespace fda

@@ -1,0 +1,6 @@
+// State kernels: fda::bf16_t slab, 64-bit integer sketch cells, worker slots 1..4.
+#define FDA_TU_TYPE fda::bf16_t
+#define FDA_TU_FX true
+#define FDA_TU_HI 0
+#define FDA_TU_NAME launch_state_bf16_fx_lo
+#include "fda_state_tu.inc"

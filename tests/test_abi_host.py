@@ -89,7 +89,7 @@ def test_plan_of_the_five_configs(name):
     p = F.fda_plan(desc, 256, 163840)
     assert p.state_floats == 2 + c["l"] * c["m"]
     assert p.worker_groups * p.workers_per_group >= c["K"]
-    assert p.workers_per_group <= 16
+    assert p.workers_per_group <= 8
     assert p.partitions % 8 == 0 and p.partitions >= 8
     assert p.lds_bytes <= 163840
     assert p.partitions * p.chunk >= c["d"]
@@ -106,4 +106,4 @@ def test_plan_of_the_five_configs(name):
 def test_plan_linear_only_needs_no_sketch():
     desc, keep = make_desc(60, 10**6, F.FDA_F32, F.FDA_VARIANT_LINEAR)
     p = F.fda_plan(desc, 256, 163840)
-    assert p.state_floats == 2 and p.worker_groups == 4 and p.row_groups == 1
+    assert p.state_floats == 2 and p.worker_groups == 10 and p.row_groups == 1
