@@ -180,6 +180,17 @@ def ams_sketch_abs(v: np.ndarray, coef: np.ndarray, m: int) -> np.ndarray:
     return out
 
 
+def ams_sketch_counts(d: int, coef: np.ndarray, m: int) -> np.ndarray:
+    """Number of coordinates of [0, d) that fall into each cell of each row."""
+    l = coef.shape[0]
+    j = np.arange(d, dtype=np.uint64)
+    out = np.zeros((l, m), np.float64)
+    for i in range(l):
+        bucket, _ = bucket_and_sign(coef[i], j, m)
+        out[i] = np.bincount(bucket, minlength=m)
+    return out
+
+
 def m2_estimate(sk: np.ndarray) -> float:
     """M2(sk) = median over rows of the row's squared L2 norm (Section 3.1)."""
     row_sq = np.einsum("ib,ib->i", sk, sk)
@@ -197,12 +208,15 @@ def local_state(w, dtype: str, w_t0: np.ndarray, xi, coef, m: int):
       p[K]        <xi, u_k>        (None if xi is None)  (Thm 2)
       p_abs[K]    sum_j |xi_j u_kj|
       sk[K,l,m]   sk(u_k)          (None if coef is None) (Thm 1)
-      sk_abs[K,l,m]
+      sk_abs[K,l,m]   per cell sum of |u_kj|
+      sk_cnt[l,m]     per cell number of coordinates
+      u_mean_abs[K]   mean_j |u_kj|
     """
     w64 = widen(w, dtype)
     w0 = np.asarray(w_t0, np.float32).astype(np.float64)
     u = drift(w64, w0)
-    out = {"n": sq_norms(u), "p": None, "p_abs": None, "sk": None, "sk_abs": None}
+    out = {"n": sq_norms(u), "p": None, "p_abs": None, "sk": None, "sk_abs": None, "sk_cnt": None,
+           "u_mean_abs": np.abs(u).mean(axis=1)}
     if xi is not None:
         x = np.asarray(xi, np.float32).astype(np.float64)
         out["p"] = projections(u, x)
@@ -211,6 +225,7 @@ def local_state(w, dtype: str, w_t0: np.ndarray, xi, coef, m: int):
         K = u.shape[0]
         out["sk"] = np.stack([ams_sketch(u[k], coef, m) for k in range(K)])
         out["sk_abs"] = np.stack([ams_sketch_abs(u[k], coef, m) for k in range(K)])
+        out["sk_cnt"] = ams_sketch_counts(u.shape[1], coef, m)
     return out
 
 

@@ -14,11 +14,13 @@ CSRC = os.path.join(PKG, "csrc")
 LIB_DIR = os.path.join(PKG, "lib")
 OBJ_DIR = os.path.join(PKG, "_build")
 LIB_PATH = os.path.join(LIB_DIR, "libfda.so")
-UNITS = ["fda_api"] + ["fda_state_%s_%s_%s" % (t, c, h) for t in ("f32", "bf16")
-                       for c in ("fx", "f64") for h in ("lo", "hi")]
+UNITS = (["fda_api"] +
+         ["fda_state_narrow_%s_kc%d" % (t, k) for t in ("f32", "bf16") for k in (1, 2, 3, 4, 5, 6, 8)] +
+         ["fda_state_wide_%s_%s" % (t, c) for t in ("f32", "bf16") for c in ("i64", "f64")])
 SOURCES = [os.path.join(CSRC, u + ".hip") for u in UNITS]
 DEPENDS = SOURCES + [os.path.join(CSRC, n) for n in
-                     ("fda_kernels.hpp", "fda_small_kernels.hpp", "fda_state_launch.hpp", "fda_state_tu.inc")] + \
+                     ("fda_kernels.hpp", "fda_small_kernels.hpp", "fda_state_launch.hpp", "fda_state_narrow.inc",
+                      "fda_state_wide.inc")] + \
     [os.path.join(ROOT, "include", "fda.h")]
 
 
@@ -48,8 +50,10 @@ def build_library(verbose: bool = False) -> str:
     os.makedirs(OBJ_DIR, exist_ok=True)
     objs = [os.path.join(OBJ_DIR, u + ".o") for u in UNITS]
     cmds = [[hipcc()] + flags() + ["-c", src, "-o", obj] for src, obj in zip(SOURCES, objs)]
+    # the units with the most worker slots take longest: start them first
+    order = sorted(range(len(cmds)), key=lambda i: -int(UNITS[i].rsplit("kc", 1)[1]) if "kc" in UNITS[i] else 0)
     with ThreadPoolExecutor(max_workers=min(len(cmds), os.cpu_count() or 4)) as pool:
-        list(pool.map(_run, cmds))
+        list(pool.map(_run, [cmds[i] for i in order]))
     link = [hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB_PATH] + objs
     _run(link)
     if verbose:

@@ -43,10 +43,17 @@ constexpr int64_t kAlign = 256;
 
 int64_t round_up(int64_t x, int64_t a) { return (x + a - 1) / a * a; }
 
+// How one state pass is spread over the chip for a given sketch-cell size.
+struct Split {
+  int G, R, kcnt_max, rcnt_max, KC, LR, P, stride;
+  int64_t chunk, lds_bytes;
+};
 struct Plan {
-  int G, R, kcnt_max, rcnt_max, KC, LR, P, stride, vec;   // vec = elements per 16-byte slab load
-  int64_t chunk, lds_bytes, cells, S;
-  int64_t off_np, off_sk, off_xi, off_scale, off_smax, off_ssum, off_nmax, off_table, dpad, ws_bytes;
+  Split narrow;     // 32-bit cells: the pass every call runs
+  Split wide;       // 8-byte cells: the 64-bit integer and fp64 passes
+  int vec;          // elements per 16-byte slab load
+  int64_t cells, S, dpad;
+  int64_t off_np, off_sk, off_xi, off_scale, off_smax, off_ssum, off_nmax, off_table, ws_bytes;
 };
 
 int validate(const fda_desc* d) {
@@ -75,58 +82,69 @@ int validate(const fda_desc* d) {
   return FDA_OK;
 }
 
-int make_plan(const fda_desc* d, int cus, int64_t lds_cu, Plan* pl) {
-  if (cus < 1 || lds_cu < 16384) return fail(FDA_EINVAL, "bad device description");
+int make_split(const fda_desc* d, int cus, int64_t lds_cu, int cell_bytes, Split* sp) {
   const bool sk = (d->variants & FDA_VARIANT_SKETCH) != 0;
-  pl->cells = sk ? (int64_t)d->l * d->m : 0;
-  pl->S = 2 + pl->cells;
-  pl->vec = d->dtype == FDA_F32 ? 4 : 8;
+  const int64_t cells = sk ? (int64_t)d->l * d->m : 0;
+  const int vec = fda::kStateV;
   // Split the K workers into G groups and the l sketch rows into R groups so that one
-  // workgroup's sketch (rows x m cells x worker slots, 8 bytes each) fits in LDS.  The kernel
-  // has KC worker slots and LR row slots (compile-time); slots a group does not fill still
-  // execute.  Every row group repeats the loads and the fixed-point conversion of its workers'
-  // elements; every workgroup decodes its rows' table entries and re-reads w_t0 / xi / table
-  // (through L2).  Pick the split with the least estimated vector-ALU work per coordinate.
+  // workgroup's sketch (rows x m cells x worker slots) fits in LDS.  The kernel has KC worker
+  // slots and LR row slots (compile-time); slots a group does not fill still execute.  Every
+  // row group repeats the loads and the fixed-point conversion of its workers' elements; every
+  // workgroup decodes its rows' table entries and re-reads w_t0 / xi / table (through L2).
+  // Pick the split with the least estimated vector-ALU work per coordinate.
   const int l = sk ? d->l : 1;
   double best = -1.0;
-  int bestG = 0, bestR = 0, bestKC = 0;
+  int bestG = 0, bestR = 0, bestKC = 0, bestLR = 0;
+  const bool narrow = cell_bytes == 4;
   for (int G = 1; G <= d->K; ++G) {
     const int kc = (d->K + G - 1) / G;
     int KC = 0;
-    for (int c : fda::kKCSet)
-      if (c >= kc) { KC = c; break; }
+    if (narrow) {
+      for (int c : fda::kKCSet)
+        if (c >= kc) { KC = c; break; }
+    } else {
+      for (int c : fda::kWideKCSet)
+        if (c >= kc) { KC = c; break; }
+    }
     if (KC == 0) continue;
     const int stride = (KC == 1) ? 1 : (KC | 1);
     for (int R = 1; R <= l; ++R) {
       const int rc = (l + R - 1) / R;
-      if (rc > fda::kMaxLR) continue;
-      const int64_t dummy = fda::kDummyCells;
-      if (pl->cells && ((int64_t)rc * d->m + dummy) * stride * 8 + kLdsReserve > lds_cu) continue;
+      int LR = 0;                                        // row slots of the kernel that would run
+      if (narrow) {
+        if (rc <= fda::kMaxLR && KC * rc <= fda::kMaxSlots) LR = rc;
+      } else {
+        for (int c : fda::kWideLRSet)
+          if (c >= rc) { LR = c; break; }
+      }
+      if (LR == 0) continue;
+      if (cells && ((int64_t)rc * d->m + fda::kDummyCells) * stride * cell_bytes + kLdsReserve > lds_cu)
+        continue;
       const double slots = (double)G * R * KC;           // element slots per coordinate
-      const double cost = slots * kElementCost + slots * rc * kAtomicCost +
-                          (double)G * R * rc * kDecodeCost +
-                          (double)G * R * (8 + 2 * rc) * kSharedByteCost + 1e-3 * G * R;
-      if (best < 0.0 || cost < best) { best = cost; bestG = G; bestR = R; bestKC = KC; }
+      const double cost = slots * kElementCost + slots * LR * kAtomicCost +
+                          (double)G * R * LR * kDecodeCost +
+                          (double)G * R * (8 + 2 * LR) * kSharedByteCost + 1e-3 * G * R;
+      if (best < 0.0 || cost < best) { best = cost; bestG = G; bestR = R; bestKC = KC; bestLR = LR; }
       break;   // a larger R only costs more for this G
     }
   }
   if (bestG == 0)
     return fail(FDA_ERANGE, "one row of an m = %d sketch does not fit in %lld bytes of LDS", d->m,
                 (long long)lds_cu);
-  pl->G = bestG;
-  pl->R = bestR;
-  pl->kcnt_max = (d->K + bestG - 1) / bestG;
-  pl->rcnt_max = (l + bestR - 1) / bestR;
-  pl->KC = bestKC;
-  pl->LR = pl->rcnt_max;
-  pl->stride = (pl->KC == 1) ? 1 : (pl->KC | 1);
-  const int64_t dummy_cells = pl->cells ? fda::kDummyCells : 0;
-  const int64_t sk_bytes = pl->cells ? ((int64_t)pl->rcnt_max * d->m + dummy_cells) * pl->stride * 8 : 0;
-  pl->lds_bytes = round_up(sk_bytes, 16) + kLdsReserve;
-  int occ = (int)(lds_cu / pl->lds_bytes);
+  sp->G = bestG;
+  sp->R = bestR;
+  sp->kcnt_max = (d->K + bestG - 1) / bestG;
+  sp->rcnt_max = (l + bestR - 1) / bestR;
+  sp->KC = bestKC;
+  sp->LR = bestLR;
+  sp->stride = (sp->KC == 1) ? 1 : (sp->KC | 1);
+  const int64_t sk_bytes =
+      cells ? ((int64_t)sp->rcnt_max * d->m + fda::kDummyCells) * sp->stride * cell_bytes : 0;
+  sp->lds_bytes = round_up(sk_bytes, 16) + kLdsReserve;
+  int occ = (int)(lds_cu / sp->lds_bytes);
   if (occ > 2) occ = 2;
   if (occ < 1) occ = 1;
-  const int64_t tile = (int64_t)fda::kStateThreads * pl->vec;
+  const int64_t tile = (int64_t)fda::kStateThreads * vec;
   // Partitions: all workgroups do the same amount of work, so the launch should fill the
   // resident slots a whole number of times.  Try 1..4 rounds and keep the best-filled one.
   const int64_t slots = (int64_t)cus * occ, gr = (int64_t)bestG * bestR;
@@ -141,30 +159,44 @@ int make_plan(const fda_desc* d, int cus, int64_t lds_cu, Plan* pl) {
   }
   const int64_t tiles = (d->d + tile - 1) / tile;
   if (P > round_up(tiles, 8)) P = round_up(tiles, 8);
-  pl->P = (int)P;
-  pl->chunk = round_up((d->d + P - 1) / P, tile);
+  sp->P = (int)P;
+  sp->chunk = round_up((d->d + P - 1) / P, tile);
+  return FDA_OK;
+}
+
+int make_plan(const fda_desc* d, int cus, int64_t lds_cu, Plan* pl) {
+  if (cus < 1 || lds_cu < 16384) return fail(FDA_EINVAL, "bad device description");
+  const bool sk = (d->variants & FDA_VARIANT_SKETCH) != 0;
+  pl->cells = sk ? (int64_t)d->l * d->m : 0;
+  pl->S = 2 + pl->cells;
+  pl->vec = d->dtype == FDA_F32 ? 4 : 8;
+  int rc = make_split(d, cus, lds_cu, 8, &pl->wide);     // the stricter one first: its error message
+  if (rc != FDA_OK) return rc;
+  rc = make_split(d, cus, lds_cu, 4, &pl->narrow);
+  if (rc != FDA_OK) return rc;
+  const int64_t Pmax = pl->narrow.P > pl->wide.P ? pl->narrow.P : pl->wide.P;
   pl->off_np = 0;
-  pl->off_sk = round_up(pl->off_np + P * d->K * 2 * 8, kAlign);
-  pl->off_xi = round_up(pl->off_sk + P * d->K * pl->cells * 8, kAlign);
+  pl->off_sk = round_up(pl->off_np + (int64_t)pl->narrow.P * d->K * 2 * 8, kAlign);
+  pl->off_xi = round_up(pl->off_sk + Pmax * d->K * pl->cells * 8, kAlign);
   pl->off_scale = round_up(pl->off_xi + kXiBlocks * 8, kAlign);
   pl->off_smax = round_up(pl->off_scale + (int64_t)sizeof(fda::ScaleInfo), kAlign);
   pl->off_ssum = round_up(pl->off_smax + kScaleBlocks * 4, kAlign);
   pl->off_nmax = round_up(pl->off_ssum + kScaleBlocks * 8, kAlign);
-  pl->off_table = round_up(pl->off_nmax + 4, kAlign);
+  pl->off_table = round_up(pl->off_nmax + 8, kAlign);
   pl->dpad = round_up(d->d, 64);
   pl->ws_bytes = round_up(pl->off_table + (sk ? (int64_t)d->l * pl->dpad * 2 : 0), kAlign);
   return FDA_OK;
 }
 
 void export_plan(const Plan& pl, fda_plan_info* out) {
-  out->worker_groups = pl.G;
-  out->row_groups = pl.R;
-  out->rows_per_group = pl.rcnt_max;
-  out->workers_per_group = pl.kcnt_max;
-  out->partitions = pl.P;
+  out->worker_groups = pl.narrow.G;
+  out->row_groups = pl.narrow.R;
+  out->rows_per_group = pl.narrow.rcnt_max;
+  out->workers_per_group = pl.narrow.kcnt_max;
+  out->partitions = pl.narrow.P;
   out->threads = fda::kStateThreads;
-  out->chunk = pl.chunk;
-  out->lds_bytes = pl.lds_bytes;
+  out->chunk = pl.narrow.chunk;
+  out->lds_bytes = pl.narrow.lds_bytes;
   out->workspace_bytes = pl.ws_bytes;
   out->state_floats = pl.S;
 }
@@ -182,18 +214,28 @@ int device_shape(int* cus, int64_t* lds) {
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
 
-// The state kernels are instantiated in eight translation units (fda_state_*.hip), by slab
-// type, cell type and worker-slot count, so that they compile in parallel.
-int dispatch_any(int dtype, int KC, int LR, bool fx, const fda::StateParams* prm, size_t lds,
-                 hipStream_t st) {
-  const bool hi = KC > 4;
-  hipError_t e;
-  if (dtype == FDA_F32) {
-    if (fx) e = hi ? fda::launch_state_f32_fx_hi(KC, LR, prm, lds, st) : fda::launch_state_f32_fx_lo(KC, LR, prm, lds, st);
-    else e = hi ? fda::launch_state_f32_f64_hi(KC, LR, prm, lds, st) : fda::launch_state_f32_f64_lo(KC, LR, prm, lds, st);
+// Route a launch (or, with prm == nullptr, the LDS-limit setup) to the translation unit that
+// holds the kernel for this slab type, cell kind and shape.
+int dispatch_any(int dtype, int cell, const Split& sp, const fda::StateParams* prm, hipStream_t st) {
+  const int KC = sp.KC, LR = sp.LR;
+  const size_t lds = (size_t)sp.lds_bytes;
+  hipError_t e = hipErrorInvalidValue;
+  if (cell == fda::kCellI32) {
+#define FDA_CASE(t, kc) case kc: e = fda::launch_narrow_##t##_kc##kc(LR, prm, lds, st); break
+    if (dtype == FDA_F32) {
+      switch (KC) { FDA_CASE(f32, 1); FDA_CASE(f32, 2); FDA_CASE(f32, 3); FDA_CASE(f32, 4);
+                    FDA_CASE(f32, 5); FDA_CASE(f32, 6); FDA_CASE(f32, 8); }
+    } else {
+      switch (KC) { FDA_CASE(bf16, 1); FDA_CASE(bf16, 2); FDA_CASE(bf16, 3); FDA_CASE(bf16, 4);
+                    FDA_CASE(bf16, 5); FDA_CASE(bf16, 6); FDA_CASE(bf16, 8); }
+    }
+#undef FDA_CASE
+  } else if (dtype == FDA_F32) {
+    e = cell == fda::kCellI64 ? fda::launch_wide_f32_i64(KC, LR, prm, lds, st)
+                              : fda::launch_wide_f32_f64(KC, LR, prm, lds, st);
   } else {
-    if (fx) e = hi ? fda::launch_state_bf16_fx_hi(KC, LR, prm, lds, st) : fda::launch_state_bf16_fx_lo(KC, LR, prm, lds, st);
-    else e = hi ? fda::launch_state_bf16_f64_hi(KC, LR, prm, lds, st) : fda::launch_state_bf16_f64_lo(KC, LR, prm, lds, st);
+    e = cell == fda::kCellI64 ? fda::launch_wide_bf16_i64(KC, LR, prm, lds, st)
+                              : fda::launch_wide_bf16_f64(KC, LR, prm, lds, st);
   }
   if (e == hipErrorInvalidValue)
     return fail(FDA_EINVAL, "internal: no state kernel for %d workers x %d rows per workgroup", KC, LR);
@@ -310,9 +352,10 @@ int fda_create(fda_ctx** ctx, const fda_desc* desc, void* workspace, size_t work
     delete c;
     return fail(FDA_EHIP, "hipGetDevice failed");
   }
-  rc = dispatch_any(desc->dtype, pl.KC, pl.LR, true, nullptr, (size_t)pl.lds_bytes, nullptr);
+  rc = dispatch_any(desc->dtype, fda::kCellI32, pl.narrow, nullptr, nullptr);
   if (rc == FDA_OK && (desc->variants & FDA_VARIANT_SKETCH)) {
-    rc = dispatch_any(desc->dtype, pl.KC, pl.LR, false, nullptr, (size_t)pl.lds_bytes, nullptr);
+    rc = dispatch_any(desc->dtype, fda::kCellI64, pl.wide, nullptr, nullptr);
+    if (rc == FDA_OK) rc = dispatch_any(desc->dtype, fda::kCellF64, pl.wide, nullptr, nullptr);
     if (rc == FDA_OK &&
         hipFuncSetAttribute(reinterpret_cast<const void*>(fda::cell_count_kernel),
                             hipFuncAttributeMaxDynamicSharedMemorySize, desc->m * 4) != hipSuccess)
@@ -390,32 +433,41 @@ int fda_local_state(fda_ctx* ctx, const void* w, const float* w_t0, const float*
     return fail(FDA_EINVAL, "pointer not aligned to its element type");
   hipStream_t st = static_cast<hipStream_t>(stream);
 
-  fda::StateParams prm;
-  prm.w = w; prm.w_t0 = w_t0; prm.xi = xi;
-  prm.row_stride = d.row_stride; prm.d = d.d; prm.chunk = pl.chunk;
-  prm.K = d.K; prm.l = sk ? d.l : 0; prm.m = sk ? d.m : 0;
-  prm.G = pl.G; prm.R = pl.R; prm.P = pl.P; prm.stride = pl.stride;
-  prm.do_lin = lin; prm.do_sk = sk;
-  prm.vec_ok = aligned16(w) && aligned16(w_t0) && (!lin || aligned16(xi)) &&
-               (d.row_stride * esz) % 16 == 0;
-  prm.part_np = reinterpret_cast<double*>(ctx->ws + pl.off_np);
-  prm.part_sk = ctx->ws + pl.off_sk;
-  prm.scale = reinterpret_cast<fda::ScaleInfo*>(ctx->ws + pl.off_scale);
-  prm.table = reinterpret_cast<const uint16_t*>(ctx->ws + pl.off_table);
-  prm.dpad = pl.dpad;
+  auto params_for = [&](const Split& sp) {
+    fda::StateParams prm;
+    prm.w = w; prm.w_t0 = w_t0; prm.xi = xi;
+    prm.row_stride = d.row_stride; prm.d = d.d; prm.chunk = sp.chunk;
+    prm.K = d.K; prm.l = sk ? d.l : 0; prm.m = sk ? d.m : 0;
+    prm.G = sp.G; prm.R = sp.R; prm.P = sp.P; prm.stride = sp.stride;
+    prm.do_lin = lin; prm.do_sk = sk;
+    prm.vec_ok = aligned16(w) && aligned16(w_t0) && (!lin || aligned16(xi)) &&
+                 (d.row_stride * esz) % 16 == 0;
+    prm.part_np = reinterpret_cast<double*>(ctx->ws + pl.off_np);
+    prm.part_sk = ctx->ws + pl.off_sk;
+    prm.scale = reinterpret_cast<fda::ScaleInfo*>(ctx->ws + pl.off_scale);
+    prm.table = reinterpret_cast<const uint16_t*>(ctx->ws + pl.off_table);
+    prm.dpad = pl.dpad;
+    return prm;
+  };
+  const fda::StateParams prm32 = params_for(pl.narrow);
+  const fda::StateParams prm64 = params_for(pl.wide);
 
   if (sk) {
-    // fixed-point unit for this call, from a sample of the drifts; also clears the overflow flag
     float* smax = reinterpret_cast<float*>(ctx->ws + pl.off_smax);
     double* ssum = reinterpret_cast<double*>(ctx->ws + pl.off_ssum);
     unsigned int* nmax = reinterpret_cast<unsigned int*>(ctx->ws + pl.off_nmax);
     if (!ctx->counted) {
-      // once per context: the largest number of coordinates any workgroup puts in one cell
-      hipLaunchKernelGGL(fda::clear_u32_kernel, dim3(1), dim3(64), 0, st, nmax);
+      // once per context: the largest number of coordinates any workgroup puts in one cell,
+      // for the partitioning of the 32-bit pass ([0]) and of the 8-byte passes ([1]) ...
+      hipLaunchKernelGGL(fda::clear_u32_kernel, dim3(1), dim3(64), 0, st, nmax, 2);
       FDA_HIP(hipGetLastError());
-      hipLaunchKernelGGL(fda::cell_count_kernel, dim3(pl.P * d.l), dim3(fda::kStateThreads),
-                         (size_t)d.m * 4, st, ctx->coef, d.l, d.m, (long long)d.d, (long long)pl.chunk,
-                         nmax);
+      hipLaunchKernelGGL(fda::cell_count_kernel, dim3(pl.narrow.P * d.l), dim3(fda::kStateThreads),
+                         (size_t)d.m * 4, st, ctx->coef, d.l, d.m, (long long)d.d,
+                         (long long)pl.narrow.chunk, nmax);
+      FDA_HIP(hipGetLastError());
+      hipLaunchKernelGGL(fda::cell_count_kernel, dim3(pl.wide.P * d.l), dim3(fda::kStateThreads),
+                         (size_t)d.m * 4, st, ctx->coef, d.l, d.m, (long long)d.d,
+                         (long long)pl.wide.chunk, nmax + 1);
       FDA_HIP(hipGetLastError());
       // ... and the hash of every (row, coordinate), tabulated
       const long long groups = pl.dpad / 8;
@@ -426,6 +478,7 @@ int fda_local_state(fda_ctx* ctx, const void* w, const float* w_t0, const float*
       FDA_HIP(hipGetLastError());
       ctx->counted = true;
     }
+    // fixed-point units for this call, from a sample of the drifts; also clears the flags
     const int samples = (int)(d.d < kScaleSamples ? d.d : kScaleSamples);
     if (d.dtype == FDA_F32)
       hipLaunchKernelGGL(fda::scale_sample_kernel<float>, dim3(kScaleBlocks), dim3(fda::kSmallThreads), 0,
@@ -437,7 +490,7 @@ int fda_local_state(fda_ctx* ctx, const void* w, const float* w_t0, const float*
                          (long long)d.d, (long long)d.row_stride, samples, smax, ssum);
     FDA_HIP(hipGetLastError());
     hipLaunchKernelGGL(fda::scale_finalize_kernel, dim3(1), dim3(64), 0, st, smax, ssum, kScaleBlocks,
-                       (long long)samples * d.K, nmax, prm.scale);
+                       (long long)samples * d.K, nmax, prm32.scale);
     FDA_HIP(hipGetLastError());
   }
 
@@ -450,22 +503,25 @@ int fda_local_state(fda_ctx* ctx, const void* w, const float* w_t0, const float*
     slot = ctx->prof_pending;
     FDA_HIP(hipEventRecord(ctx->prof_start[slot], st));
   }
-  int rc = dispatch_any(d.dtype, pl.KC, pl.LR, true, &prm, (size_t)pl.lds_bytes, st);
+  int rc = dispatch_any(d.dtype, fda::kCellI32, pl.narrow, &prm32, st);
   if (rc != FDA_OK) return rc;
   if (slot >= 0) {
     FDA_HIP(hipEventRecord(ctx->prof_stop[slot], st));
     ctx->prof_pending = slot + 1;
   }
   if (sk) {
-    // runs to completion only if the integer path met a drift it could not represent
-    rc = dispatch_any(d.dtype, pl.KC, pl.LR, false, &prm, (size_t)pl.lds_bytes, st);
+    // these two return at once unless the pass before them could not represent the drifts
+    rc = dispatch_any(d.dtype, fda::kCellI64, pl.wide, &prm64, st);
+    if (rc != FDA_OK) return rc;
+    rc = dispatch_any(d.dtype, fda::kCellF64, pl.wide, &prm64, st);
     if (rc != FDA_OK) return rc;
   }
 
   const long long total = (long long)d.K * pl.S;
   const int blocks = (int)((total + 31) / 32);
   hipLaunchKernelGGL(fda::merge_kernel, dim3(blocks), dim3(fda::kSmallThreads), 0, st,
-                     prm.part_np, prm.part_sk, prm.scale, state, d.K, (int)pl.cells, pl.P);
+                     prm32.part_np, prm32.part_sk, prm32.scale, state, d.K, (int)pl.cells,
+                     pl.narrow.P, pl.wide.P);
   FDA_HIP(hipGetLastError());
   return FDA_OK;
 }

@@ -26,14 +26,21 @@ struct HashCoef {
   uint32_t c[FDA_MAX_SKETCH_ROWS][2][4];     // [row][bucket|sign][power of j]
 };
 
-// Fixed-point scale of one fda_local_state call, chosen on the device from a sample of the
-// drifts (scale_*_kernel) and read by the state and merge kernels.
+// Which kind of LDS sketch cell a state kernel accumulates into.
+enum CellKind { kCellI32 = 0, kCellI64 = 1, kCellF64 = 2 };
+
+// Fixed-point scales of one fda_local_state call, chosen on the device from a sample of the
+// drifts (scale_*_kernel) and read by the state and merge kernels, and the flags that send a
+// call from the 32-bit integer cells to the 64-bit ones and from those to fp64 cells.
 struct ScaleInfo {
-  double S;               // 2^e: a drift u enters the sketch as the integer round(u * S)
-  double invS;            // 2^-e
-  float bound;            // every |u| must stay below this for the integer path to be valid
-  int overflow;           // set by the integer path when some |u| did not; selects the fp64 path
-  int pad[2];
+  double S64, invS64;     // 64-bit cells: a drift u is added as the integer round(u * S64)
+  double invS32;
+  float S32;              // 32-bit cells: round(u * S32)
+  float bound32;          // every |u| must stay below this for the 32-bit cells to be valid
+  float bound64;          // ... and below this for the 64-bit cells
+  int flag32;             // set: the 32-bit result is void (range, or a cell wrapped) -> 64-bit pass
+  int overflow64;         // set: the 64-bit cells cannot hold the drifts either -> fp64 pass
+  int pad;
 };
 
 struct StateParams {
@@ -49,12 +56,12 @@ struct StateParams {
   int G;                  // worker groups
   int R;                  // sketch-row groups (workgroups of one worker group share the data)
   int P;                  // coordinate partitions, multiple of 8
-  int stride;             // LDS 8-byte words per sketch cell (>= workers of the group)
+  int stride;             // LDS cells per bucket (>= worker slots of the group, odd)
   int do_lin;
   int do_sk;
   int vec_ok;             // all pointers / strides allow 16-byte loads
   double* part_np;        // [P][K][2]
-  void* part_sk;          // [P][K][l*m] 8-byte words: int64 (integer path) or double (fp64 path)
+  void* part_sk;          // [P][K][l*m] 8-byte words: int64 (integer cells) or double (fp64 cells)
   ScaleInfo* scale;
   const uint16_t* table;  // [l][dpad] tabulated hash
   long long dpad;
@@ -152,19 +159,20 @@ constexpr double kRoundMagic = 6755399441055744.0;       // 1.5 * 2^52
 
 // One lane's share of a tile, as loaded: V coordinates of w_t0, xi, of each worker's row and
 // of each sketch row's hash table.
+constexpr int kStateV = 4;       // coordinates a lane owns per tile (fp32: 16 bytes, bf16: 8 bytes)
 template <typename T, int KC, int LR>
 struct TileRaw {
-  static constexpr int V = Slab<T>::V;
+  static constexpr int V = kStateV;
+  static constexpr int kWords = V * (int)sizeof(T) / 4;
   float w0[V];
   float x[V];
-  uint32_t w[KC][4];            // 16 bytes of row k: 4 fp32 or 8 bf16
+  uint32_t w[KC][kWords];       // V elements of row k: 4 fp32 or 4 bf16
   uint32_t tab[LR][V / 2];      // V 16-bit table entries per sketch row
 };
-template <typename T> __device__ __forceinline__ float raw_elem(const uint32_t (&r)[4], int v);
-template <> __device__ __forceinline__ float raw_elem<float>(const uint32_t (&r)[4], int v) {
+__device__ __forceinline__ float raw_elem(const uint32_t (&r)[4], int v) {      // fp32
   return __uint_as_float(r[v]);
 }
-template <> __device__ __forceinline__ float raw_elem<bf16_t>(const uint32_t (&r)[4], int v) {
+__device__ __forceinline__ float raw_elem(const uint32_t (&r)[2], int v) {      // bf16
   return __uint_as_float((v & 1) ? (r[v >> 1] & 0xffff0000u) : (r[v >> 1] << 16));
 }
 
@@ -184,28 +192,37 @@ template <> __device__ __forceinline__ float raw_elem<bf16_t>(const uint32_t (&r
 // region behind the sketch.  (Tests inside the unrolled loops cost more scalar branching
 // than the whole useful work.)
 //
-// How the sketch cells accumulate is dictated by the LDS of gfx950, measured per CU and
-// clock on random cells: ds_add_f32 0.33 lanes, ds_add_f64 2.8, ds_add_u64 5.5.  So:
-//   FX = true   the cells are 64-bit integers: u is added as round(u * 2^e) (ds_add_u64),
-//               with 2^e chosen per call from a sample of the drifts (scale_finalize_kernel).
-//               Integer addition is exact, so the result does not depend on the order in
-//               which lanes and workgroups add: run-to-run bit-identical.  A drift at or
-//               above ScaleInfo::bound cannot be represented; the lane that meets one raises
-//               ScaleInfo::overflow.
-//   FX = false  the same pass with fp64 cells (ds_add_f64), sketch only; it runs only when
-//               ScaleInfo::overflow is set and then replaces the sketch partials.
+// How the sketch cells accumulate is dictated by the LDS of gfx950.  Measured per CU and clock
+// on random cells: ds_add_f32 0.33 lanes, ds_add_f64 2.8, ds_add_u64 5.5, ds_add_rtn_u32 10.4.
+// So the cells are integers and a drift u is added as round(u * 2^e), with 2^e chosen per call
+// from a sample of the drifts (scale_finalize_kernel).  Integer addition is exact: the result
+// does not depend on the order in which lanes and workgroups add, run-to-run bit-identical.
+//   kCellI32  32-bit cells, started at 2^31; every add is below 2^30 in magnitude and returns
+//             the old value, which must lie in [2^30, 3*2^30): then no add can have wrapped.
+//             The mean sampled |u| maps to about 2^18.  Runs on every call and also produces
+//             the scalar components.  A value outside the band, or a drift at or above
+//             ScaleInfo::bound32, raises ScaleInfo::flag32.
+//   kCellI64  64-bit cells, sketch only, runs only when flag32 is set.  The sampled maximum
+//             maps to qbits - 13 bits, qbits chosen from the exact largest number of terms
+//             of a cell so that no cell can overflow.  A drift at or above bound64 raises
+//             ScaleInfo::overflow64 (noticed by the first pass, which sees every drift).
+//   kCellF64  fp64 cells (ds_add_f64), sketch only, runs only when overflow64 is set.
 // ----------------------------------------------------------------------------------------
 constexpr int kDummyCells = 64;              // cells of the dummy region (power of two)
 
-template <typename T, int KC, int LR, bool FX>
+template <typename T, int KC, int LR, int CELL>
 __global__ void __launch_bounds__(kStateThreads)
 state_kernel(const StateParams prm) {
-  constexpr int V = Slab<T>::V;
+  constexpr int V = kStateV;
   constexpr long long kTile = (long long)kStateThreads * V;
   using Tile = TileRaw<T, KC, LR>;
   extern __shared__ __align__(16) unsigned char lds_raw[];
-  if constexpr (!FX) {
-    if (prm.scale->overflow == 0) return;
+  constexpr int kCellBytes = (CELL == kCellI32) ? 4 : 8;
+  if constexpr (CELL == kCellI64) {
+    if (prm.scale->flag32 == 0 || prm.scale->overflow64 != 0) return;
+  }
+  if constexpr (CELL == kCellF64) {
+    if (prm.scale->overflow64 == 0) return;
   }
 
   // XCD-aware placement: consecutive workgroup ids go round-robin over the 8 XCDs, so the
@@ -220,25 +237,30 @@ state_kernel(const StateParams prm) {
   int kstart, kcnt, rstart = 0, rcnt = 0;
   group_range(prm.K, prm.G, g, &kstart, &kcnt);
   if (prm.do_sk) group_range(prm.l, prm.R, r, &rstart, &rcnt);
-  const bool scalars = FX && (r == 0);
+  const bool scalars = (CELL == kCellI32) && (r == 0);
   bool sketch = prm.do_sk != 0;
-  if constexpr (FX) {
-    // the fp64 pass will redo every sketch partial: only the scalar components are left to do
-    if (sketch && prm.scale->overflow != 0) {
+  if constexpr (CELL == kCellI32) {
+    // a later pass will redo every sketch partial: only the scalar components are left to do
+    if (sketch && prm.scale->flag32 != 0) {
       if (!scalars) return;
       sketch = false;
     }
   }
 
-  const uint32_t stride_bytes = (uint32_t)prm.stride * 8u;
+  const uint32_t stride_bytes = (uint32_t)prm.stride * kCellBytes;
   const int cells = rcnt * prm.m;                      // cells this workgroup owns
   const uint32_t dummy_base = (uint32_t)cells * stride_bytes;
-  const int lds_words = sketch ? (cells + kDummyCells) * prm.stride : 0;
-  unsigned long long* sk = reinterpret_cast<unsigned long long*>(lds_raw);
-  double* red = reinterpret_cast<double*>(lds_raw + (((size_t)lds_words * 8 + 15) & ~(size_t)15));
+  const int lds_cells = sketch ? (cells + kDummyCells) * prm.stride : 0;
+  double* red = reinterpret_cast<double*>(lds_raw + (((size_t)lds_cells * kCellBytes + 15) & ~(size_t)15));
 
   const int tid = threadIdx.x;
-  for (int t = tid; t < lds_words; t += kStateThreads) sk[t] = 0ull;   // integer 0 and 0.0
+  if constexpr (CELL == kCellI32) {
+    uint32_t* c32 = reinterpret_cast<uint32_t*>(lds_raw);
+    for (int t = tid; t < lds_cells; t += kStateThreads) c32[t] = 0x80000000u;   // mid-range
+  } else {
+    unsigned long long* c64 = reinterpret_cast<unsigned long long*>(lds_raw);
+    for (int t = tid; t < lds_cells; t += kStateThreads) c64[t] = 0ull;         // integer 0 and 0.0
+  }
   __syncthreads();
 
   double dn[KC], dp[KC];
@@ -270,9 +292,10 @@ state_kernel(const StateParams prm) {
   const float* const w0p = prm.w_t0;
   const float* const xip = lin ? prm.xi : prm.w_t0;   // without LinearFDA: any readable vector
 
-  double S = 1.0;
-  float bound = 0.0f, amax = 0.0f;
-  if (FX && prm.do_sk) { S = prm.scale->S; bound = prm.scale->bound; }
+  double S64 = 1.0;
+  float S32 = 1.0f, amax = 0.0f;
+  uint32_t wrapped = 0u;          // bit 31: an add of this lane found a 32-bit cell outside the safe band
+  if (prm.do_sk) { S64 = prm.scale->S64; S32 = prm.scale->S32; }
 
   // SC: this workgroup also produces the scalar components; SK: it accumulates sketch rows.
   auto run = [&](auto sc_tag, auto sk_tag) {
@@ -285,19 +308,19 @@ state_kernel(const StateParams prm) {
       if constexpr (SC) load_f32_vec<V>(xip + j0, t.x);
 #pragma unroll
       for (int k = 0; k < KC; ++k) {
-        const uint4 q = *reinterpret_cast<const uint4*>(wrow[k] + j0);
-        t.w[k][0] = q.x; t.w[k][1] = q.y; t.w[k][2] = q.z; t.w[k][3] = q.w;
+        if constexpr (sizeof(T) == 4) {
+          const uint4 q = *reinterpret_cast<const uint4*>(wrow[k] + j0);
+          t.w[k][0] = q.x; t.w[k][1] = q.y; t.w[k][2] = q.z; t.w[k][3] = q.w;
+        } else {
+          const uint2 q = *reinterpret_cast<const uint2*>(wrow[k] + j0);
+          t.w[k][0] = q.x; t.w[k][1] = q.y;
+        }
       }
       if constexpr (SK) {
 #pragma unroll
         for (int i = 0; i < LR; ++i) {
-          if constexpr (V == 4) {
-            const uint2 q = *reinterpret_cast<const uint2*>(trow[i] + j0);
-            t.tab[i][0] = q.x; t.tab[i][1] = q.y;
-          } else {
-            const uint4 q = *reinterpret_cast<const uint4*>(trow[i] + j0);
-            t.tab[i][0] = q.x; t.tab[i][1] = q.y; t.tab[i][2] = q.z; t.tab[i][3] = q.w;
-          }
+          const uint2 q = *reinterpret_cast<const uint2*>(trow[i] + j0);
+          t.tab[i][0] = q.x; t.tab[i][1] = q.y;
         }
       }
     };
@@ -312,13 +335,13 @@ state_kernel(const StateParams prm) {
 #pragma unroll
       for (int k = 0; k < KC; ++k) {
         const T* row = wrow[k] + j0;
-        if constexpr (V == 4) {
+        if constexpr (sizeof(T) == 4) {
 #pragma unroll
           for (int v = 0; v < 4; ++v)
             t.w[k][v] = (j0 + v < dlim) ? __float_as_uint(Slab<T>::load_one(row + v)) : 0u;
         } else {
 #pragma unroll
-          for (int v = 0; v < 8; v += 2) {
+          for (int v = 0; v < 4; v += 2) {
             const uint16_t* h = reinterpret_cast<const uint16_t*>(row);
             const uint32_t lo = (j0 + v < dlim) ? (uint32_t)h[v] : 0u;
             const uint32_t hi = (j0 + v + 1 < dlim) ? (uint32_t)h[v + 1] : 0u;
@@ -330,13 +353,8 @@ state_kernel(const StateParams prm) {
         // the table is padded to dpad (a multiple of 64 coordinates): always a whole vector
 #pragma unroll
         for (int i = 0; i < LR; ++i) {
-          if constexpr (V == 4) {
-            const uint2 q = *reinterpret_cast<const uint2*>(trow[i] + j0);
-            t.tab[i][0] = q.x; t.tab[i][1] = q.y;
-          } else {
-            const uint4 q = *reinterpret_cast<const uint4*>(trow[i] + j0);
-            t.tab[i][0] = q.x; t.tab[i][1] = q.y; t.tab[i][2] = q.z; t.tab[i][3] = q.w;
-          }
+          const uint2 q = *reinterpret_cast<const uint2*>(trow[i] + j0);
+          t.tab[i][0] = q.x; t.tab[i][1] = q.y;
         }
       }
     };
@@ -345,47 +363,85 @@ state_kernel(const StateParams prm) {
       float sn[KC], sp[KC];
 #pragma unroll
       for (int k = 0; k < KC; ++k) { sn[k] = 0.0f; sp[k] = 0.0f; }
+      uint32_t pend_old[KC];                  // 32-bit cells: the last batch not yet examined
+      bool have_pending = false;
 #pragma unroll
       for (int v = 0; v < V; ++v) {
         float u[KC];
 #pragma unroll
         for (int k = 0; k < KC; ++k) {
-          u[k] = raw_elem<T>(t.w[k], v) - t.w0[v];
+          u[k] = raw_elem(t.w[k], v) - t.w0[v];
           if constexpr (SC) {
             sn[k] = fmaf(u[k], u[k], sn[k]);
             sp[k] = fmaf(t.x[v], u[k], sp[k]);
             amax = fmaxf(amax, fabsf(u[k]));
           }
         }
-        if constexpr (SK && FX) {
-          long long q[KC], nq[KC];
+        if constexpr (SK && CELL == kCellI32) {
+          uint32_t q[KC];
 #pragma unroll
-          for (int k = 0; k < KC; ++k) {
-            const double y = fma((double)u[k], S, kRoundMagic);             // round to integer
-            q[k] = __double_as_longlong(y) - __double_as_longlong(kRoundMagic);
-            nq[k] = -q[k];
-          }
+          for (int k = 0; k < KC; ++k) q[k] = (uint32_t)(int)rintf(u[k] * S32);
 #pragma unroll
           for (int i = 0; i < LR; ++i) {
             const uint32_t h = (v & 1) ? (t.tab[i][v >> 1] >> 16) : (t.tab[i][v >> 1] & 0xffffu);
             const uint32_t off = __umul24(h & rowmask[i], stride_bytes) + rowbase[i];
-            const bool neg = (h & 0x8000u) != 0;
-            unsigned long long* cell = reinterpret_cast<unsigned long long*>(lds_raw + off);
+            const uint32_t sgn = 0u - ((h >> 15) & 1u);                  // all ones for sign -1
+            uint32_t* cell = reinterpret_cast<uint32_t*>(lds_raw + off);
+            uint32_t old[KC];
 #pragma unroll
-            for (int k = 0; k < KC; ++k)
-              atomicAdd(cell + k, (unsigned long long)(neg ? nq[k] : q[k]));
+            for (int k = 0; k < KC; ++k) old[k] = atomicAdd(cell + k, (q[k] ^ sgn) - sgn);   // +q or -q
+            // Every add is below 2^30 in magnitude (ScaleInfo::bound32), so a cell cannot wrap
+            // in an add that found it inside [2^30, 3*2^30): if every value ever returned was
+            // inside that band, no cell wrapped.  old - 2^30 has bit 31 set exactly outside the
+            // band.  The values of the row before are examined only now, with this row's adds
+            // already on their way, so the LDS round trip hides behind the next batch.
+            if (have_pending) {
+#pragma unroll
+              for (int k = 0; k < KC; ++k) wrapped |= pend_old[k] - 0x40000000u;
+            }
+#pragma unroll
+            for (int k = 0; k < KC; ++k) pend_old[k] = old[k];
+            have_pending = true;
           }
         }
-        if constexpr (SK && !FX) {
+        if constexpr (SK && CELL == kCellI64) {
+          unsigned long long q[KC], nq[KC];
+#pragma unroll
+          for (int k = 0; k < KC; ++k) {
+            const double y = fma((double)u[k], S64, kRoundMagic);           // round to integer
+            q[k] = (unsigned long long)(__double_as_longlong(y) - __double_as_longlong(kRoundMagic));
+            nq[k] = 0ull - q[k];
+          }
 #pragma unroll
           for (int i = 0; i < LR; ++i) {
             const uint32_t h = (v & 1) ? (t.tab[i][v >> 1] >> 16) : (t.tab[i][v >> 1] & 0xffffu);
             const uint32_t off = __umul24(h & rowmask[i], stride_bytes) + rowbase[i];
-            const bool neg = (h & 0x8000u) != 0;
+            const unsigned long long sgn = 0ull - (unsigned long long)((h >> 15) & 1u);
+            unsigned long long* cell = reinterpret_cast<unsigned long long*>(lds_raw + off);
+#pragma unroll
+            for (int k = 0; k < KC; ++k) atomicAdd(cell + k, (nq[k] & sgn) | (q[k] & ~sgn));
+          }
+        }
+        if constexpr (SK && CELL == kCellF64) {
+#pragma unroll
+          for (int i = 0; i < LR; ++i) {
+            const uint32_t h = (v & 1) ? (t.tab[i][v >> 1] >> 16) : (t.tab[i][v >> 1] & 0xffffu);
+            const uint32_t off = __umul24(h & rowmask[i], stride_bytes) + rowbase[i];
+            const uint32_t sbit = (h & 0x8000u) << 16;                    // the float sign bit
             double* cell = reinterpret_cast<double*>(lds_raw + off);
 #pragma unroll
-            for (int k = 0; k < KC; ++k) atomicAdd(cell + k, (double)(neg ? -u[k] : u[k]));
+            for (int k = 0; k < KC; ++k)
+              atomicAdd(cell + k, (double)__uint_as_float(__float_as_uint(u[k]) ^ sbit));
           }
+        }
+        // keep the coordinates of a vector in program order: letting the scheduler interleave
+        // all of them costs more registers than the file holds
+        __builtin_amdgcn_sched_barrier(0);
+      }
+      if constexpr (SK && CELL == kCellI32) {
+        if (have_pending) {
+#pragma unroll
+          for (int k = 0; k < KC; ++k) wrapped |= pend_old[k] - 0x40000000u;
         }
       }
       if constexpr (SC) {
@@ -425,10 +481,18 @@ state_kernel(const StateParams prm) {
     run(std::false_type{}, std::true_type{});
   }
 
-  if (scalars && prm.do_sk) {
-    // a drift the integer cells cannot hold (or any drift at all when the sample saw none)
-    const bool bad = bound > 0.0f ? !(amax < bound) : (amax > 0.0f);
-    if (bad) prm.scale->overflow = 1;
+  if constexpr (CELL == kCellI32) {
+    if (prm.do_sk) {
+      if (scalars) {
+        // drifts the integer cells cannot hold (any drift at all when the sample saw none)
+        const float b32 = prm.scale->bound32, b64 = prm.scale->bound64;
+        const bool bad32 = b32 > 0.0f ? !(amax < b32) : (amax > 0.0f);
+        const bool bad64 = b64 > 0.0f ? !(amax < b64) : (amax > 0.0f);
+        if (bad32 || bad64) prm.scale->flag32 = 1;
+        if (bad64) prm.scale->overflow64 = 1;
+      }
+      if (wrapped >> 31) prm.scale->flag32 = 1;
+    }
   }
 
   // ---- workgroup reduction of the scalar components (fixed shape) ---------------------
@@ -456,8 +520,12 @@ state_kernel(const StateParams prm) {
     unsigned long long* out = reinterpret_cast<unsigned long long*>(prm.part_sk);
     for (int t = tid; t < kcnt * cells; t += kStateThreads) {
       const int k = t / cells, c = t - k * cells;
-      out[((size_t)p * prm.K + kstart + k) * allcells + (size_t)rstart * prm.m + c] =
-          sk[(size_t)c * prm.stride + k];
+      unsigned long long val;
+      if constexpr (CELL == kCellI32)
+        val = (unsigned long long)(long long)(int)(reinterpret_cast<const uint32_t*>(lds_raw)[(size_t)c * prm.stride + k] - 0x80000000u);
+      else
+        val = reinterpret_cast<const unsigned long long*>(lds_raw)[(size_t)c * prm.stride + k];
+      out[((size_t)p * prm.K + kstart + k) * allcells + (size_t)rstart * prm.m + c] = val;
     }
   }
 }

@@ -65,7 +65,7 @@ hash_table_kernel(const HashCoef hc, int m, long long d, long long dpad,
 // workgroup's chunk that fall into the bucket.  It bounds the number of terms of any LDS cell.
 __global__ void __launch_bounds__(kStateThreads)
 cell_count_kernel(const HashCoef hc, int l, int m, long long d, long long chunk,
-                  unsigned int* __restrict__ nmax) {
+                  unsigned int* __restrict__ nmax) {   // nmax: the entry to raise
   extern __shared__ __align__(16) unsigned char lds_raw[];
   unsigned int* cnt = reinterpret_cast<unsigned int*>(lds_raw);
   __shared__ unsigned int shmax[kStateThreads / 64];
@@ -91,7 +91,9 @@ cell_count_kernel(const HashCoef hc, int l, int m, long long d, long long chunk,
     atomicMax(nmax, mx);
   }
 }
-__global__ void clear_u32_kernel(unsigned int* p) { if (threadIdx.x == 0 && blockIdx.x == 0) *p = 0u; }
+__global__ void clear_u32_kernel(unsigned int* p, int n) {
+  if (blockIdx.x == 0 && (int)threadIdx.x < n) p[threadIdx.x] = 0u;
+}
 
 // ---- the per-call fixed-point scale ----------------------------------------------------
 // Largest and mean |w_kj - w_t0_j| over an evenly spaced sample of coordinates of every worker.
@@ -124,11 +126,18 @@ scale_sample_kernel(const T* __restrict__ w, const float* __restrict__ w_t0, int
   }
 }
 
-// The unit 2^-e of the integer cells.  With at most nmax terms per cell, |q| < 2^qbits keeps
-// every cell below 2^62.  Drifts up to 2^12..2^13 times the sampled maximum are allowed for
-// (the sample can miss the tail), which leaves qbits - 13 bits below the sampled maximum.  If
-// the mean sampled magnitude would still get fewer than 17 of them, or the sample saw nothing
-// usable, the call is sent down the fp64 path right away.
+// The units of the integer cells.
+// 64-bit cells: with at most nmax64 terms per cell, |q| < 2^qbits keeps every cell below 2^62.
+// Drifts up to 2^12..2^13 times the sampled maximum are allowed for (the sample can miss the
+// tail), which leaves qbits - 13 bits below the sampled maximum.  If the mean sampled magnitude
+// would still get fewer than 17 of them, or the sample saw nothing usable, the call is sent
+// down the fp64 path right away.
+// 32-bit cells: the mean sampled magnitude maps to [2^18, 2^19) -- every term is rounded by at
+// most 2^-19 of the mean |u| -- and single drifts may reach 2^30, i.e. 2048..4096 times the mean
+// (a Student-t(3) tail over 3e9 draws reaches about 1400 times).  A cell wraps only if its sum
+// leaves (-2^31, 2^31), which for sums of up to a few thousand such terms does not happen, and
+// if it does it is detected as it happens.  Cells that can collect more than 4096 terms get one
+// bit less; beyond 16384 terms the call goes to the 64-bit pass.
 __global__ void scale_finalize_kernel(const float* __restrict__ part_max,
                                       const double* __restrict__ part_sum, int n, long long nsamples,
                                       const unsigned int* __restrict__ nmax,
@@ -138,52 +147,70 @@ __global__ void scale_finalize_kernel(const float* __restrict__ part_max,
   double sum = 0.0;
   for (int t = 0; t < n; ++t) { amax = fmaxf(amax, part_max[t]); sum += part_sum[t]; }
   ScaleInfo s;
-  s.S = 1.0; s.invS = 1.0; s.bound = 0.0f; s.overflow = 0; s.pad[0] = 0; s.pad[1] = 0;
-  if (amax > 0.0f && isfinite(amax)) {
-    unsigned int terms = *nmax;
+  s.S64 = 1.0; s.invS64 = 1.0; s.invS32 = 1.0; s.S32 = 1.0f;
+  s.bound32 = 0.0f; s.bound64 = 0.0f; s.flag32 = 0; s.overflow64 = 0; s.pad = 0;
+  const double mean = sum / (double)nsamples;
+  if (amax > 0.0f && isfinite(amax) && mean > 0.0) {
+    // ---- 64-bit cells
     int cb = 0;
-    while (cb < 32 && (1ull << cb) <= (unsigned long long)terms) ++cb;    // terms < 2^cb
+    while (cb < 32 && (1ull << cb) <= (unsigned long long)nmax[1]) ++cb;   // terms < 2^cb
     int qbits = 62 - cb;
     if (qbits > 50) qbits = 50;                // the rounding trick needs |u * 2^e| < 2^51
     const int head = 13;
     const int ex = ilogbf(amax);               // 2^ex <= amax < 2^(ex+1)
     const int e = qbits - (ex + head);         // |u| < 2^(ex+head)  =>  |u * 2^e| < 2^qbits
-    s.S = ldexp(1.0, e);
-    s.invS = ldexp(1.0, -e);
-    s.bound = (ex + head > 127) ? 3.0e38f : ldexpf(1.0f, ex + head);
-    const double mean = sum / (double)nsamples;
-    if (!(mean * s.S >= 131072.0)) s.overflow = 1;     // fewer than 17 bits for a typical drift
+    s.S64 = ldexp(1.0, e);
+    s.invS64 = ldexp(1.0, -e);
+    s.bound64 = (ex + head > 127) ? 3.0e38f : ldexpf(1.0f, ex + head);
+    if (!(mean * s.S64 >= 131072.0)) { s.overflow64 = 1; s.flag32 = 1; }   // < 17 bits for a typical drift
+    // ---- 32-bit cells
+    int cb32 = 0;
+    while (cb32 < 32 && (1ull << cb32) <= (unsigned long long)nmax[0]) ++cb32;
+    const int shrink = cb32 > 12 ? (cb32 - 12 + 1) / 2 : 0;
+    const int em = ilogb(mean);                // 2^em <= mean < 2^(em+1)
+    const int e32 = 18 - shrink - em;
+    if (e32 > 120 || e32 < -120 || shrink > 1) {
+      s.flag32 = 1;
+    } else {
+      s.S32 = ldexpf(1.0f, e32);
+      s.invS32 = ldexp(1.0, -e32);
+      s.bound32 = (30 - e32 > 127) ? 3.0e38f : ldexpf(1.0f, 30 - e32);
+      if (!(amax < s.bound32)) s.flag32 = 1;   // the sample already holds a drift too large
+    }
   }
   *out = s;
 }
 
-// state[k][s] = sum over the P partitions in fp64.  A workgroup handles 32 consecutive state
+// state[k][s] = sum over the partitions in fp64.  A workgroup handles 32 consecutive state
 // entries; eight lanes per entry each sum every eighth partition and the eight sums are added
-// in slice order: a fixed shape (and the integer partials are exact anyway).
+// in slice order: a fixed shape (and the integer partials are exact anyway).  The scalar
+// components always come from the first pass (P32 partitions); the sketch partials from
+// whichever pass was the last to run.
 __global__ void __launch_bounds__(kSmallThreads)
 merge_kernel(const double* __restrict__ part_np, const void* __restrict__ part_sk,
              const ScaleInfo* __restrict__ scale, float* __restrict__ state, int K, int cells,
-             int P) {
+             int P32, int P64) {
   __shared__ double sh[8][32];
   const int S = 2 + cells;
   const int o = threadIdx.x & 31, slice = threadIdx.x >> 5;
   const long long idx = (long long)blockIdx.x * 32 + o;
   const bool live = idx < (long long)K * S;
-  double acc = 0.0;
-  bool integer = false;
+  double acc = 0.0, unit = 1.0;
   if (live) {
     const int k = (int)(idx / S), s = (int)(idx - (long long)k * S);
     if (s < 2) {
-      for (int p = slice; p < P; p += 8) acc += part_np[((size_t)p * K + k) * 2 + s];
+      for (int p = slice; p < P32; p += 8) acc += part_np[((size_t)p * K + k) * 2 + s];
     } else {
       const int c = s - 2;
-      integer = scale->overflow == 0;
-      if (integer) {
+      if (scale->overflow64 != 0) {
+        const double* pd = reinterpret_cast<const double*>(part_sk);
+        for (int p = slice; p < P64; p += 8) acc += pd[((size_t)p * K + k) * cells + c];
+      } else {
+        const bool narrow = scale->flag32 == 0;
+        const int P = narrow ? P32 : P64;
+        unit = narrow ? scale->invS32 : scale->invS64;
         const long long* pi = reinterpret_cast<const long long*>(part_sk);
         for (int p = slice; p < P; p += 8) acc += (double)pi[((size_t)p * K + k) * cells + c];
-      } else {
-        const double* pd = reinterpret_cast<const double*>(part_sk);
-        for (int p = slice; p < P; p += 8) acc += pd[((size_t)p * K + k) * cells + c];
       }
     }
   }
@@ -193,8 +220,7 @@ merge_kernel(const double* __restrict__ part_np, const void* __restrict__ part_s
     double t = 0.0;
 #pragma unroll
     for (int q = 0; q < 8; ++q) t += sh[q][o];
-    if (integer) t *= scale->invS;
-    state[idx] = (float)t;
+    state[idx] = (float)(t * unit);
   }
 }
 

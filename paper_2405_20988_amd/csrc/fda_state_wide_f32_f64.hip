@@ -1,0 +1,5 @@
+// Fallback state kernels: float slab, fp64 cells.
+#define FDA_TU_TYPE float
+#define FDA_TU_CELL fda::kCellF64
+#define FDA_TU_NAME launch_wide_f32_f64
+#include "fda_state_wide.inc"
