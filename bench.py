@@ -58,7 +58,7 @@ def main():
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MiB",
                     help="instead of the benchmark, run a plain device copy of this many MiB five "
                          "times (a kernel of known traffic, to scale rocprofv3's FETCH_SIZE / WRITE_SIZE)")
-    ap.add_argument("--cpu-sample", type=int, default=2_000_000,
+    ap.add_argument("--cpu-sample", type=int, default=6_000_000,
                     help="coordinates of the workload the CPU oracle is timed on")
     args = ap.parse_args()
     if args.gpus != 1:

@@ -36,8 +36,9 @@ constexpr double kElementCost = 10.0;      // rough cost of loading / differenci
 constexpr double kAtomicCost = 3.0;        // select the signed value, issue the LDS atomic
 constexpr double kDecodeCost = 5.0;        // unpack one table entry into an LDS address and a sign
 constexpr double kSharedByteCost = 0.5;    // per byte of w_t0 / xi / table re-read by another workgroup
-constexpr int kScaleBlocks = 256;
-constexpr int kScaleSamples = 65536;       // sampled coordinates per worker for the scale
+constexpr int kMaxEstBlocksPerRow = 128;   // 32768 / 256: workgroups of estimate_kernel per sketch row
+constexpr int kScaleBlocks = 64;
+constexpr int kScaleSamples = 16384;       // sampled coordinates per worker for the scale (64 workgroups)
 constexpr int kXiBlocks = 1024;
 constexpr int64_t kAlign = 256;
 
@@ -53,7 +54,8 @@ struct Plan {
   Split wide;       // 8-byte cells: the 64-bit integer and fp64 passes
   int vec;          // elements per 16-byte slab load
   int64_t cells, S, dpad;
-  int64_t off_np, off_sk, off_xi, off_scale, off_smax, off_ssum, off_nmax, off_table, ws_bytes;
+  int64_t off_np, off_sk, off_xi, off_scale, off_smax, off_ssum, off_nmax, off_est, off_ticket, off_table,
+      ws_bytes;
 };
 
 int validate(const fda_desc* d) {
@@ -141,9 +143,8 @@ int make_split(const fda_desc* d, int cus, int64_t lds_cu, int cell_bytes, Split
   const int64_t sk_bytes =
       cells ? ((int64_t)sp->rcnt_max * d->m + fda::kDummyCells) * sp->stride * cell_bytes : 0;
   sp->lds_bytes = round_up(sk_bytes, 16) + kLdsReserve;
-  int occ = (int)(lds_cu / sp->lds_bytes);
-  if (occ > 2) occ = 2;
-  if (occ < 1) occ = 1;
+  // one workgroup per CU: the kernels hold more registers than two resident workgroups would allow
+  const int occ = 1;
   const int64_t tile = (int64_t)fda::kStateThreads * vec;
   // Partitions: all workgroups do the same amount of work, so the launch should fill the
   // resident slots a whole number of times.  Try 1..4 rounds and keep the best-filled one.
@@ -182,7 +183,9 @@ int make_plan(const fda_desc* d, int cus, int64_t lds_cu, Plan* pl) {
   pl->off_smax = round_up(pl->off_scale + (int64_t)sizeof(fda::ScaleInfo), kAlign);
   pl->off_ssum = round_up(pl->off_smax + kScaleBlocks * 4, kAlign);
   pl->off_nmax = round_up(pl->off_ssum + kScaleBlocks * 8, kAlign);
-  pl->off_table = round_up(pl->off_nmax + 8, kAlign);
+  pl->off_est = round_up(pl->off_nmax + 8, kAlign);
+  pl->off_ticket = round_up(pl->off_est + (2 + (int64_t)FDA_MAX_SKETCH_ROWS * kMaxEstBlocksPerRow) * 8, kAlign);
+  pl->off_table = round_up(pl->off_ticket + 8, kAlign);
   pl->dpad = round_up(d->d, 64);
   pl->ws_bytes = round_up(pl->off_table + (sk ? (int64_t)d->l * pl->dpad * 2 : 0), kAlign);
   return FDA_OK;
@@ -255,6 +258,7 @@ struct fda_ctx {
   int device;
   int cus;
   bool counted = false;       // cell_count_kernel has been enqueued for this context
+  bool tickets_cleared = false;
   // optional timing of the state kernel (fda_profile_enable)
   bool prof_on = false;
   hipEvent_t prof_start[kProfSlots] = {};
@@ -265,6 +269,17 @@ struct fda_ctx {
 };
 
 namespace {
+// The finished-workgroup counters of scale_kernel and estimate_kernel start at zero and are left
+// at zero by every launch; the workspace arrives uninitialised, so they are cleared once.
+int clear_tickets_once(fda_ctx* c, hipStream_t st) {
+  if (c->tickets_cleared) return FDA_OK;
+  hipLaunchKernelGGL(fda::clear_u32_kernel, dim3(1), dim3(64), 0, st,
+                     reinterpret_cast<unsigned int*>(c->ws + c->plan.off_ticket), 2);
+  FDA_HIP(hipGetLastError());
+  c->tickets_cleared = true;
+  return FDA_OK;
+}
+
 // Fold the recorded event pairs into the running totals (waits for them).
 int prof_drain(fda_ctx* c) {
   for (int t = 0; t < c->prof_pending; ++t) {
@@ -453,6 +468,8 @@ int fda_local_state(fda_ctx* ctx, const void* w, const float* w_t0, const float*
   const fda::StateParams prm64 = params_for(pl.wide);
 
   if (sk) {
+    int rc0 = clear_tickets_once(ctx, st);
+    if (rc0 != FDA_OK) return rc0;
     float* smax = reinterpret_cast<float*>(ctx->ws + pl.off_smax);
     double* ssum = reinterpret_cast<double*>(ctx->ws + pl.off_ssum);
     unsigned int* nmax = reinterpret_cast<unsigned int*>(ctx->ws + pl.off_nmax);
@@ -480,17 +497,16 @@ int fda_local_state(fda_ctx* ctx, const void* w, const float* w_t0, const float*
     }
     // fixed-point units for this call, from a sample of the drifts; also clears the flags
     const int samples = (int)(d.d < kScaleSamples ? d.d : kScaleSamples);
+    const int sblocks = (samples + fda::kSmallThreads - 1) / fda::kSmallThreads;
+    unsigned int* ticket = reinterpret_cast<unsigned int*>(ctx->ws + pl.off_ticket);
     if (d.dtype == FDA_F32)
-      hipLaunchKernelGGL(fda::scale_sample_kernel<float>, dim3(kScaleBlocks), dim3(fda::kSmallThreads), 0,
-                         st, static_cast<const float*>(w), w_t0, d.K, (long long)d.d,
-                         (long long)d.row_stride, samples, smax, ssum);
+      hipLaunchKernelGGL(fda::scale_kernel<float>, dim3(sblocks), dim3(fda::kSmallThreads), 0, st,
+                         static_cast<const float*>(w), w_t0, d.K, (long long)d.d, (long long)d.row_stride,
+                         samples, smax, ssum, ticket, nmax, prm32.scale);
     else
-      hipLaunchKernelGGL(fda::scale_sample_kernel<fda::bf16_t>, dim3(kScaleBlocks),
-                         dim3(fda::kSmallThreads), 0, st, static_cast<const fda::bf16_t*>(w), w_t0, d.K,
-                         (long long)d.d, (long long)d.row_stride, samples, smax, ssum);
-    FDA_HIP(hipGetLastError());
-    hipLaunchKernelGGL(fda::scale_finalize_kernel, dim3(1), dim3(64), 0, st, smax, ssum, kScaleBlocks,
-                       (long long)samples * d.K, nmax, prm32.scale);
+      hipLaunchKernelGGL(fda::scale_kernel<fda::bf16_t>, dim3(sblocks), dim3(fda::kSmallThreads), 0, st,
+                         static_cast<const fda::bf16_t*>(w), w_t0, d.K, (long long)d.d,
+                         (long long)d.row_stride, samples, smax, ssum, ticket, nmax, prm32.scale);
     FDA_HIP(hipGetLastError());
   }
 
@@ -534,8 +550,15 @@ int fda_estimate_variance(fda_ctx* ctx, const float* state, double theta, double
   if (!(tie_tol >= 0.0)) return fail(FDA_EINVAL, "tie_tol must be >= 0");
   const fda_desc& d = ctx->desc;
   hipStream_t st = static_cast<hipStream_t>(stream);
-  hipLaunchKernelGGL(fda::estimate_kernel, dim3(1), dim3(1024), 0, st, state, d.K, d.l, d.m,
-                     d.variants, d.eps, theta, tie_tol, out_dev);
+  const bool sk = (d.variants & FDA_VARIANT_SKETCH) != 0;
+  const int bpr = (d.m + fda::kEstCols - 1) / fda::kEstCols;
+  const int eblocks = sk ? d.l * bpr : 1;
+  int rc = clear_tickets_once(ctx, st);
+  if (rc != FDA_OK) return rc;
+  hipLaunchKernelGGL(fda::estimate_kernel, dim3(eblocks), dim3(fda::kSmallThreads), 0, st, state, d.K,
+                     sk ? d.l : 0, sk ? d.m : 1, d.variants, d.eps, theta, tie_tol,
+                     reinterpret_cast<double*>(ctx->ws + ctx->plan.off_est),
+                     reinterpret_cast<unsigned int*>(ctx->ws + ctx->plan.off_ticket) + 1, out_dev);
   FDA_HIP(hipGetLastError());
   if (out_host != nullptr) {
     FDA_HIP(hipMemcpyAsync(out_host, out_dev, sizeof(fda_estimate), hipMemcpyDeviceToHost, st));

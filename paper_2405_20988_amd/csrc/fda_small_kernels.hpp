@@ -96,38 +96,8 @@ __global__ void clear_u32_kernel(unsigned int* p, int n) {
 }
 
 // ---- the per-call fixed-point scale ----------------------------------------------------
-// Largest and mean |w_kj - w_t0_j| over an evenly spaced sample of coordinates of every worker.
-template <typename T>
-__global__ void __launch_bounds__(kSmallThreads)
-scale_sample_kernel(const T* __restrict__ w, const float* __restrict__ w_t0, int K, long long d,
-                    long long row_stride, int samples, float* __restrict__ part_max,
-                    double* __restrict__ part_sum) {
-  __shared__ float sh[kSmallThreads / 64];
-  __shared__ double scratch[kSmallThreads / 64];
-  float m = 0.0f;
-  double sum = 0.0;
-  const long long total = (long long)K * samples;
-  for (long long t = (long long)blockIdx.x * blockDim.x + threadIdx.x; t < total;
-       t += (long long)gridDim.x * blockDim.x) {
-    const int k = (int)(t / samples);
-    const long long j = (t - (long long)k * samples) * d / samples;
-    const float u = fabsf(Slab<T>::load_one(w + (long long)k * row_stride + j) - w_t0[j]);
-    m = fmaxf(m, u);                           // fmaxf drops NaN
-    if (u == u && u < 3.0e38f) sum += (double)u;
-  }
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) m = fmaxf(m, __shfl_down(m, o, 64));
-  if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = m;
-  const double tot = block_sum(sum, scratch);  // has the barriers sh needs
-  if (threadIdx.x == 0) {
-    for (int t = 1; t < kSmallThreads / 64; ++t) m = fmaxf(m, sh[t]);
-    part_max[blockIdx.x] = m;
-    part_sum[blockIdx.x] = tot;
-  }
-}
-
 // The units of the integer cells.
-// 64-bit cells: with at most nmax64 terms per cell, |q| < 2^qbits keeps every cell below 2^62.
+// 64-bit cells: with at most nmax[1] terms per cell, |q| < 2^qbits keeps every cell below 2^62.
 // Drifts up to 2^12..2^13 times the sampled maximum are allowed for (the sample can miss the
 // tail), which leaves qbits - 13 bits below the sampled maximum.  If the mean sampled magnitude
 // would still get fewer than 17 of them, or the sample saw nothing usable, the call is sent
@@ -136,20 +106,12 @@ scale_sample_kernel(const T* __restrict__ w, const float* __restrict__ w_t0, int
 // most 2^-19 of the mean |u| -- and single drifts may reach 2^30, i.e. 2048..4096 times the mean
 // (a Student-t(3) tail over 3e9 draws reaches about 1400 times).  A cell wraps only if its sum
 // leaves (-2^31, 2^31), which for sums of up to a few thousand such terms does not happen, and
-// if it does it is detected as it happens.  Cells that can collect more than 4096 terms get one
-// bit less; beyond 16384 terms the call goes to the 64-bit pass.
-__global__ void scale_finalize_kernel(const float* __restrict__ part_max,
-                                      const double* __restrict__ part_sum, int n, long long nsamples,
-                                      const unsigned int* __restrict__ nmax,
-                                      ScaleInfo* __restrict__ out) {
-  if (threadIdx.x != 0 || blockIdx.x != 0) return;
-  float amax = 0.0f;
-  double sum = 0.0;
-  for (int t = 0; t < n; ++t) { amax = fmaxf(amax, part_max[t]); sum += part_sum[t]; }
+// if it does it is noticed.  Cells that can collect more than 4096 terms get one bit less;
+// beyond 16384 terms the call goes to the 64-bit pass.
+__device__ inline ScaleInfo choose_scale(float amax, double mean, const unsigned int* nmax) {
   ScaleInfo s;
   s.S64 = 1.0; s.invS64 = 1.0; s.invS32 = 1.0; s.S32 = 1.0f;
   s.bound32 = 0.0f; s.bound64 = 0.0f; s.flag32 = 0; s.overflow64 = 0; s.pad = 0;
-  const double mean = sum / (double)nsamples;
   if (amax > 0.0f && isfinite(amax) && mean > 0.0) {
     // ---- 64-bit cells
     int cb = 0;
@@ -178,7 +140,65 @@ __global__ void scale_finalize_kernel(const float* __restrict__ part_max,
       if (!(amax < s.bound32)) s.flag32 = 1;   // the sample already holds a drift too large
     }
   }
-  *out = s;
+  return s;
+}
+
+// Largest and mean |w_kj - w_t0_j| over `samples` evenly spaced coordinates of every worker
+// (one coordinate per thread, all workers), reduced per workgroup; the workgroup that finishes
+// last combines the per-workgroup results in a fixed order, chooses the scales and clears the
+// flags.  `ticket` counts finished workgroups and is left at zero.
+template <typename T>
+__global__ void __launch_bounds__(kSmallThreads)
+scale_kernel(const T* __restrict__ w, const float* __restrict__ w_t0, int K, long long d,
+             long long row_stride, int samples, float* __restrict__ part_max,
+             double* __restrict__ part_sum, unsigned int* __restrict__ ticket,
+             const unsigned int* __restrict__ nmax, ScaleInfo* __restrict__ out) {
+  __shared__ float sh[kSmallThreads / 64];
+  __shared__ double scratch[kSmallThreads / 64];
+  __shared__ int last;
+  float m = 0.0f;
+  double sum = 0.0;
+  const int t = blockIdx.x * blockDim.x + threadIdx.x;
+  if (t < samples) {
+    const long long j = (long long)t * (d / samples);
+    const float base = w_t0[j];
+    float part = 0.0f;
+    for (int k = 0; k < K; ++k) {
+      const float u = fabsf(Slab<T>::load_one(w + (long long)k * row_stride + j) - base);
+      m = fmaxf(m, u);                         // fmaxf drops NaN
+      if (u == u && u < 3.0e38f) part += u;
+    }
+    sum = (double)part;
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) m = fmaxf(m, __shfl_down(m, o, 64));
+  if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = m;
+  const double tot = block_sum(sum, scratch);  // has the barriers sh needs
+  if (threadIdx.x == 0) {
+    for (int q = 1; q < kSmallThreads / 64; ++q) m = fmaxf(m, sh[q]);
+    part_max[blockIdx.x] = m;
+    part_sum[blockIdx.x] = tot;
+    __threadfence();
+    last = (atomicAdd(ticket, 1u) == gridDim.x - 1) ? 1 : 0;
+  }
+  __syncthreads();
+  if (!last) return;
+  __threadfence();
+  if (threadIdx.x < 64) {                      // gridDim.x <= 64: one partial per lane
+    float am = 0.0f;
+    double sm = 0.0;
+    if (threadIdx.x < gridDim.x) {
+      am = reinterpret_cast<volatile float*>(part_max)[threadIdx.x];
+      sm = reinterpret_cast<volatile double*>(part_sum)[threadIdx.x];
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) am = fmaxf(am, __shfl_down(am, o, 64));
+    sm = wave_sum(sm);
+    if (threadIdx.x == 0) {
+      *out = choose_scale(am, sm / ((double)samples * K), nmax);
+      *ticket = 0u;
+    }
+  }
 }
 
 // state[k][s] = sum over the partitions in fp64.  A workgroup handles 32 consecutive state
@@ -225,75 +245,94 @@ merge_kernel(const double* __restrict__ part_np, const void* __restrict__ part_s
 }
 
 // ----------------------------------------------------------------------------------------
-// Algorithm 1 lines 7-8, one workgroup, all in fp64:
+// Algorithm 1 lines 7-8, all in fp64:
 //   mean_k of the states;  row norms of the mean sketch;  M2 = their median (Section 3.1);
 //   H_sketch = n - M2/(1+eps) (Thm 1);  H_linear = n - p^2 (Thm 2);  sync = H > theta.
+// Workgroup b takes 256 consecutive cells of one sketch row (one cell per thread: mean over the
+// K workers, squared, summed over the workgroup); workgroup 0 also takes the scalar components.
+// The workgroup that finishes last adds the per-workgroup sums of every row in workgroup order,
+// takes the median and writes the result.  `ticket` counts finished workgroups and is left at 0.
 // ----------------------------------------------------------------------------------------
-__global__ void __launch_bounds__(1024)
+constexpr int kEstCols = kSmallThreads;      // cells per workgroup
+
+__global__ void __launch_bounds__(kSmallThreads)
 estimate_kernel(const float* __restrict__ state, int K, int l, int m, int variants, double eps,
-                double theta, double tie_tol, fda_estimate* __restrict__ out) {
-  __shared__ double scratch[16];
-  __shared__ double rows[FDA_MAX_SKETCH_ROWS];
+                double theta, double tie_tol, double* __restrict__ part, unsigned int* __restrict__ ticket,
+                fda_estimate* __restrict__ out) {
+  __shared__ double scratch[kSmallThreads / 64];
+  __shared__ int last;
   const int cells = (variants & FDA_VARIANT_SKETCH) ? l * m : 0;
   const int S = 2 + cells;
+  const int bpr = (m + kEstCols - 1) / kEstCols;     // workgroups per sketch row
   const int tid = threadIdx.x;
-  double vn = 0.0, vp = 0.0;
-  for (int k = tid; k < K; k += blockDim.x) {
-    vn += (double)state[(size_t)k * S];
-    vp += (double)state[(size_t)k * S + 1];
-  }
-  const double sn = block_sum(vn, scratch);
-  const double sp = block_sum(vp, scratch);
+  // part[0], part[1]: sums of the two scalar components; part[2 + b]: workgroup b's row sum
   if (cells) {
-    for (int i = 0; i < l; ++i) {
-      double acc = 0.0;
-      for (int bkt = tid; bkt < m; bkt += blockDim.x) {
-        double c = 0.0;
-        for (int k = 0; k < K; ++k) c += (double)state[(size_t)k * S + 2 + i * m + bkt];
-        c /= (double)K;
-        acc += c * c;
-      }
-      const double r = block_sum(acc, scratch);
-      if (tid == 0) rows[i] = r;
+    const int i = blockIdx.x / bpr, col = (blockIdx.x - i * bpr) * kEstCols + tid;
+    double sq = 0.0;
+    if (col < m) {
+      double c = 0.0;
+      for (int k = 0; k < K; ++k) c += (double)state[(size_t)k * S + 2 + i * m + col];
+      c /= (double)K;
+      sq = c * c;
     }
+    const double r = block_sum(sq, scratch);
+    if (tid == 0) part[2 + blockIdx.x] = r;
+  }
+  if (blockIdx.x == 0) {
+    double vn = 0.0, vp = 0.0;
+    for (int k = tid; k < K; k += blockDim.x) {
+      vn += (double)state[(size_t)k * S];
+      vp += (double)state[(size_t)k * S + 1];
+    }
+    const double sn = block_sum(vn, scratch);
+    const double sp = block_sum(vp, scratch);
+    if (tid == 0) { part[0] = sn; part[1] = sp; }
   }
   if (tid == 0) {
-    fda_estimate e;
-    e.mean_sqnorm = sn / (double)K;
-    e.mean_proj = 0.0; e.m2 = 0.0; e.h_linear = 0.0; e.h_sketch = 0.0;
-    e.sync_linear = 0; e.sync_sketch = 0; e.near_tie_linear = 0; e.near_tie_sketch = 0;
-    e.nonfinite = 0; e.reserved = 0;
-    const double band = tie_tol * fmax(e.mean_sqnorm, fabs(theta));
-    if (variants & FDA_VARIANT_LINEAR) {
-      e.mean_proj = sp / (double)K;
-      e.h_linear = e.mean_sqnorm - e.mean_proj * e.mean_proj;
-      if (isfinite(e.h_linear)) {
-        e.sync_linear = e.h_linear > theta ? 1 : 0;
-        e.near_tie_linear = fabs(e.h_linear - theta) <= band ? 1 : 0;
-      } else {
-        e.sync_linear = 1; e.nonfinite = 1;
-      }
-    }
-    if (cells) {
-      // median of l values: insertion sort, then middle (even l: mean of the two middle)
-      double r[FDA_MAX_SKETCH_ROWS];
-      for (int i = 0; i < l; ++i) {
-        double v = rows[i];
-        int q = i;
-        while (q > 0 && !(r[q - 1] <= v)) { r[q] = r[q - 1]; --q; }
-        r[q] = v;
-      }
-      e.m2 = (l & 1) ? r[l / 2] : 0.5 * (r[l / 2 - 1] + r[l / 2]);
-      e.h_sketch = e.mean_sqnorm - e.m2 / (1.0 + eps);
-      if (isfinite(e.h_sketch)) {
-        e.sync_sketch = e.h_sketch > theta ? 1 : 0;
-        e.near_tie_sketch = fabs(e.h_sketch - theta) <= band ? 1 : 0;
-      } else {
-        e.sync_sketch = 1; e.nonfinite = 1;
-      }
-    }
-    *out = e;
+    __threadfence();
+    last = (atomicAdd(ticket, 1u) == gridDim.x - 1) ? 1 : 0;
   }
+  __syncthreads();
+  if (!last || tid != 0) return;
+  __threadfence();
+  const volatile double* vpart = part;
+  fda_estimate e;
+  e.mean_sqnorm = vpart[0] / (double)K;
+  e.mean_proj = 0.0; e.m2 = 0.0; e.h_linear = 0.0; e.h_sketch = 0.0;
+  e.sync_linear = 0; e.sync_sketch = 0; e.near_tie_linear = 0; e.near_tie_sketch = 0;
+  e.nonfinite = 0; e.reserved = 0;
+  const double band = tie_tol * fmax(e.mean_sqnorm, fabs(theta));
+  if (variants & FDA_VARIANT_LINEAR) {
+    e.mean_proj = vpart[1] / (double)K;
+    e.h_linear = e.mean_sqnorm - e.mean_proj * e.mean_proj;
+    if (isfinite(e.h_linear)) {
+      e.sync_linear = e.h_linear > theta ? 1 : 0;
+      e.near_tie_linear = fabs(e.h_linear - theta) <= band ? 1 : 0;
+    } else {
+      e.sync_linear = 1; e.nonfinite = 1;
+    }
+  }
+  if (cells) {
+    // median of l values: insertion sort, then middle (even l: mean of the two middle)
+    double r[FDA_MAX_SKETCH_ROWS];
+    for (int i = 0; i < l; ++i) {
+      double v = 0.0;
+      for (int b = 0; b < bpr; ++b) v += vpart[2 + i * bpr + b];
+      int q = i;
+      while (q > 0 && !(r[q - 1] <= v)) { r[q] = r[q - 1]; --q; }
+      r[q] = v;
+    }
+    e.m2 = (l & 1) ? r[l / 2] : 0.5 * (r[l / 2 - 1] + r[l / 2]);
+    e.h_sketch = e.mean_sqnorm - e.m2 / (1.0 + eps);
+    if (isfinite(e.h_sketch)) {
+      e.sync_sketch = e.h_sketch > theta ? 1 : 0;
+      e.near_tie_sketch = fabs(e.h_sketch - theta) <= band ? 1 : 0;
+    } else {
+      e.sync_sketch = 1; e.nonfinite = 1;
+    }
+  }
+  *out = e;
+  *ticket = 0u;
 }
 
 // ----------------------------------------------------------------------------------------
