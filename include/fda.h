@@ -148,8 +148,10 @@ int fda_get_plan(const fda_ctx* ctx, fda_plan_info* out);
  *          sign_i(j) (w_kj - w_t0_j)   (absent without SKETCH)
  * Pointers 16-byte aligned and row_stride*sizeof(element) a multiple of 16 take the
  * vector path; anything else is handled element by element (slow, not an error).
- * Sketch cells are accumulated with LDS floating-point atomics, so their last bits may
- * differ from run to run; everything across workgroups is merged in a fixed order.
+ * Sketch cells are accumulated as integers (a drift u enters as round(u * 2^e), 2^e chosen
+ * per call so that the rounding is at most 2^-19 of the mean |u|), and everything across
+ * workgroups is merged in a fixed order: the state is bit-identical from run to run.
+ * The first call of a context also tabulates the hash (2*l*d bytes of the workspace).
  */
 int fda_local_state(fda_ctx* ctx, const void* w, const float* w_t0, const float* xi,
                     float* state, void* stream);
@@ -186,6 +188,16 @@ int fda_sync(fda_ctx* ctx, void* w, float* w_t0, float* w_prev, const int32_t* p
  */
 int fda_update_xi(fda_ctx* ctx, const float* w_t0, const float* w_prev, float* xi,
                   const int32_t* pred_dev, void* stream);
+
+/*
+ * Diagnostic: which kind of LDS sketch cell the last fda_local_state of this context ended
+ * up using -- 0: 32-bit integers (the normal case), 1: 64-bit integers (a drift was too large
+ * for, or a sum did not fit, the 32-bit cells), 2: fp64 (the drifts' dynamic range is beyond
+ * the 64-bit cells), -1: the context has no sketch.  Waits for `stream`.  The result of
+ * fda_local_state is the same within the stated tolerance whichever path ran; only the time
+ * differs.
+ */
+int fda_last_state_path(fda_ctx* ctx, int32_t* path, void* stream);
 
 /*
  * Measurement aid (no part of the method): when enabled, fda_local_state brackets its

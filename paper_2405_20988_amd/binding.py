@@ -85,9 +85,10 @@ def load_library():
                                           C.POINTER(FdaEstimate), vp]
     lib.fda_sync.argtypes = [vp, vp, vp, vp, i32p, vp]
     lib.fda_update_xi.argtypes = [vp, vp, vp, vp, i32p, vp]
+    lib.fda_last_state_path.argtypes = [vp, C.POINTER(C.c_int32), vp]
     lib.fda_profile_enable.argtypes = [vp, C.c_int]
     lib.fda_profile_read.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(C.c_int64), C.c_int]
-    for name in ("fda_profile_enable", "fda_profile_read", "fda_plan", "fda_workspace_bytes", "fda_create", "fda_destroy",
+    for name in ("fda_last_state_path", "fda_profile_enable", "fda_profile_read", "fda_plan", "fda_workspace_bytes", "fda_create", "fda_destroy",
                  "fda_state_floats", "fda_get_plan", "fda_local_state",
                  "fda_estimate_variance", "fda_sync", "fda_update_xi"):
         getattr(lib, name).restype = C.c_int
@@ -191,3 +192,10 @@ def fda_profile_read(ctx: int, reset: bool = True):
     _check(load_library().fda_profile_read(ctx, C.byref(ms), C.byref(n), 1 if reset else 0),
            "fda_profile_read")
     return float(ms.value), int(n.value)
+
+
+def fda_last_state_path(ctx: int, stream: int = 0) -> int:
+    """0 / 1 / 2: the last fda_local_state used 32-bit, 64-bit integer or fp64 sketch cells."""
+    v = C.c_int32(0)
+    _check(load_library().fda_last_state_path(ctx, C.byref(v), stream), "fda_last_state_path")
+    return int(v.value)

@@ -394,6 +394,17 @@ int fda_destroy(fda_ctx* ctx) {
   return FDA_OK;
 }
 
+int fda_last_state_path(fda_ctx* ctx, int32_t* path, void* stream) {
+  if (ctx == nullptr || path == nullptr) return fail(FDA_EINVAL, "NULL argument");
+  if (!(ctx->desc.variants & FDA_VARIANT_SKETCH)) { *path = -1; return FDA_OK; }
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  fda::ScaleInfo info;
+  FDA_HIP(hipMemcpyAsync(&info, ctx->ws + ctx->plan.off_scale, sizeof(info), hipMemcpyDeviceToHost, st));
+  FDA_HIP(hipStreamSynchronize(st));
+  *path = info.overflow64 ? 2 : (info.flag32 ? 1 : 0);
+  return FDA_OK;
+}
+
 int fda_profile_enable(fda_ctx* ctx, int on) {
   if (ctx == nullptr) return fail(FDA_EINVAL, "ctx is NULL");
   if (on && ctx->prof_start[0] == nullptr) {

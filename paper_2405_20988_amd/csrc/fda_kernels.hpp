@@ -434,9 +434,6 @@ state_kernel(const StateParams prm) {
               atomicAdd(cell + k, (double)__uint_as_float(__float_as_uint(u[k]) ^ sbit));
           }
         }
-        // keep the coordinates of a vector in program order: letting the scheduler interleave
-        // all of them costs more registers than the file holds
-        __builtin_amdgcn_sched_barrier(0);
       }
       if constexpr (SK && CELL == kCellI32) {
         if (have_pending) {

@@ -68,6 +68,9 @@ class FdaMonitor:
         B.fda_update_xi(self.ctx, w_t0.data_ptr(), w_prev.data_ptr(), xi.data_ptr(),
                         self.pred_ptr(pred), self._stream())
 
+    def last_state_path(self):
+        return B.fda_last_state_path(self.ctx, self._stream())
+
     def state_numpy(self):
         """(n[K], p[K], sk[K,l,m] or None) as float32 host arrays."""
         s = self.state.cpu().numpy()

@@ -498,4 +498,53 @@ def test_drifts_outside_the_sampled_range(dtype):
         mon.local_state(w, w_t0_used, xi)
         ref = O.local_state(S.slab_to_numpy(w), dtype, w_t0_used.cpu().numpy(), xi.cpu().numpy(), coef, m)
         check_state(mon, ref)
+        # the 32-bit cells cannot hold these; fp32 slabs need the fp64 cells, a bf16 slab's
+        # rounding residue narrows the range enough for the 64-bit integers
+        assert mon.last_state_path() == (2 if dtype == "f32" else 1) or kind == "sparse"
+        assert mon.last_state_path() >= 1
         mon.close()
+
+
+def test_sketch_cell_paths():
+    """The three kinds of sketch cell: ordinary drifts stay on the 32-bit cells; a few drifts
+    thousands of times the mean go to the 64-bit cells; a 32-bit cell that leaves its safe band
+    is noticed while the pass runs and the 64-bit cells redo the sketch."""
+    say("[case] sketch cell paths")
+    import paper_2405_20988_amd as F
+    g = torch.Generator(device=DEV)
+    g.manual_seed(12)
+    # (a) ordinary
+    wl = S.make("cfg4", device=DEV, seed=12, d=100_003)
+    mon = monitor_for(wl)
+    mon.local_state(wl.w, wl.w_t0, wl.xi)
+    assert mon.last_state_path() == 0
+    check_state(mon, oracle_state(wl))
+    mon.close()
+    # (b) two drifts per worker 8000 times the mean, every coordinate sampled
+    K, d, l, m = 4, 16_000, 5, 250
+    coef = S.hash_coefficients(12, l)
+    w_t0 = torch.zeros(d, device=DEV)
+    u = torch.randn((K, d), generator=g, device=DEV) * 1e-6
+    for k in range(K):
+        u[k, 100 + k] = 1.0
+        u[k, 9_000 + k] = -1.0
+    xi = torch.randn(d, generator=g, device=DEV) / d ** 0.5
+    mon = F.FdaMonitor(K, d, "f32", 3, l, m, 0.06, coef, device=DEV)
+    mon.local_state(u, w_t0, xi)
+    assert mon.last_state_path() == 1
+    check_state(mon, O.local_state(u.cpu().numpy(), "f32", w_t0.cpu().numpy(), xi.cpu().numpy(), coef, m))
+    mon.close()
+    # (c) every coordinate in one bucket with one sign and equal positive drifts: the cell of a
+    # workgroup collects 12288 terms of about 2^17.5 units and leaves [2^30, 3*2^30)
+    d, m = 256 * 12_288, 4
+    coef = np.array([[[1 << 30, 0, 0, 0], [0, 0, 0, 0]]], np.uint32)      # bucket 2, sign +1
+    w_t0 = torch.zeros(d, device=DEV)
+    w = torch.full((1, d), 0.5, device=DEV)
+    mon = F.FdaMonitor(1, d, "f32", 2, 1, m, 0.06, coef, device=DEV)
+    assert mon.plan["chunk"] == 12_288, mon.plan
+    mon.local_state(w, w_t0)
+    assert mon.last_state_path() == 1
+    n, _, sk = mon.state_numpy()
+    assert sk[0, 0].tolist() == [0.0, 0.0, 0.5 * d, 0.0]
+    assert n[0] == 0.25 * d
+    mon.close()
