@@ -128,7 +128,9 @@ int fda_workspace_bytes(const fda_desc* desc, size_t* bytes);
 
 /* Create a context on the current HIP device.  `workspace` is a DEVICE pointer, 256-byte
  * aligned, of at least fda_workspace_bytes() bytes, owned by the caller and left with the
- * context until fda_destroy.  On failure *ctx is set to NULL. */
+ * context until fda_destroy.  On failure *ctx is set to NULL.
+ * All calls of one context use that workspace for their partial results: enqueue them on one
+ * stream (or order them yourself); calls of one context that overlap on the device race. */
 int fda_create(fda_ctx** ctx, const fda_desc* desc, void* workspace, size_t workspace_bytes);
 int fda_destroy(fda_ctx* ctx);
 
@@ -169,6 +171,34 @@ int fda_estimate_variance(fda_ctx* ctx, const float* state, double theta, double
                           fda_estimate* out_dev, fda_estimate* out_host, void* stream);
 
 /*
+ * Algorithm 1, line 7 without line 6: the AVERAGE state of the K workers, computed directly.
+ * With all workers in one address space the linearity of the sketch (Section 3.1,
+ * sk(a u + b v) = a sk(u) + b sk(v)) and of the inner product give
+ *   mean_state[0] = (1/K) sum_k ||u_k||^2,
+ *   mean_state[1] = <xi, u_bar> = (1/K) sum_k <xi,u_k>,
+ *   mean_state[2 + i*m + b] = sk(u_bar)[i][b] = (1/K) sum_k sk(u_k)[i][b],   u_bar = (1/K) sum_k u_k,
+ * i.e. exactly the average of the K states fda_local_state writes, at l instead of l*K sketch
+ * additions per coordinate.  Use it when the per-worker states themselves are not needed (they
+ * are what a worker of a distributed run would send; one device holding all workers only needs
+ * their mean).
+ *   w, w_t0, xi   as in fda_local_state
+ *   mean_state    DEVICE [S] fp32, written
+ * A drift enters the sketch as the integer round(u * 2^e) (2^e as in fda_local_state), the K
+ * integers of a coordinate are summed and added to 64-bit cells: exact, hence bit-identical
+ * from run to run; drifts beyond 2^11 times the sampled mean |u| send the call down an fp64 path.
+ * Returns FDA_ERANGE if K times the coordinates per workgroup reaches 2^33.
+ */
+int fda_mean_state(fda_ctx* ctx, const void* w, const float* w_t0, const float* xi,
+                   float* mean_state, void* stream);
+
+/*
+ * Algorithm 1, line 8 on an average state: as fda_estimate_variance, but `mean_state` is the
+ * DEVICE [S] vector fda_mean_state wrote (no averaging left to do).
+ */
+int fda_estimate_variance_mean(fda_ctx* ctx, const float* mean_state, double theta, double tie_tol,
+                               fda_estimate* out_dev, fda_estimate* out_host, void* stream);
+
+/*
  * Algorithm 1, line 9 ("In-place"): every row of the slab becomes the average model.
  *   w        DEVICE slab, rewritten: row k <- (1/K) sum_k' row k'  (fp32 sum in worker
  *            order, divided by K; bf16 slabs store its round-to-nearest-even)
@@ -198,11 +228,13 @@ int fda_update_xi(fda_ctx* ctx, const float* w_t0, const float* w_prev, float* x
  * differs.
  */
 int fda_last_state_path(fda_ctx* ctx, int32_t* path, void* stream);
+/* The same for the last fda_mean_state: 0: integer sums in 64-bit cells, 1: fp64, -1: no sketch. */
+int fda_last_mean_state_path(fda_ctx* ctx, int32_t* path, void* stream);
 
 /*
- * Measurement aid (no part of the method): when enabled, fda_local_state brackets its
- * streaming state kernel -- the pass over the slab, Algorithm 1 line 6 -- with HIP events
- * on the caller's stream.  fda_profile_read waits for the recorded events and returns the
+ * Measurement aid (no part of the method): when enabled, fda_local_state and fda_mean_state
+ * bracket their streaming kernel -- the pass over the slab, Algorithm 1 line 6 -- with HIP
+ * events on the caller's stream.  fda_profile_read waits for the recorded events and returns the
  * accumulated kernel time in milliseconds and the number of launches it covers since the
  * last reset.  Events are created on first enable and destroyed with the context.
  */

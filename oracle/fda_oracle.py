@@ -229,6 +229,36 @@ def local_state(w, dtype: str, w_t0: np.ndarray, xi, coef, m: int):
     return out
 
 
+def mean_state(w, dtype: str, w_t0: np.ndarray, xi, coef, m: int):
+    """The average state of Algorithm 1, line 7, from the average drift.
+
+    u_bar = (1/K) sum_k u_k;  the sketch and the inner product are linear (Section 3.1), so the
+    average of the K states is (mean_k ||u_k||^2, <xi, u_bar>, sk(u_bar)): this function
+    evaluates exactly that, sketching u_bar itself.  (That it equals the average of
+    local_state's per-worker outputs is one of the pinned identities.)
+
+    Returns a dict with n (float), p (float or None), sk[l,m] (or None) and the scales the
+    tolerances use: p_abs = mean_k sum_j |xi_j u_kj|, sk_abs[l,m] = mean_k per-cell sum of
+    |u_kj|, sk_cnt[l,m], u_mean_abs = mean over k, j of |u_kj|.
+    """
+    w64 = widen(w, dtype)
+    w0 = np.asarray(w_t0, np.float32).astype(np.float64)
+    u = drift(w64, w0)
+    K = u.shape[0]
+    u_bar = u.sum(axis=0) / K
+    out = {"n": float(sq_norms(u).sum() / K), "p": None, "p_abs": None, "sk": None, "sk_abs": None,
+           "sk_cnt": None, "u_mean_abs": float(np.abs(u).mean())}
+    if xi is not None:
+        x = np.asarray(xi, np.float32).astype(np.float64)
+        out["p"] = float(u_bar @ x)
+        out["p_abs"] = float(abs_projections(u, x).sum() / K)
+    if coef is not None:
+        out["sk"] = ams_sketch(u_bar, coef, m)
+        out["sk_abs"] = ams_sketch_abs(np.abs(u).sum(axis=0) / K, coef, m)
+        out["sk_cnt"] = ams_sketch_counts(u.shape[1], coef, m)
+    return out
+
+
 # --------------------------------------------------------------------------- #
 # averaged state, estimates, decision (Algorithm 1, lines 7-8)
 # --------------------------------------------------------------------------- #

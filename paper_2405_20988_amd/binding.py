@@ -83,12 +83,17 @@ def load_library():
     lib.fda_local_state.argtypes = [vp, vp, vp, vp, vp, vp]
     lib.fda_estimate_variance.argtypes = [vp, vp, C.c_double, C.c_double, vp,
                                           C.POINTER(FdaEstimate), vp]
+    lib.fda_mean_state.argtypes = [vp, vp, vp, vp, vp, vp]
+    lib.fda_estimate_variance_mean.argtypes = [vp, vp, C.c_double, C.c_double, vp,
+                                               C.POINTER(FdaEstimate), vp]
+    lib.fda_last_mean_state_path.argtypes = [vp, C.POINTER(C.c_int32), vp]
     lib.fda_sync.argtypes = [vp, vp, vp, vp, i32p, vp]
     lib.fda_update_xi.argtypes = [vp, vp, vp, vp, i32p, vp]
     lib.fda_last_state_path.argtypes = [vp, C.POINTER(C.c_int32), vp]
     lib.fda_profile_enable.argtypes = [vp, C.c_int]
     lib.fda_profile_read.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(C.c_int64), C.c_int]
-    for name in ("fda_last_state_path", "fda_profile_enable", "fda_profile_read", "fda_plan", "fda_workspace_bytes", "fda_create", "fda_destroy",
+    for name in ("fda_mean_state", "fda_estimate_variance_mean", "fda_last_mean_state_path",
+                 "fda_last_state_path", "fda_profile_enable", "fda_profile_read", "fda_plan", "fda_workspace_bytes", "fda_create", "fda_destroy",
                  "fda_state_floats", "fda_get_plan", "fda_local_state",
                  "fda_estimate_variance", "fda_sync", "fda_update_xi"):
         getattr(lib, name).restype = C.c_int
@@ -172,6 +177,20 @@ def fda_estimate_variance(ctx: int, state: int, theta: float, tie_tol: float, ou
     return host
 
 
+def fda_mean_state(ctx: int, w: int, w_t0: int, xi: int | None, mean_state: int, stream: int = 0) -> None:
+    _check(load_library().fda_mean_state(ctx, w, w_t0, xi, mean_state, stream), "fda_mean_state")
+
+
+def fda_estimate_variance_mean(ctx: int, mean_state: int, theta: float, tie_tol: float, out_dev: int,
+                               want_host: bool = True, stream: int = 0):
+    """Returns the host copy of the result (an FdaEstimate) if want_host, else None."""
+    host = FdaEstimate() if want_host else None
+    _check(load_library().fda_estimate_variance_mean(ctx, mean_state, theta, tie_tol, out_dev,
+                                                     C.byref(host) if want_host else None, stream),
+           "fda_estimate_variance_mean")
+    return host
+
+
 def fda_sync(ctx: int, w: int, w_t0: int, w_prev: int | None, pred_dev: int | None = None,
              stream: int = 0) -> None:
     _check(load_library().fda_sync(ctx, w, w_t0, w_prev, pred_dev, stream), "fda_sync")
@@ -198,4 +217,11 @@ def fda_last_state_path(ctx: int, stream: int = 0) -> int:
     """0 / 1 / 2: the last fda_local_state used 32-bit, 64-bit integer or fp64 sketch cells."""
     v = C.c_int32(0)
     _check(load_library().fda_last_state_path(ctx, C.byref(v), stream), "fda_last_state_path")
+    return int(v.value)
+
+
+def fda_last_mean_state_path(ctx: int, stream: int = 0) -> int:
+    """0 / 1: the last fda_mean_state used integer sums in 64-bit cells, or fp64."""
+    v = C.c_int32(0)
+    _check(load_library().fda_last_mean_state_path(ctx, C.byref(v), stream), "fda_last_mean_state_path")
     return int(v.value)

@@ -16,11 +16,12 @@ OBJ_DIR = os.path.join(PKG, "_build")
 LIB_PATH = os.path.join(LIB_DIR, "libfda.so")
 UNITS = (["fda_api"] +
          ["fda_state_narrow_%s_kc%d" % (t, k) for t in ("f32", "bf16") for k in (1, 2, 3, 4, 5, 6, 8)] +
-         ["fda_state_wide_%s_%s" % (t, c) for t in ("f32", "bf16") for c in ("i64", "f64")])
+         ["fda_state_wide_%s_%s" % (t, c) for t in ("f32", "bf16") for c in ("i64", "f64")] +
+         ["fda_mean_%s_%s" % (t, c) for t in ("f32", "bf16") for c in ("i64", "f64")])
 SOURCES = [os.path.join(CSRC, u + ".hip") for u in UNITS]
 DEPENDS = SOURCES + [os.path.join(CSRC, n) for n in
                      ("fda_kernels.hpp", "fda_small_kernels.hpp", "fda_state_launch.hpp", "fda_state_narrow.inc",
-                      "fda_state_wide.inc")] + \
+                      "fda_state_wide.inc", "fda_mean_kernel.hpp", "fda_mean_launch.hpp", "fda_mean.inc")] + \
     [os.path.join(ROOT, "include", "fda.h")]
 
 

@@ -10,6 +10,7 @@
 #include "fda.h"
 #include "fda_small_kernels.hpp"
 #include "fda_state_launch.hpp"
+#include "fda_mean_launch.hpp"
 
 namespace {
 
@@ -49,9 +50,15 @@ struct Split {
   int G, R, kcnt_max, rcnt_max, KC, LR, P, stride;
   int64_t chunk, lds_bytes;
 };
+// How one mean-state pass is spread over the chip.
+struct MeanSplit {
+  int R, rcnt_max, P, occ;
+  int64_t chunk, lds_bytes;
+};
 struct Plan {
   Split narrow;     // 32-bit cells: the pass every call runs
   Split wide;       // 8-byte cells: the 64-bit integer and fp64 passes
+  MeanSplit mean;   // fda_mean_state
   int vec;          // elements per 16-byte slab load
   int64_t cells, S, dpad;
   int64_t off_np, off_sk, off_xi, off_scale, off_smax, off_ssum, off_nmax, off_est, off_ticket, off_table,
@@ -165,6 +172,36 @@ int make_split(const fda_desc* d, int cus, int64_t lds_cu, int cell_bytes, Split
   return FDA_OK;
 }
 
+int make_mean_split(const fda_desc* d, int cus, int64_t lds_cu, MeanSplit* ms) {
+  const bool sk = (d->variants & FDA_VARIANT_SKETCH) != 0;
+  const int l = sk ? d->l : 1;
+  // every workgroup reads all K workers; its sketch rows (8-byte cells) must fit in LDS, and the
+  // fewer row groups the better, since each repeats all the loads
+  int R = 0, rc = 0;
+  int64_t bytes = 0;
+  for (int cand = 1; cand <= l; ++cand) {
+    rc = (l + cand - 1) / cand;
+    if (rc > fda::kMeanMaxLR) continue;
+    bytes = (sk ? ((int64_t)rc * d->m + fda::kDummyCells) * 8 : 0) + kLdsReserve;
+    if (bytes <= lds_cu) { R = cand; break; }
+  }
+  if (R == 0)
+    return fail(FDA_ERANGE, "one row of an m = %d sketch does not fit in %lld bytes of LDS", d->m,
+                (long long)lds_cu);
+  ms->R = R;
+  ms->rcnt_max = rc;
+  ms->lds_bytes = bytes;
+  ms->occ = (2 * bytes <= lds_cu) ? 2 : 1;       // two workgroups per CU when the registers and LDS allow
+  const int64_t tile = (int64_t)fda::kStateThreads * fda::kStateV;
+  const int64_t tiles = (d->d + tile - 1) / tile;
+  int64_t P = (int64_t)cus * ms->occ / R / 8 * 8;  // one round of resident workgroups
+  if (P < 8) P = 8;
+  if (P > round_up(tiles, 8)) P = round_up(tiles, 8);
+  ms->P = (int)P;
+  ms->chunk = round_up((d->d + P - 1) / P, tile);
+  return FDA_OK;
+}
+
 int make_plan(const fda_desc* d, int cus, int64_t lds_cu, Plan* pl) {
   if (cus < 1 || lds_cu < 16384) return fail(FDA_EINVAL, "bad device description");
   const bool sk = (d->variants & FDA_VARIANT_SKETCH) != 0;
@@ -175,12 +212,18 @@ int make_plan(const fda_desc* d, int cus, int64_t lds_cu, Plan* pl) {
   if (rc != FDA_OK) return rc;
   rc = make_split(d, cus, lds_cu, 4, &pl->narrow);
   if (rc != FDA_OK) return rc;
+  rc = make_mean_split(d, cus, lds_cu, &pl->mean);
+  if (rc != FDA_OK) return rc;
+  // the per-workgroup partials of fda_local_state and of fda_mean_state share one region
   const int64_t Pmax = pl->narrow.P > pl->wide.P ? pl->narrow.P : pl->wide.P;
+  int64_t np_bytes = (int64_t)pl->narrow.P * d->K * 2 * 8, sk_bytes = Pmax * d->K * pl->cells * 8;
+  if (np_bytes < (int64_t)pl->mean.P * 2 * 8) np_bytes = (int64_t)pl->mean.P * 2 * 8;
+  if (sk_bytes < (int64_t)pl->mean.P * pl->cells * 8) sk_bytes = (int64_t)pl->mean.P * pl->cells * 8;
   pl->off_np = 0;
-  pl->off_sk = round_up(pl->off_np + (int64_t)pl->narrow.P * d->K * 2 * 8, kAlign);
-  pl->off_xi = round_up(pl->off_sk + Pmax * d->K * pl->cells * 8, kAlign);
+  pl->off_sk = round_up(pl->off_np + np_bytes, kAlign);
+  pl->off_xi = round_up(pl->off_sk + sk_bytes, kAlign);
   pl->off_scale = round_up(pl->off_xi + kXiBlocks * 8, kAlign);
-  pl->off_smax = round_up(pl->off_scale + (int64_t)sizeof(fda::ScaleInfo), kAlign);
+  pl->off_smax = round_up(pl->off_scale + 2 * (int64_t)sizeof(fda::ScaleInfo), kAlign);
   pl->off_ssum = round_up(pl->off_smax + kScaleBlocks * 4, kAlign);
   pl->off_nmax = round_up(pl->off_ssum + kScaleBlocks * 8, kAlign);
   pl->off_est = round_up(pl->off_nmax + 8, kAlign);
@@ -246,6 +289,21 @@ int dispatch_any(int dtype, int cell, const Split& sp, const fda::StateParams* p
   return FDA_OK;
 }
 
+int dispatch_mean(int dtype, int cell, const MeanSplit& ms, const fda::MeanParams* prm, hipStream_t st) {
+  const size_t lds = (size_t)ms.lds_bytes;
+  hipError_t e;
+  if (dtype == FDA_F32)
+    e = cell == fda::kCellI64 ? fda::launch_mean_f32_i64(ms.rcnt_max, prm, lds, st)
+                              : fda::launch_mean_f32_f64(ms.rcnt_max, prm, lds, st);
+  else
+    e = cell == fda::kCellI64 ? fda::launch_mean_bf16_i64(ms.rcnt_max, prm, lds, st)
+                              : fda::launch_mean_bf16_f64(ms.rcnt_max, prm, lds, st);
+  if (e == hipErrorInvalidValue)
+    return fail(FDA_EINVAL, "internal: no mean-state kernel for %d rows per workgroup", ms.rcnt_max);
+  if (e != hipSuccess) return fail(FDA_EHIP, "mean-state kernel launch failed: %s", hipGetErrorString(e));
+  return FDA_OK;
+}
+
 constexpr int kProfSlots = 64;
 
 }  // namespace
@@ -290,6 +348,86 @@ int prof_drain(fda_ctx* c) {
     c->prof_launches += 1;
   }
   c->prof_pending = 0;
+  return FDA_OK;
+}
+
+// Start / stop of one timed kernel (fda_profile_enable); slot < 0: timing is off.
+int prof_begin(fda_ctx* c, hipStream_t st, int* slot) {
+  *slot = -1;
+  if (!c->prof_on) return FDA_OK;
+  if (c->prof_pending == kProfSlots) {
+    int rc = prof_drain(c);
+    if (rc != FDA_OK) return rc;
+  }
+  *slot = c->prof_pending;
+  FDA_HIP(hipEventRecord(c->prof_start[*slot], st));
+  return FDA_OK;
+}
+int prof_end(fda_ctx* c, hipStream_t st, int slot) {
+  if (slot < 0) return FDA_OK;
+  FDA_HIP(hipEventRecord(c->prof_stop[slot], st));
+  c->prof_pending = slot + 1;
+  return FDA_OK;
+}
+
+// Before the first sketch of a context: the hash table and the cell counts.  Then, per call, the
+// fixed-point units from a sample of the drifts (this also clears the flags in *scale).
+int prepare_sketch(fda_ctx* ctx, const void* w, const float* w_t0, fda::ScaleInfo* scale, hipStream_t st) {
+  const fda_desc& d = ctx->desc;
+  const Plan& pl = ctx->plan;
+  int rc0 = clear_tickets_once(ctx, st);
+  if (rc0 != FDA_OK) return rc0;
+  float* smax = reinterpret_cast<float*>(ctx->ws + pl.off_smax);
+  double* ssum = reinterpret_cast<double*>(ctx->ws + pl.off_ssum);
+  unsigned int* nmax = reinterpret_cast<unsigned int*>(ctx->ws + pl.off_nmax);
+  if (!ctx->counted) {
+    // once per context: the largest number of coordinates any workgroup puts in one cell,
+    // for the partitioning of the 32-bit pass ([0]) and of the 8-byte passes ([1]) ...
+    hipLaunchKernelGGL(fda::clear_u32_kernel, dim3(1), dim3(64), 0, st, nmax, 2);
+    FDA_HIP(hipGetLastError());
+    hipLaunchKernelGGL(fda::cell_count_kernel, dim3(pl.narrow.P * d.l), dim3(fda::kStateThreads),
+                       (size_t)d.m * 4, st, ctx->coef, d.l, d.m, (long long)d.d,
+                       (long long)pl.narrow.chunk, nmax);
+    FDA_HIP(hipGetLastError());
+    hipLaunchKernelGGL(fda::cell_count_kernel, dim3(pl.wide.P * d.l), dim3(fda::kStateThreads),
+                       (size_t)d.m * 4, st, ctx->coef, d.l, d.m, (long long)d.d,
+                       (long long)pl.wide.chunk, nmax + 1);
+    FDA_HIP(hipGetLastError());
+    // ... and the hash of every (row, coordinate), tabulated
+    const long long groups = pl.dpad / 8;
+    hipLaunchKernelGGL(fda::hash_table_kernel,
+                       dim3((unsigned)((groups + fda::kSmallThreads - 1) / fda::kSmallThreads), d.l),
+                       dim3(fda::kSmallThreads), 0, st, ctx->coef, d.m, (long long)d.d,
+                       (long long)pl.dpad, reinterpret_cast<uint16_t*>(ctx->ws + pl.off_table));
+    FDA_HIP(hipGetLastError());
+    ctx->counted = true;
+  }
+  const int samples = (int)(d.d < kScaleSamples ? d.d : kScaleSamples);
+  const int sblocks = (samples + fda::kSmallThreads - 1) / fda::kSmallThreads;
+  unsigned int* ticket = reinterpret_cast<unsigned int*>(ctx->ws + pl.off_ticket);
+  if (d.dtype == FDA_F32)
+    hipLaunchKernelGGL(fda::scale_kernel<float>, dim3(sblocks), dim3(fda::kSmallThreads), 0, st,
+                       static_cast<const float*>(w), w_t0, d.K, (long long)d.d, (long long)d.row_stride,
+                       samples, smax, ssum, ticket, nmax, scale);
+  else
+    hipLaunchKernelGGL(fda::scale_kernel<fda::bf16_t>, dim3(sblocks), dim3(fda::kSmallThreads), 0, st,
+                       static_cast<const fda::bf16_t*>(w), w_t0, d.K, (long long)d.d,
+                       (long long)d.row_stride, samples, smax, ssum, ticket, nmax, scale);
+  FDA_HIP(hipGetLastError());
+  return FDA_OK;
+}
+
+// The argument checks fda_local_state and fda_mean_state share.
+int check_state_args(const fda_ctx* ctx, const void* w, const float* w_t0, const float* xi, const float* out) {
+  if (ctx == nullptr || w == nullptr || w_t0 == nullptr || out == nullptr)
+    return fail(FDA_EINVAL, "NULL argument");
+  const fda_desc& d = ctx->desc;
+  if ((d.variants & FDA_VARIANT_LINEAR) && xi == nullptr)
+    return fail(FDA_EINVAL, "xi is NULL but FDA_VARIANT_LINEAR is requested");
+  const int esz = d.dtype == FDA_F32 ? 4 : 2;
+  if (reinterpret_cast<uintptr_t>(w) % esz != 0 || reinterpret_cast<uintptr_t>(w_t0) % 4 != 0 ||
+      reinterpret_cast<uintptr_t>(out) % 4 != 0 || (xi && reinterpret_cast<uintptr_t>(xi) % 4 != 0))
+    return fail(FDA_EINVAL, "pointer not aligned to its element type");
   return FDA_OK;
 }
 }  // namespace
@@ -368,6 +506,9 @@ int fda_create(fda_ctx** ctx, const fda_desc* desc, void* workspace, size_t work
     return fail(FDA_EHIP, "hipGetDevice failed");
   }
   rc = dispatch_any(desc->dtype, fda::kCellI32, pl.narrow, nullptr, nullptr);
+  if (rc == FDA_OK) rc = dispatch_mean(desc->dtype, fda::kCellI64, pl.mean, nullptr, nullptr);
+  if (rc == FDA_OK && (desc->variants & FDA_VARIANT_SKETCH))
+    rc = dispatch_mean(desc->dtype, fda::kCellF64, pl.mean, nullptr, nullptr);
   if (rc == FDA_OK && (desc->variants & FDA_VARIANT_SKETCH)) {
     rc = dispatch_any(desc->dtype, fda::kCellI64, pl.wide, nullptr, nullptr);
     if (rc == FDA_OK) rc = dispatch_any(desc->dtype, fda::kCellF64, pl.wide, nullptr, nullptr);
@@ -402,6 +543,18 @@ int fda_last_state_path(fda_ctx* ctx, int32_t* path, void* stream) {
   FDA_HIP(hipMemcpyAsync(&info, ctx->ws + ctx->plan.off_scale, sizeof(info), hipMemcpyDeviceToHost, st));
   FDA_HIP(hipStreamSynchronize(st));
   *path = info.overflow64 ? 2 : (info.flag32 ? 1 : 0);
+  return FDA_OK;
+}
+
+int fda_last_mean_state_path(fda_ctx* ctx, int32_t* path, void* stream) {
+  if (ctx == nullptr || path == nullptr) return fail(FDA_EINVAL, "NULL argument");
+  if (!(ctx->desc.variants & FDA_VARIANT_SKETCH)) { *path = -1; return FDA_OK; }
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  fda::ScaleInfo info;
+  FDA_HIP(hipMemcpyAsync(&info, ctx->ws + ctx->plan.off_scale + sizeof(fda::ScaleInfo), sizeof(info),
+                         hipMemcpyDeviceToHost, st));
+  FDA_HIP(hipStreamSynchronize(st));
+  *path = info.flagm ? 1 : 0;
   return FDA_OK;
 }
 
@@ -446,17 +599,13 @@ int fda_get_plan(const fda_ctx* ctx, fda_plan_info* out) {
 
 int fda_local_state(fda_ctx* ctx, const void* w, const float* w_t0, const float* xi,
                     float* state, void* stream) {
-  if (ctx == nullptr || w == nullptr || w_t0 == nullptr || state == nullptr)
-    return fail(FDA_EINVAL, "NULL argument");
+  int rc = check_state_args(ctx, w, w_t0, xi, state);
+  if (rc != FDA_OK) return rc;
   const fda_desc& d = ctx->desc;
   const Plan& pl = ctx->plan;
   const bool lin = (d.variants & FDA_VARIANT_LINEAR) != 0;
   const bool sk = (d.variants & FDA_VARIANT_SKETCH) != 0;
-  if (lin && xi == nullptr) return fail(FDA_EINVAL, "xi is NULL but FDA_VARIANT_LINEAR is requested");
   const int esz = d.dtype == FDA_F32 ? 4 : 2;
-  if (reinterpret_cast<uintptr_t>(w) % esz != 0 || reinterpret_cast<uintptr_t>(w_t0) % 4 != 0 ||
-      reinterpret_cast<uintptr_t>(state) % 4 != 0 || (xi && reinterpret_cast<uintptr_t>(xi) % 4 != 0))
-    return fail(FDA_EINVAL, "pointer not aligned to its element type");
   hipStream_t st = static_cast<hipStream_t>(stream);
 
   auto params_for = [&](const Split& sp) {
@@ -479,63 +628,16 @@ int fda_local_state(fda_ctx* ctx, const void* w, const float* w_t0, const float*
   const fda::StateParams prm64 = params_for(pl.wide);
 
   if (sk) {
-    int rc0 = clear_tickets_once(ctx, st);
-    if (rc0 != FDA_OK) return rc0;
-    float* smax = reinterpret_cast<float*>(ctx->ws + pl.off_smax);
-    double* ssum = reinterpret_cast<double*>(ctx->ws + pl.off_ssum);
-    unsigned int* nmax = reinterpret_cast<unsigned int*>(ctx->ws + pl.off_nmax);
-    if (!ctx->counted) {
-      // once per context: the largest number of coordinates any workgroup puts in one cell,
-      // for the partitioning of the 32-bit pass ([0]) and of the 8-byte passes ([1]) ...
-      hipLaunchKernelGGL(fda::clear_u32_kernel, dim3(1), dim3(64), 0, st, nmax, 2);
-      FDA_HIP(hipGetLastError());
-      hipLaunchKernelGGL(fda::cell_count_kernel, dim3(pl.narrow.P * d.l), dim3(fda::kStateThreads),
-                         (size_t)d.m * 4, st, ctx->coef, d.l, d.m, (long long)d.d,
-                         (long long)pl.narrow.chunk, nmax);
-      FDA_HIP(hipGetLastError());
-      hipLaunchKernelGGL(fda::cell_count_kernel, dim3(pl.wide.P * d.l), dim3(fda::kStateThreads),
-                         (size_t)d.m * 4, st, ctx->coef, d.l, d.m, (long long)d.d,
-                         (long long)pl.wide.chunk, nmax + 1);
-      FDA_HIP(hipGetLastError());
-      // ... and the hash of every (row, coordinate), tabulated
-      const long long groups = pl.dpad / 8;
-      hipLaunchKernelGGL(fda::hash_table_kernel,
-                         dim3((unsigned)((groups + fda::kSmallThreads - 1) / fda::kSmallThreads), d.l),
-                         dim3(fda::kSmallThreads), 0, st, ctx->coef, d.m, (long long)d.d,
-                         (long long)pl.dpad, reinterpret_cast<uint16_t*>(ctx->ws + pl.off_table));
-      FDA_HIP(hipGetLastError());
-      ctx->counted = true;
-    }
-    // fixed-point units for this call, from a sample of the drifts; also clears the flags
-    const int samples = (int)(d.d < kScaleSamples ? d.d : kScaleSamples);
-    const int sblocks = (samples + fda::kSmallThreads - 1) / fda::kSmallThreads;
-    unsigned int* ticket = reinterpret_cast<unsigned int*>(ctx->ws + pl.off_ticket);
-    if (d.dtype == FDA_F32)
-      hipLaunchKernelGGL(fda::scale_kernel<float>, dim3(sblocks), dim3(fda::kSmallThreads), 0, st,
-                         static_cast<const float*>(w), w_t0, d.K, (long long)d.d, (long long)d.row_stride,
-                         samples, smax, ssum, ticket, nmax, prm32.scale);
-    else
-      hipLaunchKernelGGL(fda::scale_kernel<fda::bf16_t>, dim3(sblocks), dim3(fda::kSmallThreads), 0, st,
-                         static_cast<const fda::bf16_t*>(w), w_t0, d.K, (long long)d.d,
-                         (long long)d.row_stride, samples, smax, ssum, ticket, nmax, prm32.scale);
-    FDA_HIP(hipGetLastError());
+    rc = prepare_sketch(ctx, w, w_t0, prm32.scale, st);
+    if (rc != FDA_OK) return rc;
   }
-
   int slot = -1;
-  if (ctx->prof_on) {
-    if (ctx->prof_pending == kProfSlots) {
-      int rc0 = prof_drain(ctx);
-      if (rc0 != FDA_OK) return rc0;
-    }
-    slot = ctx->prof_pending;
-    FDA_HIP(hipEventRecord(ctx->prof_start[slot], st));
-  }
-  int rc = dispatch_any(d.dtype, fda::kCellI32, pl.narrow, &prm32, st);
+  rc = prof_begin(ctx, st, &slot);
   if (rc != FDA_OK) return rc;
-  if (slot >= 0) {
-    FDA_HIP(hipEventRecord(ctx->prof_stop[slot], st));
-    ctx->prof_pending = slot + 1;
-  }
+  rc = dispatch_any(d.dtype, fda::kCellI32, pl.narrow, &prm32, st);
+  if (rc != FDA_OK) return rc;
+  rc = prof_end(ctx, st, slot);
+  if (rc != FDA_OK) return rc;
   if (sk) {
     // these two return at once unless the pass before them could not represent the drifts
     rc = dispatch_any(d.dtype, fda::kCellI64, pl.wide, &prm64, st);
@@ -553,8 +655,61 @@ int fda_local_state(fda_ctx* ctx, const void* w, const float* w_t0, const float*
   return FDA_OK;
 }
 
-int fda_estimate_variance(fda_ctx* ctx, const float* state, double theta, double tie_tol,
-                          fda_estimate* out_dev, fda_estimate* out_host, void* stream) {
+int fda_mean_state(fda_ctx* ctx, const void* w, const float* w_t0, const float* xi,
+                   float* mean_state, void* stream) {
+  int rc = check_state_args(ctx, w, w_t0, xi, mean_state);
+  if (rc != FDA_OK) return rc;
+  const fda_desc& d = ctx->desc;
+  const Plan& pl = ctx->plan;
+  const MeanSplit& ms = pl.mean;
+  const bool lin = (d.variants & FDA_VARIANT_LINEAR) != 0;
+  const bool sk = (d.variants & FDA_VARIANT_SKETCH) != 0;
+  const int esz = d.dtype == FDA_F32 ? 4 : 2;
+  // a cell's integer sum stays below K * chunk * 2^30 in magnitude
+  if (sk && (double)d.K * (double)ms.chunk >= 8589934592.0)
+    return fail(FDA_ERANGE, "K * coordinates per workgroup must stay below 2^33");
+  hipStream_t st = static_cast<hipStream_t>(stream);
+
+  fda::MeanParams prm;
+  prm.w = w; prm.w_t0 = w_t0; prm.xi = xi;
+  prm.row_stride = d.row_stride; prm.d = d.d; prm.chunk = ms.chunk;
+  prm.K = d.K; prm.l = sk ? d.l : 0; prm.m = sk ? d.m : 0;
+  prm.R = ms.R; prm.P = ms.P;
+  prm.do_lin = lin; prm.do_sk = sk;
+  // whole-vector loads: 16 bytes of w_t0 / xi, and 16 (fp32) or 8 (bf16) bytes of a slab row
+  prm.vec_ok = aligned16(w_t0) && (!lin || aligned16(xi)) &&
+               reinterpret_cast<uintptr_t>(w) % (4 * esz) == 0 && (d.row_stride * esz) % (4 * esz) == 0;
+  prm.part_np = reinterpret_cast<double*>(ctx->ws + pl.off_np);
+  prm.part_sk = ctx->ws + pl.off_sk;
+  prm.scale = reinterpret_cast<fda::ScaleInfo*>(ctx->ws + pl.off_scale) + 1;
+  prm.table = reinterpret_cast<const uint16_t*>(ctx->ws + pl.off_table);
+  prm.dpad = pl.dpad;
+
+  if (sk) {
+    rc = prepare_sketch(ctx, w, w_t0, prm.scale, st);
+    if (rc != FDA_OK) return rc;
+  }
+  int slot = -1;
+  rc = prof_begin(ctx, st, &slot);
+  if (rc != FDA_OK) return rc;
+  rc = dispatch_mean(d.dtype, fda::kCellI64, ms, &prm, st);
+  if (rc != FDA_OK) return rc;
+  rc = prof_end(ctx, st, slot);
+  if (rc != FDA_OK) return rc;
+  if (sk) {
+    // returns at once unless a drift was too large for the integers
+    rc = dispatch_mean(d.dtype, fda::kCellF64, ms, &prm, st);
+    if (rc != FDA_OK) return rc;
+  }
+  const int blocks = (int)((pl.S + 31) / 32);
+  hipLaunchKernelGGL(fda::merge_mean_kernel, dim3(blocks), dim3(fda::kSmallThreads), 0, st,
+                     prm.part_np, prm.part_sk, prm.scale, mean_state, d.K, (int)pl.cells, ms.P);
+  FDA_HIP(hipGetLastError());
+  return FDA_OK;
+}
+
+static int estimate_rows(fda_ctx* ctx, const float* state, int rows, double theta, double tie_tol,
+                         fda_estimate* out_dev, fda_estimate* out_host, void* stream) {
   if (ctx == nullptr || state == nullptr || out_dev == nullptr)
     return fail(FDA_EINVAL, "NULL argument");
   if (reinterpret_cast<uintptr_t>(out_dev) % 8 != 0) return fail(FDA_EINVAL, "out_dev must be 8-byte aligned");
@@ -566,7 +721,7 @@ int fda_estimate_variance(fda_ctx* ctx, const float* state, double theta, double
   const int eblocks = sk ? d.l * bpr : 1;
   int rc = clear_tickets_once(ctx, st);
   if (rc != FDA_OK) return rc;
-  hipLaunchKernelGGL(fda::estimate_kernel, dim3(eblocks), dim3(fda::kSmallThreads), 0, st, state, d.K,
+  hipLaunchKernelGGL(fda::estimate_kernel, dim3(eblocks), dim3(fda::kSmallThreads), 0, st, state, rows,
                      sk ? d.l : 0, sk ? d.m : 1, d.variants, d.eps, theta, tie_tol,
                      reinterpret_cast<double*>(ctx->ws + ctx->plan.off_est),
                      reinterpret_cast<unsigned int*>(ctx->ws + ctx->plan.off_ticket) + 1, out_dev);
@@ -576,6 +731,16 @@ int fda_estimate_variance(fda_ctx* ctx, const float* state, double theta, double
     FDA_HIP(hipStreamSynchronize(st));
   }
   return FDA_OK;
+}
+
+int fda_estimate_variance(fda_ctx* ctx, const float* state, double theta, double tie_tol,
+                          fda_estimate* out_dev, fda_estimate* out_host, void* stream) {
+  return estimate_rows(ctx, state, ctx ? ctx->desc.K : 0, theta, tie_tol, out_dev, out_host, stream);
+}
+
+int fda_estimate_variance_mean(fda_ctx* ctx, const float* mean_state, double theta, double tie_tol,
+                               fda_estimate* out_dev, fda_estimate* out_host, void* stream) {
+  return estimate_rows(ctx, mean_state, 1, theta, tie_tol, out_dev, out_host, stream);
 }
 
 int fda_sync(fda_ctx* ctx, void* w, float* w_t0, float* w_prev, const int32_t* pred_dev,

@@ -40,7 +40,10 @@ struct ScaleInfo {
   float bound64;          // ... and below this for the 64-bit cells
   int flag32;             // set: the 32-bit result is void (range, or a cell wrapped) -> 64-bit pass
   int overflow64;         // set: the 64-bit cells cannot hold the drifts either -> fp64 pass
-  int pad;
+  int flagm;              // mean-state kernel: set when a drift reached boundm -> its fp64 pass
+  double invSm;
+  float Sm;               // mean-state kernel: a drift u enters as the integer round(u * Sm)
+  float boundm;           // ... and every |u| must stay below this
 };
 
 struct StateParams {

@@ -111,7 +111,8 @@ __global__ void clear_u32_kernel(unsigned int* p, int n) {
 __device__ inline ScaleInfo choose_scale(float amax, double mean, const unsigned int* nmax) {
   ScaleInfo s;
   s.S64 = 1.0; s.invS64 = 1.0; s.invS32 = 1.0; s.S32 = 1.0f;
-  s.bound32 = 0.0f; s.bound64 = 0.0f; s.flag32 = 0; s.overflow64 = 0; s.pad = 0;
+  s.bound32 = 0.0f; s.bound64 = 0.0f; s.flag32 = 0; s.overflow64 = 0;
+  s.flagm = 0; s.invSm = 1.0; s.Sm = 1.0f; s.boundm = 0.0f;
   if (amax > 0.0f && isfinite(amax) && mean > 0.0) {
     // ---- 64-bit cells
     int cb = 0;
@@ -130,6 +131,16 @@ __device__ inline ScaleInfo choose_scale(float amax, double mean, const unsigned
     while (cb32 < 32 && (1ull << cb32) <= (unsigned long long)nmax[0]) ++cb32;
     const int shrink = cb32 > 12 ? (cb32 - 12 + 1) / 2 : 0;
     const int em = ilogb(mean);                // 2^em <= mean < 2^(em+1)
+    // ---- mean-state kernel: 32-bit terms, 64-bit sums, the mean magnitude at [2^18, 2^19)
+    const int emn = 18 - em;
+    if (emn > 120 || emn < -120) {
+      s.flagm = 1;
+    } else {
+      s.Sm = ldexpf(1.0f, emn);
+      s.invSm = ldexp(1.0, -emn);
+      s.boundm = (30 - emn > 127) ? 3.0e38f : ldexpf(1.0f, 30 - emn);
+      if (!(amax < s.boundm)) s.flagm = 1;
+    }
     const int e32 = 18 - shrink - em;
     if (e32 > 120 || e32 < -120 || shrink > 1) {
       s.flag32 = 1;
@@ -241,6 +252,46 @@ merge_kernel(const double* __restrict__ part_np, const void* __restrict__ part_s
 #pragma unroll
     for (int q = 0; q < 8; ++q) t += sh[q][o];
     state[idx] = (float)(t * unit);
+  }
+}
+
+// mean_state[s] = (sum over the partitions) / K, for the partials of mean_state_kernel: the two
+// scalar sums in fp64, the sketch cells as 64-bit integers in units of 1/Sm (or fp64 when the
+// call went down the fp64 path).  Same fixed shape as merge_kernel.
+__global__ void __launch_bounds__(kSmallThreads)
+merge_mean_kernel(const double* __restrict__ part_np, const void* __restrict__ part_sk,
+                  const ScaleInfo* __restrict__ scale, float* __restrict__ mean_state, int K,
+                  int cells, int P) {
+  __shared__ double sh[8][32];
+  const int S = 2 + cells;
+  const int o = threadIdx.x & 31, slice = threadIdx.x >> 5;
+  const int s = blockIdx.x * 32 + o;
+  const bool live = s < S;
+  double acc = 0.0, unit = 1.0;
+  if (live) {
+    if (s < 2) {
+      for (int p = slice; p < P; p += 8) acc += part_np[(size_t)p * 2 + s];
+    } else {
+      const int c = s - 2;
+      if (scale->flagm != 0) {
+        const double* pd = reinterpret_cast<const double*>(part_sk);
+        for (int p = slice; p < P; p += 8) acc += pd[(size_t)p * cells + c];
+      } else {
+        unit = scale->invSm;
+        const long long* pi = reinterpret_cast<const long long*>(part_sk);
+        long long isum = 0;                       // exact
+        for (int p = slice; p < P; p += 8) isum += pi[(size_t)p * cells + c];
+        acc = (double)isum;
+      }
+    }
+  }
+  sh[slice][o] = acc;
+  __syncthreads();
+  if (live && slice == 0) {
+    double t = 0.0;
+#pragma unroll
+    for (int q = 0; q < 8; ++q) t += sh[q][o];
+    mean_state[s] = (float)(t * unit / (double)K);
   }
 }
 

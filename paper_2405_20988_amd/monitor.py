@@ -29,6 +29,7 @@ class FdaMonitor:
         self.S = B.fda_state_floats(self.ctx)
         self.plan = B.fda_get_plan(self.ctx).as_dict()
         self.state = torch.empty((self.K, self.S), dtype=torch.float32, device=self.device)
+        self.mean = torch.empty((self.S,), dtype=torch.float32, device=self.device)
         self.est_dev = torch.zeros(C.sizeof(B.FdaEstimate), dtype=torch.uint8, device=self.device)
 
     def close(self):
@@ -60,6 +61,16 @@ class FdaMonitor:
         return B.fda_estimate_variance(self.ctx, st.data_ptr(), float(theta), float(tie_tol),
                                        self.est_dev.data_ptr(), want_host, self._stream())
 
+    def mean_state(self, w, w_t0, xi=None):
+        B.fda_mean_state(self.ctx, w.data_ptr(), w_t0.data_ptr(),
+                         None if xi is None else xi.data_ptr(), self.mean.data_ptr(), self._stream())
+        return self.mean
+
+    def estimate_variance_mean(self, theta, tie_tol=1e-5, want_host=True, mean_state=None):
+        st = self.mean if mean_state is None else mean_state
+        return B.fda_estimate_variance_mean(self.ctx, st.data_ptr(), float(theta), float(tie_tol),
+                                            self.est_dev.data_ptr(), want_host, self._stream())
+
     def sync(self, w, w_t0, w_prev=None, pred=None):
         B.fda_sync(self.ctx, w.data_ptr(), w_t0.data_ptr(),
                    None if w_prev is None else w_prev.data_ptr(), self.pred_ptr(pred), self._stream())
@@ -70,6 +81,17 @@ class FdaMonitor:
 
     def last_state_path(self):
         return B.fda_last_state_path(self.ctx, self._stream())
+
+    def last_mean_state_path(self):
+        return B.fda_last_mean_state_path(self.ctx, self._stream())
+
+    def mean_numpy(self):
+        """(n_bar, p_bar, sk(u_bar)[l,m] or None) as float32 host values."""
+        s = self.mean.cpu().numpy()
+        sk = None
+        if self.variants & B.FDA_VARIANT_SKETCH:
+            sk = s[2:].reshape(self.desc.l, self.desc.m).copy()
+        return float(s[0]), float(s[1]), sk
 
     def state_numpy(self):
         """(n[K], p[K], sk[K,l,m] or None) as float32 host arrays."""

@@ -1,0 +1,254 @@
+"""Parity of fda_mean_state / fda_estimate_variance_mean (the average state of Algorithm 1
+line 7 computed directly, by linearity of the sketch) with the CPU fp64 oracle, and with the
+average of the per-worker states fda_local_state writes.
+
+Tolerances as for the per-worker states, with every scale averaged over the workers:
+  mean ||u_k||^2       relative 1e-5
+  <xi,u_bar>           1e-5 * mean_k sum_j |xi_j u_kj|
+  sketch cell          1e-5 * mean_k (sum_{j in cell} |u_kj| + n_cell * mean_j |u_kj|)
+Integer-valued inputs must match bit for bit after the one division by K.
+"""
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+import fda_synth as S
+from oracle import fda_oracle as O
+
+pytestmark = pytest.mark.gpu
+
+RTOL = 1e-5
+DEV = "cuda:0"
+
+
+def say(msg):
+    print(msg, flush=True)
+    sys.stdout.flush()
+
+
+def monitor_for(wl, variants=3, row_stride=None):
+    import paper_2405_20988_amd as F
+    return F.FdaMonitor(wl.K, wl.d, wl.dtype, variants, wl.l, wl.m, wl.eps, wl.hash_coef,
+                        row_stride=row_stride, device=DEV)
+
+
+def oracle_mean(wl, variants=3):
+    return O.mean_state(S.slab_to_numpy(wl.w), wl.dtype, wl.w_t0.cpu().numpy(),
+                        wl.xi.cpu().numpy() if variants & 1 else None,
+                        wl.hash_coef if variants & 2 else None, wl.m)
+
+
+def check_mean(mon, ref, variants=3):
+    n, p, sk = mon.mean_numpy()
+    assert n == pytest.approx(ref["n"], rel=RTOL)
+    if variants & 1:
+        assert abs(p - ref["p"]) <= RTOL * ref["p_abs"] + 1e-30, abs(p - ref["p"]) / ref["p_abs"]
+    else:
+        assert p == 0.0
+    if variants & 2:
+        err = np.abs(sk - ref["sk"])
+        scale = ref["sk_abs"] + ref["sk_cnt"] * ref["u_mean_abs"]
+        assert (err <= RTOL * scale + 1e-30).all(), float((err / (scale + 1e-300)).max())
+
+
+def check_estimate(est, ref, variants=3):
+    nbar = ref["mean_sqnorm"]
+    assert est.mean_sqnorm == pytest.approx(nbar, rel=RTOL)
+    if variants & 1:
+        assert abs(est.h_linear - ref["h_linear"]) <= RTOL * nbar
+        if not ref["near_tie_linear"]:
+            assert est.sync_linear == ref["sync_linear"]
+    if variants & 2:
+        assert abs(est.m2 - ref["m2"]) <= RTOL * max(nbar, ref["m2"])
+        assert abs(est.h_sketch - ref["h_sketch"]) <= RTOL * nbar
+        if not ref["near_tie_sketch"]:
+            assert est.sync_sketch == ref["sync_sketch"]
+    assert est.nonfinite == ref["nonfinite"]
+
+
+# several tiles per workgroup where the partition count saturates, ragged tails, worker counts
+# that are and are not multiples of the batch of slab rows (4 for fp32, 8 for bf16), sketches
+# that need more than one row group
+MEAN_CASES = [
+    ("cfg1", None, {}),
+    ("cfg2", 1_200_003, {}),
+    ("cfg3", 300_007, {}),
+    ("cfg4", 150_001, {}),
+    ("cfg5", 1_100_005, {}),
+    ("cfg5", 4099, {}),
+    ("cfg5", 200_003, {"K": 11}),             # bf16, a full batch of 8 rows and a ragged one of 3
+    ("cfg5", 100_001, {"K": 3}),              # bf16, a single ragged batch
+    ("cfg1", 7, {"K": 3}),
+    ("cfg2", 70_001, {"K": 1}),
+    ("cfg3", 50_000, {"K": 17}),
+    ("cfg4", 40_003, {"K": 33, "l": 4}),
+    ("cfg1", 30_001, {"l": 16, "m": 64}),     # two row groups of 8 rows
+    ("cfg1", 30_001, {"l": 1, "m": 1}),
+    ("cfg2", 20_000, {"K": 3, "l": 3, "m": 19_000}),   # one row per row group: the sketch fills LDS
+]
+
+
+@pytest.mark.parametrize("name,d,over", MEAN_CASES)
+def test_mean_state_and_estimate_parity(name, d, over):
+    say(f"[case] mean-state parity {name} d={d} {over}")
+    wl = S.make(name, device=DEV, seed=1, d=d, **over)
+    mon = monitor_for(wl)
+    mon.mean_state(wl.w, wl.w_t0, wl.xi)
+    torch.cuda.synchronize()
+    ref = oracle_mean(wl)
+    check_mean(mon, ref)
+    var = O.true_variance(O.widen(S.slab_to_numpy(wl.w), wl.dtype))
+    for mult in (0.25, 0.5, 1.0, 2.0):
+        theta = mult * var
+        est = mon.estimate_variance_mean(theta)
+        want = O.estimate_variance(np.array([ref["n"]]), np.array([ref["p"]]), ref["sk"][None], wl.eps, theta)
+        check_estimate(est, want)
+    mon.close()
+
+
+@pytest.mark.parametrize("variants", [1, 2])
+def test_mean_state_single_variant(variants):
+    say(f"[case] mean-state single variant {variants}")
+    wl = S.make("cfg3", device=DEV, seed=2, d=90_001, K=30)
+    mon = monitor_for(wl, variants)
+    mon.mean_state(wl.w, wl.w_t0, wl.xi if variants & 1 else None)
+    ref = oracle_mean(wl, variants)
+    check_mean(mon, ref, variants)
+    theta = 0.5 * O.true_variance(O.widen(S.slab_to_numpy(wl.w), wl.dtype))
+    est = mon.estimate_variance_mean(theta)
+    want = O.estimate_variance(np.array([ref["n"]]), None if ref["p"] is None else np.array([ref["p"]]),
+                               None if ref["sk"] is None else ref["sk"][None], wl.eps, theta)
+    check_estimate(est, want, variants)
+    mon.close()
+
+
+@pytest.mark.parametrize("dtype,K,d,l,m", [("f32", 4, 200_003, 5, 250), ("f32", 64, 30_001, 5, 500),
+                                            ("bf16", 8, 300_007, 7, 1000), ("f32", 16, 5, 3, 4)])
+def test_mean_state_integer_inputs_bit_exact(dtype, K, d, l, m):
+    """Small-integer drifts and a power-of-two K: every sum and the division by K are exact, so
+    the mean state must equal the oracle bit for bit -- any wrong bucket or sign would show."""
+    say(f"[case] mean-state integer inputs {dtype} K={K} d={d} {l}x{m}")
+    import paper_2405_20988_amd as F
+    g = torch.Generator(device=DEV)
+    g.manual_seed(3)
+    w_t0 = torch.randint(-16, 17, (d,), generator=g, device=DEV).float()
+    u = torch.randint(-4, 5, (K, d), generator=g, device=DEV).float()
+    xi = torch.randint(-2, 3, (d,), generator=g, device=DEV).float()
+    w = (w_t0 + u).to(torch.float32 if dtype == "f32" else torch.bfloat16)
+    coef = S.hash_coefficients(5, l)
+    mon = F.FdaMonitor(K, d, dtype, 3, l, m, 0.06, coef, device=DEV)
+    mon.mean_state(w, w_t0, xi)
+    n, p, sk = mon.mean_numpy()
+    ref = O.mean_state(S.slab_to_numpy(w), dtype, w_t0.cpu().numpy(), xi.cpu().numpy(), coef, m)
+    assert K & (K - 1) == 0
+    assert n == ref["n"] and p == ref["p"]
+    assert np.array_equal(sk.astype(np.float64), ref["sk"])
+    assert mon.last_mean_state_path() == 0
+    mon.close()
+
+
+def test_mean_state_equals_average_of_local_states():
+    """Linearity (Section 3.1) on the device's own numbers: both entry points quantize a drift
+    the same way and add integers, so the mean state is the average of the K states up to the
+    fp32 roundings of the K stored states (and the estimate agrees)."""
+    say("[case] mean state vs average of the per-worker states")
+    for name, d in (("cfg3", 400_003), ("cfg5", 900_001)):
+        wl = S.make(name, device=DEV, seed=4, d=d)
+        mon = monitor_for(wl)
+        mon.local_state(wl.w, wl.w_t0, wl.xi)
+        n, p, sk = mon.state_numpy()
+        e1 = mon.estimate_variance(1e-9)
+        mon.mean_state(wl.w, wl.w_t0, wl.xi)
+        nb, pb, skb = mon.mean_numpy()
+        e2 = mon.estimate_variance_mean(1e-9)
+        assert mon.last_state_path() == 0 and mon.last_mean_state_path() == 0
+        assert nb == pytest.approx(n.astype(np.float64).mean(), rel=1e-6)
+        w32 = wl.w.float() if wl.dtype == "bf16" else wl.w
+        p_abs = float(((w32 - wl.w_t0).abs() * wl.xi.abs()).sum(dim=1).double().mean())
+        assert abs(pb - p.astype(np.float64).mean()) <= 2e-6 * p_abs
+        avg = sk.astype(np.float64).mean(axis=0)
+        assert np.allclose(skb, avg, rtol=0, atol=2e-7 * np.abs(sk).mean(axis=0).max())
+        assert e2.h_sketch == pytest.approx(e1.h_sketch, rel=1e-5)
+        assert e2.h_linear == pytest.approx(e1.h_linear, rel=1e-5)
+        assert (e2.sync_sketch, e2.sync_linear) == (e1.sync_sketch, e1.sync_linear)
+        mon.close()
+
+
+def test_mean_state_bit_reproducible():
+    say("[case] mean state run-to-run bits")
+    wl = S.make("cfg5", device=DEV, seed=5, d=2_000_003)
+    mon = monitor_for(wl)
+    a = mon.mean_state(wl.w, wl.w_t0, wl.xi).clone()
+    for _ in range(3):
+        b = mon.mean_state(wl.w, wl.w_t0, wl.xi)
+        assert torch.equal(a, b)
+    mon.close()
+
+
+def test_mean_state_out_of_range_drifts_take_fp64_path():
+    """A few drifts far above the sampled magnitudes cannot be held by the 32-bit terms: the call
+    must notice, redo the sketch in fp64 and still meet the tolerance."""
+    say("[case] mean-state fp64 path")
+    wl = S.make("cfg3", device=DEV, seed=6, d=250_007, K=6)
+    # coordinates the strided sample of the scale does not visit
+    step = wl.d // 16384
+    for k, j in ((0, 1), (3, 7 * step + 3), (5, wl.d - 2)):
+        wl.w[k, j] += 4.0e3
+    mon = monitor_for(wl)
+    mon.mean_state(wl.w, wl.w_t0, wl.xi)
+    assert mon.last_mean_state_path() == 1
+    check_mean(mon, oracle_mean(wl))
+    # and the next call on ordinary data is back on the integer path
+    wl2 = S.make("cfg3", device=DEV, seed=7, d=250_007, K=6)
+    wl2.hash_coef = wl.hash_coef              # the context keeps the coefficients it was created with
+    mon.mean_state(wl2.w, wl2.w_t0, wl2.xi)
+    assert mon.last_mean_state_path() == 0
+    check_mean(mon, oracle_mean(wl2))
+    mon.close()
+
+
+def test_mean_state_all_zero_and_nonfinite():
+    say("[case] mean-state zero drift / non-finite")
+    wl = S.make("cfg1", device=DEV, seed=8, d=20_011)
+    w = wl.w_t0.repeat(wl.K, 1).contiguous()
+    mon = monitor_for(wl)
+    out = mon.mean_state(w, wl.w_t0, wl.xi)
+    assert not out.any()
+    est = mon.estimate_variance_mean(0.0)
+    assert est.sync_sketch == 0 and est.sync_linear == 0 and est.nonfinite == 0
+    w[2, 777] = float("inf")
+    mon.mean_state(w, wl.w_t0, wl.xi)
+    est = mon.estimate_variance_mean(1.0)
+    assert est.nonfinite == 1 and est.sync_sketch == 1 and est.sync_linear == 1
+    w[2, 777] = float("nan")
+    mon.mean_state(w, wl.w_t0, wl.xi)
+    est = mon.estimate_variance_mean(1.0)
+    assert est.nonfinite == 1 and est.sync_sketch == 1 and est.sync_linear == 1
+    mon.close()
+
+
+def test_mean_state_unaligned_and_strided():
+    """Slab rows that are not 16-byte aligned, and a row stride larger than d."""
+    say("[case] mean-state unaligned / strided")
+    import paper_2405_20988_amd as F
+    wl = S.make("cfg3", device=DEV, seed=9, d=60_001, K=5)
+    # strided rows
+    stride = wl.d + 24
+    buf = torch.zeros((wl.K, stride), dtype=wl.w.dtype, device=DEV)
+    buf[:, :wl.d] = wl.w
+    mon = monitor_for(wl, row_stride=stride)
+    mon.mean_state(buf, wl.w_t0, wl.xi)
+    ref = oracle_mean(wl)
+    check_mean(mon, ref)
+    mon.close()
+    # rows that start 4 bytes off a 16-byte boundary, odd stride
+    stride = wl.d + 3
+    flat = torch.zeros(wl.K * stride + 1, dtype=wl.w.dtype, device=DEV)
+    view = flat[1:].view(wl.K, stride)
+    view[:, :wl.d] = wl.w
+    mon = monitor_for(wl, row_stride=stride)
+    mon.mean_state(view, wl.w_t0, wl.xi)
+    check_mean(mon, ref)
+    mon.close()

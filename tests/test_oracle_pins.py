@@ -97,6 +97,43 @@ def test_hand_case_k3_d8_hash_and_sketch():
     assert est["sync_sketch"] == 1
 
 
+def test_mean_state_hand_case_and_linearity():
+    """mean_state (sketch of the mean drift) against the hand case's mean sketch, and against the
+    average of the per-worker states on random data (linearity, Section 3.1)."""
+    g = gold("hand_case_k3_d8.json")
+    coef = np.array(g["hash_coef"], np.uint32)
+    w = np.array(g["w"], np.float32)
+    w0 = np.array(g["w_t0"], np.float32)
+    ms = O.mean_state(w, "f32", w0, np.array(g["xi_a"], np.float32), coef, g["m"])
+    assert 3 * ms["n"] == pytest.approx(sum(g["sq_norms"]), rel=1e-15)
+    assert 3 * ms["p"] == pytest.approx(sum(g["proj_a"]), rel=1e-15)
+    assert np.allclose(3 * ms["sk"], g["mean_sketch_times_3"], rtol=0, atol=1e-14)
+    # a mean state is a one-worker state as far as the estimate is concerned
+    est = O.estimate_variance(np.array([ms["n"]]), np.array([ms["p"]]), ms["sk"][None], g["eps"], theta=0.0)
+    assert est["h_sketch"] == pytest.approx(g["h_sketch"], rel=1e-13)
+    assert est["h_linear"] == pytest.approx(g["h_linear_a"], rel=1e-13)
+
+    rng = np.random.default_rng(61)
+    K, d, l, m = 7, 3001, 4, 97
+    coef = rand_coef(rng, l)
+    w0 = rng.normal(size=d).astype(np.float32)
+    w = (w0[None, :] + rng.standard_t(3, size=(K, d)) * 1e-3).astype(np.float32)
+    xi = rng.normal(size=d).astype(np.float32)
+    st = O.local_state(w, "f32", w0, xi, coef, m)
+    ms = O.mean_state(w, "f32", w0, xi, coef, m)
+    assert ms["n"] == pytest.approx(st["n"].mean(), rel=1e-14)
+    assert ms["p"] == pytest.approx(st["p"].mean(), abs=1e-14 * st["p_abs"].mean())
+    assert np.allclose(ms["sk"], st["sk"].mean(axis=0), rtol=0, atol=1e-13 * st["sk_abs"].mean(axis=0).max())
+    assert np.allclose(ms["sk_abs"], st["sk_abs"].mean(axis=0), rtol=1e-13)
+    assert ms["p_abs"] == pytest.approx(st["p_abs"].mean(), rel=1e-14)
+    assert ms["u_mean_abs"] == pytest.approx(st["u_mean_abs"].mean(), rel=1e-14)
+    assert (ms["sk_cnt"] == st["sk_cnt"]).all()
+    e1 = O.estimate_variance(st["n"], st["p"], st["sk"], 0.05, theta=1e-3)
+    e2 = O.estimate_variance(np.array([ms["n"]]), np.array([ms["p"]]), ms["sk"][None], 0.05, theta=1e-3)
+    for key in ("mean_sqnorm", "mean_proj", "m2", "h_linear", "h_sketch"):
+        assert e2[key] == pytest.approx(e1[key], rel=1e-11), key
+
+
 def test_tug_of_war_m1():
     g = gold("hand_case_k3_d8.json")
     coef = np.array([[[123, 456, 789, 1011], [0, 1, 0, 0]]], np.uint32)   # bucket poly irrelevant
