@@ -139,6 +139,40 @@ def main():
                 "traffic": traffic_from_profile(workload), "algorithmic_bytes": abytes,
                 "kernel_ms": round(kern_ms_avg, 4), "launches": launches}
 
+    # The same step with the average state computed directly (fda_mean_state: sketch of the mean
+    # drift, by linearity) instead of the K per-worker states -- labelled separately, never `value`.
+    def mean_step():
+        mon.mean_state(wl.w, wl.w_t0, xi)
+        mon.estimate_variance_mean(theta, want_host=False)
+        mon.sync(wl.w, wl.w_t0, w_prev, pred=pred)
+        if args.variants & 1:
+            mon.update_xi(wl.w_t0, w_prev, wl.xi, pred=pred)
+
+    for _ in range(args.warmup):
+        mean_step()
+    torch.cuda.synchronize()
+    F.fda_profile_enable(mon.ctx, True)
+    F.fda_profile_read(mon.ctx, reset=True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        mean_step()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    mkernel_ms, mlaunches = F.fda_profile_read(mon.ctx, reset=True)
+    F.fda_profile_enable(mon.ctx, False)
+    est_m = mon.estimate_variance_mean(theta)
+    assert (est_m.sync_sketch if args.variants & 2 else est_m.sync_linear) == 0
+    mean_ms = (t1 - t0) * 1e3 / args.steps
+    mk = mkernel_ms / max(mlaunches, 1)
+    mean_info = {"what": "same step with fda_mean_state + fda_estimate_variance_mean (average state by "
+                         "linearity of the sketch; no per-worker states)",
+                 "ms_per_step": round(mean_ms, 4), "value": K * d / (mean_ms * 1e-3),
+                 "unit": "worker-params/s", "kernel": "mean_state_kernel", "kernel_ms": round(mk, 4),
+                 "achieved": round(abytes / (mk * 1e-3) / 1e9, 1), "peak": HBM_PEAK_GBS,
+                 "frac": round(abytes / (mk * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+                 "h_sketch": est_m.h_sketch, "h_linear": est_m.h_linear}
+
     # forced synchronization + xi refresh, timed separately (it rewrites the slab, so last)
     ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     reps = 3
@@ -174,6 +208,7 @@ def main():
                    "step": "fda_local_state + fda_estimate_variance + predicated fda_sync/fda_update_xi "
                            "(decision: no sync)"},
         "roofline": roofline,
+        "mean_state_mode": mean_info,
         "sync": sync_info,
     }
 

@@ -2,7 +2,9 @@
 times.  The oracle cannot finish a whole state there in seconds, so it computes sampled
 outputs one by one -- the scalar state of a few workers and complete sketch rows of a few
 (worker, row) pairs -- plus one property that holds at any size (the cells of a row add up to
-the signed sum of the drift)."""
+the signed sum of the drift).  The average state of fda_mean_state is checked in the same pass:
+the oracle walks over all K rows once, accumulating the mean drift, and sketches it for the
+sampled rows."""
 import sys
 
 import numpy as np
@@ -52,9 +54,21 @@ def test_full_size_sampled_outputs(name, workers, rows):
     for i in rows:
         say(f"       oracle: hashing row {i} over {wl.d} keys")
         hashed[i] = O.bucket_and_sign(wl.hash_coef[i], j, wl.m)
-    for k in workers:
+    mon.mean_state(wl.w, wl.w_t0, wl.xi)
+    torch.cuda.synchronize()
+    nb, pb, skb = mon.mean_numpy()
+    assert mon.last_state_path() == 0 and mon.last_mean_state_path() == 0
+    usum = np.zeros(wl.d, np.float64)
+    uabs = np.zeros(wl.d, np.float64)
+    nsum = 0.0
+    for k in range(wl.K):
         say(f"       oracle: worker {k}")
         u = O.widen(row_to_numpy(wl, k), wl.dtype) - w0
+        usum += u
+        uabs += np.abs(u)
+        nsum += float(u @ u)
+        if k not in workers:
+            continue
         assert n[k] == pytest.approx(float(u @ u), rel=RTOL)
         want_p = float(u @ xi)
         assert abs(p[k] - want_p) <= RTOL * float(np.abs(u) @ np.abs(xi))
@@ -69,4 +83,21 @@ def test_full_size_sampled_outputs(name, workers, rows):
             assert abs(float(sk[k, i].astype(np.float64).sum()) - float((sign * u).sum())) \
                 <= RTOL * float(np.abs(u).sum())
         del u
+    # the average state (Algorithm 1 line 7) from the average drift
+    say("       oracle: mean state")
+    usum /= wl.K
+    uabs /= wl.K
+    assert nb == pytest.approx(nsum / wl.K, rel=RTOL)
+    assert abs(pb - float(usum @ xi)) <= RTOL * float(uabs @ np.abs(xi))
+    for i in rows:
+        bucket, sign = hashed[i]
+        want = np.bincount(bucket, weights=sign * usum, minlength=wl.m)
+        scale = np.bincount(bucket, weights=uabs, minlength=wl.m) + \
+            np.bincount(bucket, minlength=wl.m) * uabs.mean()
+        err = np.abs(skb[i] - want)
+        assert (err <= RTOL * scale).all(), float((err / scale).max())
+    est_m = mon.estimate_variance_mean(1e30)
+    assert est_m.nonfinite == 0 and est_m.mean_sqnorm == pytest.approx(est.mean_sqnorm, rel=1e-6)
+    assert est_m.h_sketch == pytest.approx(est.h_sketch, rel=1e-5)
+    assert est_m.h_linear == pytest.approx(est.h_linear, rel=1e-5)
     mon.close()
