@@ -55,6 +55,10 @@ def main():
     ap.add_argument("--variants", type=int, default=3, help="1 linear, 2 sketch, 3 both")
     ap.add_argument("--d", type=int, default=None, help="override d (for quick checks)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--wbar", action="store_true",
+                    help="mean-state mode: also emit the average model from the state pass and "
+                         "synchronize with fda_sync_from_mean instead of fda_sync + fda_update_xi "
+                         "(costs the state pass more than it saves unless synchronizations are frequent)")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MiB",
                     help="instead of the benchmark, run a plain device copy of this many MiB five "
                          "times (a kernel of known traffic, to scale rocprofv3's FETCH_SIZE / WRITE_SIZE)")
@@ -141,12 +145,19 @@ def main():
 
     # The same step with the average state computed directly (fda_mean_state: sketch of the mean
     # drift, by linearity) instead of the K per-worker states -- labelled separately, never `value`.
+    w_bar = torch.empty_like(wl.w_t0)
+
     def mean_step():
-        mon.mean_state(wl.w, wl.w_t0, xi)
-        mon.estimate_variance_mean(theta, want_host=False)
-        mon.sync(wl.w, wl.w_t0, w_prev, pred=pred)
-        if args.variants & 1:
-            mon.update_xi(wl.w_t0, w_prev, wl.xi, pred=pred)
+        if not args.wbar:
+            mon.mean_state(wl.w, wl.w_t0, xi)
+            mon.estimate_variance_mean(theta, want_host=False)
+            mon.sync(wl.w, wl.w_t0, w_prev, pred=pred)
+            if args.variants & 1:
+                mon.update_xi(wl.w_t0, w_prev, wl.xi, pred=pred)
+        else:
+            mon.mean_state(wl.w, wl.w_t0, xi, w_bar=w_bar)
+            mon.estimate_variance_mean(theta, want_host=False)
+            mon.sync_from_mean(wl.w, wl.w_t0, w_bar, w_prev=w_prev, xi=xi, pred=pred)
 
     for _ in range(args.warmup):
         mean_step()
@@ -165,8 +176,10 @@ def main():
     assert (est_m.sync_sketch if args.variants & 2 else est_m.sync_linear) == 0
     mean_ms = (t1 - t0) * 1e3 / args.steps
     mk = mkernel_ms / max(mlaunches, 1)
-    mean_info = {"what": "same step with fda_mean_state + fda_estimate_variance_mean (average state by "
-                         "linearity of the sketch; no per-worker states)",
+    mean_info = {"what": "same step with fda_mean_state (average state by linearity of the sketch, no "
+                         "per-worker states" + ("; also emits the average model" if args.wbar else "") +
+                         ") + fda_estimate_variance_mean + predicated " +
+                         ("fda_sync_from_mean" if args.wbar else "fda_sync/fda_update_xi"),
                  "ms_per_step": round(mean_ms, 4), "value": K * d / (mean_ms * 1e-3),
                  "unit": "worker-params/s", "kernel": "mean_state_kernel", "kernel_ms": round(mk, 4),
                  "achieved": round(abytes / (mk * 1e-3) / 1e9, 1), "peak": HBM_PEAK_GBS,
@@ -191,7 +204,20 @@ def main():
     ev1.record()
     torch.cuda.synchronize()
     xi_ms = ev0.elapsed_time(ev1) / reps
-    sync_info = {"sync_ms": round(sync_ms, 4), "sync_GBps": round(sync_bytes / sync_ms / 1e6, 1),
+    # the write-only synchronization from the average model fda_mean_state emitted (xi included)
+    mon.mean_state(wl.w, wl.w_t0, xi, w_bar=w_bar)
+    torch.cuda.synchronize()
+    ev0.record()
+    for _ in range(reps):
+        mon.sync_from_mean(wl.w, wl.w_t0, w_bar, w_prev=w_prev, xi=wl.xi, pred=None)
+    ev1.record()
+    torch.cuda.synchronize()
+    fused_ms = ev0.elapsed_time(ev1) / reps
+    fused_bytes = K * d * esz + 4 * d * 5
+    sync_info = {"sync_from_mean_ms": round(fused_ms, 4),
+                 "sync_from_mean_GBps": round(fused_bytes / fused_ms / 1e6, 1),
+                 "sync_from_mean_algorithmic_bytes": fused_bytes,
+                 "sync_ms": round(sync_ms, 4), "sync_GBps": round(sync_bytes / sync_ms / 1e6, 1),
                  "sync_algorithmic_bytes": sync_bytes, "update_xi_ms": round(xi_ms, 4),
                  "update_xi_GBps": round(20 * d / xi_ms / 1e6, 1)}
 

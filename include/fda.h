@@ -183,13 +183,17 @@ int fda_estimate_variance(fda_ctx* ctx, const float* state, double theta, double
  * their mean).
  *   w, w_t0, xi   as in fda_local_state
  *   mean_state    DEVICE [S] fp32, written
+ *   w_bar         DEVICE [d] fp32 or NULL.  If given it receives the average model
+ *                 w_t0 + u_bar (what Algorithm 1 line 9 would install: the same pass has every
+ *                 worker's element in registers anyway; 4 more bytes written per coordinate),
+ *                 and the context keeps ||w_bar - w_t0||^2 for fda_sync_from_mean.
  * A drift enters the sketch as the integer round(u * 2^e) (2^e as in fda_local_state), the K
  * integers of a coordinate are summed and added to 64-bit cells: exact, hence bit-identical
  * from run to run; drifts beyond 2^11 times the sampled mean |u| send the call down an fp64 path.
  * Returns FDA_ERANGE if K times the coordinates per workgroup reaches 2^33.
  */
 int fda_mean_state(fda_ctx* ctx, const void* w, const float* w_t0, const float* xi,
-                   float* mean_state, void* stream);
+                   float* mean_state, float* w_bar, void* stream);
 
 /*
  * Algorithm 1, line 8 on an average state: as fda_estimate_variance, but `mean_state` is the
@@ -211,6 +215,23 @@ int fda_estimate_variance_mean(fda_ctx* ctx, const float* mean_state, double the
  */
 int fda_sync(fda_ctx* ctx, void* w, float* w_t0, float* w_prev, const int32_t* pred_dev,
              void* stream);
+
+/*
+ * Algorithm 1, line 9 and Section 3.2 in one write-only pass, for a caller whose last
+ * fda_mean_state of this context produced `w_bar` from the slab as it still is:
+ *   w        DEVICE slab, rewritten: every row <- w_bar (bf16 slabs: round-to-nearest-even)
+ *   w_prev   DEVICE [d] fp32 or NULL: receives the old w_t0
+ *   w_t0     DEVICE [d] fp32: <- w_bar
+ *   xi       DEVICE [d] fp32 or NULL: <- (w_bar - old w_t0) / ||w_bar - old w_t0||_2, zero vector
+ *            when the norm is zero or not finite (the norm is the one fda_mean_state left)
+ *   w_bar    DEVICE [d] fp32 as written by fda_mean_state
+ *   pred_dev as in fda_sync
+ * Differs from fda_sync + fda_update_xi only in how the average was rounded (w_t0 + mean drift
+ * instead of the sum of the rows divided by K; both within 1e-5 of the largest |w_kj|) and in
+ * never reading the slab.
+ */
+int fda_sync_from_mean(fda_ctx* ctx, void* w, float* w_t0, float* w_prev, float* xi,
+                       const float* w_bar, const int32_t* pred_dev, void* stream);
 
 /*
  * Section 3.2: xi <- (w_t0 - w_prev) / ||w_t0 - w_prev||_2 (all DEVICE [d] fp32); the zero

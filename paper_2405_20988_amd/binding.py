@@ -83,7 +83,8 @@ def load_library():
     lib.fda_local_state.argtypes = [vp, vp, vp, vp, vp, vp]
     lib.fda_estimate_variance.argtypes = [vp, vp, C.c_double, C.c_double, vp,
                                           C.POINTER(FdaEstimate), vp]
-    lib.fda_mean_state.argtypes = [vp, vp, vp, vp, vp, vp]
+    lib.fda_mean_state.argtypes = [vp, vp, vp, vp, vp, vp, vp]
+    lib.fda_sync_from_mean.argtypes = [vp, vp, vp, vp, vp, vp, i32p, vp]
     lib.fda_estimate_variance_mean.argtypes = [vp, vp, C.c_double, C.c_double, vp,
                                                C.POINTER(FdaEstimate), vp]
     lib.fda_last_mean_state_path.argtypes = [vp, C.POINTER(C.c_int32), vp]
@@ -92,7 +93,7 @@ def load_library():
     lib.fda_last_state_path.argtypes = [vp, C.POINTER(C.c_int32), vp]
     lib.fda_profile_enable.argtypes = [vp, C.c_int]
     lib.fda_profile_read.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(C.c_int64), C.c_int]
-    for name in ("fda_mean_state", "fda_estimate_variance_mean", "fda_last_mean_state_path",
+    for name in ("fda_sync_from_mean", "fda_mean_state", "fda_estimate_variance_mean", "fda_last_mean_state_path",
                  "fda_last_state_path", "fda_profile_enable", "fda_profile_read", "fda_plan", "fda_workspace_bytes", "fda_create", "fda_destroy",
                  "fda_state_floats", "fda_get_plan", "fda_local_state",
                  "fda_estimate_variance", "fda_sync", "fda_update_xi"):
@@ -177,8 +178,15 @@ def fda_estimate_variance(ctx: int, state: int, theta: float, tie_tol: float, ou
     return host
 
 
-def fda_mean_state(ctx: int, w: int, w_t0: int, xi: int | None, mean_state: int, stream: int = 0) -> None:
-    _check(load_library().fda_mean_state(ctx, w, w_t0, xi, mean_state, stream), "fda_mean_state")
+def fda_mean_state(ctx: int, w: int, w_t0: int, xi: int | None, mean_state: int,
+                   w_bar: int | None = None, stream: int = 0) -> None:
+    _check(load_library().fda_mean_state(ctx, w, w_t0, xi, mean_state, w_bar, stream), "fda_mean_state")
+
+
+def fda_sync_from_mean(ctx: int, w: int, w_t0: int, w_prev: int | None, xi: int | None, w_bar: int,
+                       pred_dev: int | None = None, stream: int = 0) -> None:
+    _check(load_library().fda_sync_from_mean(ctx, w, w_t0, w_prev, xi, w_bar, pred_dev, stream),
+           "fda_sync_from_mean")
 
 
 def fda_estimate_variance_mean(ctx: int, mean_state: int, theta: float, tie_tol: float, out_dev: int,

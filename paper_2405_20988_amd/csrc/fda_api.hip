@@ -61,7 +61,7 @@ struct Plan {
   MeanSplit mean;   // fda_mean_state
   int vec;          // elements per 16-byte slab load
   int64_t cells, S, dpad;
-  int64_t off_np, off_sk, off_xi, off_scale, off_smax, off_ssum, off_nmax, off_est, off_ticket, off_table,
+  int64_t off_np, off_sk, off_xi, off_scale, off_smax, off_ssum, off_nmax, off_dnorm, off_est, off_ticket, off_table,
       ws_bytes;
 };
 
@@ -217,7 +217,7 @@ int make_plan(const fda_desc* d, int cus, int64_t lds_cu, Plan* pl) {
   // the per-workgroup partials of fda_local_state and of fda_mean_state share one region
   const int64_t Pmax = pl->narrow.P > pl->wide.P ? pl->narrow.P : pl->wide.P;
   int64_t np_bytes = (int64_t)pl->narrow.P * d->K * 2 * 8, sk_bytes = Pmax * d->K * pl->cells * 8;
-  if (np_bytes < (int64_t)pl->mean.P * 2 * 8) np_bytes = (int64_t)pl->mean.P * 2 * 8;
+  if (np_bytes < (int64_t)pl->mean.P * 3 * 8) np_bytes = (int64_t)pl->mean.P * 3 * 8;
   if (sk_bytes < (int64_t)pl->mean.P * pl->cells * 8) sk_bytes = (int64_t)pl->mean.P * pl->cells * 8;
   pl->off_np = 0;
   pl->off_sk = round_up(pl->off_np + np_bytes, kAlign);
@@ -226,7 +226,8 @@ int make_plan(const fda_desc* d, int cus, int64_t lds_cu, Plan* pl) {
   pl->off_smax = round_up(pl->off_scale + 2 * (int64_t)sizeof(fda::ScaleInfo), kAlign);
   pl->off_ssum = round_up(pl->off_smax + kScaleBlocks * 4, kAlign);
   pl->off_nmax = round_up(pl->off_ssum + kScaleBlocks * 8, kAlign);
-  pl->off_est = round_up(pl->off_nmax + 8, kAlign);
+  pl->off_dnorm = round_up(pl->off_nmax + 8, kAlign);
+  pl->off_est = round_up(pl->off_dnorm + 8, kAlign);
   pl->off_ticket = round_up(pl->off_est + (2 + (int64_t)FDA_MAX_SKETCH_ROWS * kMaxEstBlocksPerRow) * 8, kAlign);
   pl->off_table = round_up(pl->off_ticket + 8, kAlign);
   pl->dpad = round_up(d->d, 64);
@@ -656,7 +657,7 @@ int fda_local_state(fda_ctx* ctx, const void* w, const float* w_t0, const float*
 }
 
 int fda_mean_state(fda_ctx* ctx, const void* w, const float* w_t0, const float* xi,
-                   float* mean_state, void* stream) {
+                   float* mean_state, float* w_bar, void* stream) {
   int rc = check_state_args(ctx, w, w_t0, xi, mean_state);
   if (rc != FDA_OK) return rc;
   const fda_desc& d = ctx->desc;
@@ -668,6 +669,8 @@ int fda_mean_state(fda_ctx* ctx, const void* w, const float* w_t0, const float* 
   // a cell's integer sum stays below K * chunk * 2^30 in magnitude
   if (sk && (double)d.K * (double)ms.chunk >= 8589934592.0)
     return fail(FDA_ERANGE, "K * coordinates per workgroup must stay below 2^33");
+  if (w_bar != nullptr && reinterpret_cast<uintptr_t>(w_bar) % 4 != 0)
+    return fail(FDA_EINVAL, "pointer not aligned to its element type");
   hipStream_t st = static_cast<hipStream_t>(stream);
 
   fda::MeanParams prm;
@@ -677,8 +680,9 @@ int fda_mean_state(fda_ctx* ctx, const void* w, const float* w_t0, const float* 
   prm.R = ms.R; prm.P = ms.P;
   prm.do_lin = lin; prm.do_sk = sk;
   // whole-vector loads: 16 bytes of w_t0 / xi, and 16 (fp32) or 8 (bf16) bytes of a slab row
-  prm.vec_ok = aligned16(w_t0) && (!lin || aligned16(xi)) &&
+  prm.vec_ok = aligned16(w_t0) && (!lin || aligned16(xi)) && (w_bar == nullptr || aligned16(w_bar)) &&
                reinterpret_cast<uintptr_t>(w) % (4 * esz) == 0 && (d.row_stride * esz) % (4 * esz) == 0;
+  prm.w_bar = w_bar;
   prm.part_np = reinterpret_cast<double*>(ctx->ws + pl.off_np);
   prm.part_sk = ctx->ws + pl.off_sk;
   prm.scale = reinterpret_cast<fda::ScaleInfo*>(ctx->ws + pl.off_scale) + 1;
@@ -701,9 +705,10 @@ int fda_mean_state(fda_ctx* ctx, const void* w, const float* w_t0, const float* 
     rc = dispatch_mean(d.dtype, fda::kCellF64, ms, &prm, st);
     if (rc != FDA_OK) return rc;
   }
-  const int blocks = (int)((pl.S + 31) / 32);
+  const int blocks = (int)((pl.S + 1 + 31) / 32);
   hipLaunchKernelGGL(fda::merge_mean_kernel, dim3(blocks), dim3(fda::kSmallThreads), 0, st,
-                     prm.part_np, prm.part_sk, prm.scale, mean_state, d.K, (int)pl.cells, ms.P);
+                     prm.part_np, prm.part_sk, prm.scale, mean_state,
+                     reinterpret_cast<double*>(ctx->ws + pl.off_dnorm), d.K, (int)pl.cells, ms.P);
   FDA_HIP(hipGetLastError());
   return FDA_OK;
 }
@@ -764,6 +769,34 @@ int fda_sync(fda_ctx* ctx, void* w, float* w_t0, float* w_prev, const int32_t* p
     hipLaunchKernelGGL(fda::sync_kernel<fda::bf16_t>, dim3((unsigned)blocks), dim3(fda::kSmallThreads), 0,
                        st, static_cast<fda::bf16_t*>(w), w_t0, w_prev, pred_dev, d.K, (long long)d.d,
                        (long long)d.row_stride, vec_ok);
+  FDA_HIP(hipGetLastError());
+  return FDA_OK;
+}
+
+int fda_sync_from_mean(fda_ctx* ctx, void* w, float* w_t0, float* w_prev, float* xi,
+                       const float* w_bar, const int32_t* pred_dev, void* stream) {
+  if (ctx == nullptr || w == nullptr || w_t0 == nullptr || w_bar == nullptr)
+    return fail(FDA_EINVAL, "NULL argument");
+  const fda_desc& d = ctx->desc;
+  const int esz = d.dtype == FDA_F32 ? 4 : 2;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  const int vec_ok = aligned16(w) && aligned16(w_t0) && aligned16(w_bar) &&
+                     (w_prev == nullptr || aligned16(w_prev)) && (xi == nullptr || aligned16(xi)) &&
+                     (d.row_stride * esz) % 16 == 0;
+  const int V = ctx->plan.vec;
+  const long long nvec = (d.d + V - 1) / V;
+  long long blocks = (nvec + fda::kSmallThreads - 1) / fda::kSmallThreads;
+  const long long cap = (long long)ctx->cus * 16;
+  if (blocks > cap) blocks = cap;
+  const double* dnorm = reinterpret_cast<const double*>(ctx->ws + ctx->plan.off_dnorm);
+  if (d.dtype == FDA_F32)
+    hipLaunchKernelGGL(fda::sync_from_mean_kernel<float>, dim3((unsigned)blocks), dim3(fda::kSmallThreads),
+                       0, st, static_cast<float*>(w), w_t0, w_prev, xi, w_bar, dnorm, pred_dev, d.K,
+                       (long long)d.d, (long long)d.row_stride, vec_ok);
+  else
+    hipLaunchKernelGGL(fda::sync_from_mean_kernel<fda::bf16_t>, dim3((unsigned)blocks),
+                       dim3(fda::kSmallThreads), 0, st, static_cast<fda::bf16_t*>(w), w_t0, w_prev, xi,
+                       w_bar, dnorm, pred_dev, d.K, (long long)d.d, (long long)d.row_stride, vec_ok);
   FDA_HIP(hipGetLastError());
   return FDA_OK;
 }

@@ -12,6 +12,10 @@
 // consecutive coordinates; for each it sums the K drifts, accumulates sum_k u^2 and <xi,u>
 // (fp32 within the tile, fp64 across tiles; row group 0 only), and at the end of the tile adds
 // sign * (sum of the K drifts) into the LDS sketch [row][bucket] once per sketch row.
+// On request (w_bar != NULL) row group 0 also writes the average model w_t0 + mean_k u_k and
+// accumulates the squared norm of what fda_sync_from_mean will see as the model change,
+// (w_bar - w_t0) as rounded to fp32 -- Algorithm 1 line 9 and the xi of Section 3.2 then need
+// no second pass over the slab.
 //
 //   kCellI64  a drift enters as the integer round(u * Sm) (Sm = ScaleInfo::Sm, the mean sampled
 //             |u| maps to about 2^18, every |u| must stay below boundm = 2^30 / Sm); the K
@@ -40,7 +44,8 @@ struct MeanParams {
   int do_lin;
   int do_sk;
   int vec_ok;             // all pointers / strides allow whole-vector loads
-  double* part_np;        // [P][2]: sum_k ||u_k||^2 and sum_k <xi,u_k> of the partition
+  float* w_bar;           // [d] or NULL: receives w_t0 + mean_k u_k
+  double* part_np;        // [P][3]: sum_k ||u_k||^2, sum_k <xi,u_k>, ||w_bar - w_t0||^2 of the partition
   void* part_sk;          // [P][l*m] 8-byte words: int64 (integer cells) or double (fp64 cells)
   ScaleInfo* scale;
   const uint16_t* table;  // [l][dpad] tabulated hash
@@ -124,8 +129,10 @@ mean_state_kernel(const MeanParams prm) {
   const int NB = (K + KB - 1) / KB;                     // batches of slab rows per tile
   const int tail = K - (NB - 1) * KB;                   // rows of the last batch, 1..KB
   const float Sm = prm.do_sk ? prm.scale->Sm : 1.0f;
+  float* const wbp = scalars ? prm.w_bar : nullptr;
+  const float kf = (float)K;
 
-  double dn = 0.0, dp = 0.0;
+  double dn = 0.0, dp = 0.0, dd = 0.0;
   float amax = 0.0f;
 
   // SC: this workgroup also produces the scalar components; SK: it accumulates sketch rows.
@@ -134,9 +141,10 @@ mean_state_kernel(const MeanParams prm) {
     constexpr bool SK = decltype(sk_tag)::value;
     long long acc[V];         // integer cells: sum over the workers of round(u * Sm)
     double us[V];             // fp64 cells: sum over the workers of u
+    float um[V];              // scalar workgroups: sum over the workers of u, for the average model
     float sn = 0.0f, sp = 0.0f;
 #pragma unroll
-    for (int v = 0; v < V; ++v) { acc[v] = 0; us[v] = 0.0; }
+    for (int v = 0; v < V; ++v) { acc[v] = 0; us[v] = 0.0; um[v] = 0.0f; }
 
     // slab rows k0 .. k0+KB-1 (rows past the last worker repeat it; consume() drops them)
     auto load_batch_fast = [&](Batch& bt, long long j0, int k0) {
@@ -211,6 +219,7 @@ mean_state_kernel(const MeanParams prm) {
             sn = fmaf(u, u, sn);
             sp = fmaf(h.x[v], u, sp);
             amax = fmaxf(amax, fabsf(u));
+            um[v] += u;
           }
           if constexpr (SK && CELL == kCellI64) acc[v] += (long long)(int)rintf(u * Sm);
           if constexpr (SK && CELL == kCellF64) us[v] += (double)u;
@@ -219,10 +228,35 @@ mean_state_kernel(const MeanParams prm) {
     };
 
     // end of a tile: the scalar partials go to fp64, the V sums into the sketch rows
-    auto finish = [&](const Head& h) {
+    auto finish = [&](const Head& h, long long j0, bool whole) {
       if constexpr (SC) {
         dn += (double)sn; dp += (double)sp;
         sn = 0.0f; sp = 0.0f;
+        if (wbp != nullptr) {
+          float wb[V], sd = 0.0f;
+#pragma unroll
+          for (int v = 0; v < V; ++v) {
+            wb[v] = h.w0[v] + um[v] / kf;
+            const float df = wb[v] - h.w0[v];        // the model change as fp32 storage keeps it
+            sd = fmaf(df, df, sd);
+          }
+          if (whole) {
+            store_f32_vec<V>(wbp + j0, wb);
+            dd += (double)sd;
+          } else {
+            sd = 0.0f;
+#pragma unroll
+            for (int v = 0; v < V; ++v)
+              if (j0 + v < dlim) {
+                wbp[j0 + v] = wb[v];
+                const float df = wb[v] - h.w0[v];
+                sd = fmaf(df, df, sd);
+              }
+            dd += (double)sd;
+          }
+        }
+#pragma unroll
+        for (int v = 0; v < V; ++v) um[v] = 0.0f;
       }
       if constexpr (SK) {
 #pragma unroll
@@ -270,7 +304,7 @@ mean_state_kernel(const MeanParams prm) {
         load_batch_fast(bn, jn, 0);
         if (tail < KB) consume(bc, hc, std::true_type{}, tail);
         else consume(bc, hc, std::false_type{}, KB);
-        finish(hc);
+        finish(hc, j0, true);
         hc = hn;
         bc = bn;
         j0 += kTile;
@@ -286,7 +320,7 @@ mean_state_kernel(const MeanParams prm) {
         if (bi == NB - 1 && tail < KB) consume(bt, h, std::true_type{}, tail);
         else consume(bt, h, std::false_type{}, KB);
       }
-      finish(h);
+      finish(h, j0, false);
     }
   };
   if (scalars) {
@@ -311,14 +345,15 @@ mean_state_kernel(const MeanParams prm) {
   if (scalars) {
     const double a = wave_sum(dn);
     const double c = wave_sum(dp);
-    if (lane == 0) { red[wave * 2] = a; red[wave * 2 + 1] = c; }
+    const double e = wave_sum(dd);
+    if (lane == 0) { red[wave * 3] = a; red[wave * 3 + 1] = c; red[wave * 3 + 2] = e; }
   }
   __syncthreads();
-  if (scalars && tid < 2) {
+  if (scalars && tid < 3) {
     double s = 0.0;
-    for (int wv = 0; wv < kWaves; ++wv) s += red[wv * 2 + tid];
+    for (int wv = 0; wv < kWaves; ++wv) s += red[wv * 3 + tid];
     if (tid == 1 && !lin) s = 0.0;               // no LinearFDA: the projection slot stays zero
-    prm.part_np[(size_t)p * 2 + tid] = s;
+    prm.part_np[(size_t)p * 3 + tid] = s;
   }
   // ---- flush the LDS sketch to this workgroup's slice of the partial buffer -----------
   if (sketch) {

@@ -257,20 +257,22 @@ merge_kernel(const double* __restrict__ part_np, const void* __restrict__ part_s
 
 // mean_state[s] = (sum over the partitions) / K, for the partials of mean_state_kernel: the two
 // scalar sums in fp64, the sketch cells as 64-bit integers in units of 1/Sm (or fp64 when the
-// call went down the fp64 path).  Same fixed shape as merge_kernel.
+// call went down the fp64 path).  Same fixed shape as merge_kernel.  One entry past the state,
+// the summed squared norm of the model change goes to *dnorm (for fda_sync_from_mean).
 __global__ void __launch_bounds__(kSmallThreads)
 merge_mean_kernel(const double* __restrict__ part_np, const void* __restrict__ part_sk,
-                  const ScaleInfo* __restrict__ scale, float* __restrict__ mean_state, int K,
-                  int cells, int P) {
+                  const ScaleInfo* __restrict__ scale, float* __restrict__ mean_state,
+                  double* __restrict__ dnorm, int K, int cells, int P) {
   __shared__ double sh[8][32];
   const int S = 2 + cells;
   const int o = threadIdx.x & 31, slice = threadIdx.x >> 5;
   const int s = blockIdx.x * 32 + o;
-  const bool live = s < S;
+  const bool live = s <= S;
   double acc = 0.0, unit = 1.0;
   if (live) {
-    if (s < 2) {
-      for (int p = slice; p < P; p += 8) acc += part_np[(size_t)p * 2 + s];
+    if (s < 2 || s == S) {
+      const int q = s < 2 ? s : 2;
+      for (int p = slice; p < P; p += 8) acc += part_np[(size_t)p * 3 + q];
     } else {
       const int c = s - 2;
       if (scale->flagm != 0) {
@@ -291,7 +293,56 @@ merge_mean_kernel(const double* __restrict__ part_np, const void* __restrict__ p
     double t = 0.0;
 #pragma unroll
     for (int q = 0; q < 8; ++q) t += sh[q][o];
-    mean_state[s] = (float)(t * unit / (double)K);
+    if (s == S) *dnorm = t;
+    else mean_state[s] = (float)(t * unit / (double)K);
+  }
+}
+
+// Algorithm 1 line 9 when the average model is already there (w_bar from mean_state_kernel):
+// every row <- w_bar, w_prev <- w_t0, w_t0 <- w_bar, and (xi != NULL) the xi of Section 3.2,
+// (w_bar - old w_t0) / ||w_bar - old w_t0||, with the squared norm taken from *dnorm.
+template <typename T>
+__global__ void __launch_bounds__(kSmallThreads)
+sync_from_mean_kernel(T* __restrict__ w, float* __restrict__ w_t0, float* __restrict__ w_prev,
+                      float* __restrict__ xi, const float* __restrict__ w_bar,
+                      const double* __restrict__ dnorm, const int32_t* __restrict__ pred, int K,
+                      long long d, long long row_stride, int vec_ok) {
+  constexpr int V = Slab<T>::V;
+  if (pred != nullptr && *pred == 0) return;
+  float scale = 0.0f;
+  if (xi != nullptr) {
+    const double nrm = sqrt(*dnorm);
+    scale = (nrm > 0.0 && isfinite(nrm)) ? (float)(1.0 / nrm) : 0.0f;
+  }
+  const long long nvec = (d + V - 1) / V;
+  for (long long vi = (long long)blockIdx.x * blockDim.x + threadIdx.x; vi < nvec;
+       vi += (long long)gridDim.x * blockDim.x) {
+    const long long j0 = vi * V;
+    if (vec_ok && j0 + V <= d) {
+      float nb[V], old[V];
+      load_f32_vec<V>(w_bar + j0, nb);
+      load_f32_vec<V>(w_t0 + j0, old);
+      if (w_prev != nullptr) store_f32_vec<V>(w_prev + j0, old);
+      store_f32_vec<V>(w_t0 + j0, nb);
+      if (xi != nullptr) {
+        float x[V];
+#pragma unroll
+        for (int v = 0; v < V; ++v) x[v] = (scale == 0.0f) ? 0.0f : (nb[v] - old[v]) * scale;
+        store_f32_vec<V>(xi + j0, x);
+      }
+#pragma unroll 4
+      for (int k = 0; k < K; ++k) Slab<T>::store_vec(w + (long long)k * row_stride + j0, nb);
+    } else {
+      for (int v = 0; v < V; ++v) {
+        const long long j = j0 + v;
+        if (j >= d) break;
+        const float a = w_bar[j], o = w_t0[j];
+        if (w_prev != nullptr) w_prev[j] = o;
+        w_t0[j] = a;
+        if (xi != nullptr) xi[j] = (scale == 0.0f) ? 0.0f : (a - o) * scale;
+        for (int k = 0; k < K; ++k) Slab<T>::store_one(w + (long long)k * row_stride + j, a);
+      }
+    }
   }
 }
 

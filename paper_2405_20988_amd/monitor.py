@@ -61,10 +61,17 @@ class FdaMonitor:
         return B.fda_estimate_variance(self.ctx, st.data_ptr(), float(theta), float(tie_tol),
                                        self.est_dev.data_ptr(), want_host, self._stream())
 
-    def mean_state(self, w, w_t0, xi=None):
+    def mean_state(self, w, w_t0, xi=None, w_bar=None):
         B.fda_mean_state(self.ctx, w.data_ptr(), w_t0.data_ptr(),
-                         None if xi is None else xi.data_ptr(), self.mean.data_ptr(), self._stream())
+                         None if xi is None else xi.data_ptr(), self.mean.data_ptr(),
+                         None if w_bar is None else w_bar.data_ptr(), self._stream())
         return self.mean
+
+    def sync_from_mean(self, w, w_t0, w_bar, w_prev=None, xi=None, pred=None):
+        B.fda_sync_from_mean(self.ctx, w.data_ptr(), w_t0.data_ptr(),
+                             None if w_prev is None else w_prev.data_ptr(),
+                             None if xi is None else xi.data_ptr(), w_bar.data_ptr(),
+                             self.pred_ptr(pred), self._stream())
 
     def estimate_variance_mean(self, theta, tie_tol=1e-5, want_host=True, mean_state=None):
         st = self.mean if mean_state is None else mean_state

@@ -252,3 +252,113 @@ def test_mean_state_unaligned_and_strided():
     mon.mean_state(view, wl.w_t0, wl.xi)
     check_mean(mon, ref)
     mon.close()
+
+
+@pytest.mark.parametrize("name,d,over", [("cfg4", 250_003, {}), ("cfg5", 400_005, {}),
+                                         ("cfg1", None, {}), ("cfg2", 9, {"K": 2}),
+                                         ("cfg3", 120_001, {"K": 7})])
+def test_sync_from_mean_parity(name, d, over):
+    """fda_mean_state with w_bar, then fda_sync_from_mean: the average model, the broadcast, w_prev
+    and xi (Algorithm 1 line 9, Section 3.2) against the oracle's sync and update_xi."""
+    say(f"[case] sync-from-mean parity {name} d={d} {over}")
+    wl = S.make(name, device=DEV, seed=5, d=d, **over)
+    mon = monitor_for(wl)
+    w_host = S.slab_to_numpy(wl.w)
+    w0_host = wl.w_t0.cpu().numpy().copy()
+    ref = O.sync(w_host, wl.dtype, w0_host)
+    scale = np.abs(O.widen(w_host, wl.dtype)).max(axis=0)
+    w_prev = torch.full_like(wl.w_t0, 7.0)
+    xi = torch.zeros_like(wl.w_t0)
+    w_bar = torch.full_like(wl.w_t0, -3.0)
+
+    mon.mean_state(wl.w, wl.w_t0, wl.xi, w_bar=w_bar)
+    torch.cuda.synchronize()
+    check_mean(mon, oracle_mean(wl))                    # the extra output does not disturb the state
+    wb_host = w_bar.cpu().numpy()
+    assert (np.abs(wb_host.astype(np.float64) - ref["mean"]) <= RTOL * scale + 1e-30).all()
+
+    # predicate 0: nothing may change
+    mon.estimate_variance_mean(1e30)
+    before = wl.w.clone()
+    mon.sync_from_mean(wl.w, wl.w_t0, w_bar, w_prev=w_prev, xi=xi, pred="sketch")
+    torch.cuda.synchronize()
+    assert torch.equal(before.view(torch.uint8), wl.w.view(torch.uint8))
+    assert np.array_equal(wl.w_t0.cpu().numpy(), w0_host)
+    assert (w_prev == 7.0).all() and not xi.any()
+
+    # predicate 1
+    est = mon.estimate_variance_mean(0.0)
+    assert est.sync_sketch == 1
+    mon.sync_from_mean(wl.w, wl.w_t0, w_bar, w_prev=w_prev, xi=xi, pred="sketch")
+    torch.cuda.synchronize()
+    assert np.array_equal(w_prev.cpu().numpy(), ref["w_prev"])            # bit-exact copy
+    assert np.array_equal(wl.w_t0.cpu().numpy(), wb_host)                 # w_t0 <- w_bar, bit-exact
+    rows = S.slab_to_numpy(wl.w)
+    assert (rows == rows[0]).all()                                        # every worker holds the same bits
+    if wl.dtype == "f32":
+        assert np.array_equal(rows[0], wb_host)
+    else:
+        diff = np.abs(rows[0].astype(np.int32) - ref["rows"].astype(np.int32))
+        assert diff.max() <= 1
+        assert (diff != 0).mean() < 1e-2
+        assert np.array_equal(rows[0], O.round_to_bf16_bits(wb_host.astype(np.float64)))
+    # xi from the last two synchronized models, as the device now holds them
+    want_xi = O.update_xi(wl.w_t0.cpu().numpy(), w_prev.cpu().numpy())
+    got_xi = xi.cpu().numpy().astype(np.float64)
+    assert np.abs(got_xi - want_xi).max() <= RTOL * np.abs(want_xi).max()
+    assert float(got_xi @ got_xi) == pytest.approx(1.0, rel=1e-5)
+    # "after synchronization the model variance is zero"
+    out = mon.mean_state(wl.w, wl.w_t0, xi)
+    if wl.dtype == "f32":
+        assert not out.any()
+    # without w_prev and xi, no predicate
+    mon.mean_state(wl.w, wl.w_t0, xi, w_bar=w_bar)
+    mon.sync_from_mean(wl.w, wl.w_t0, w_bar)
+    torch.cuda.synchronize()
+    assert np.array_equal(wl.w_t0.cpu().numpy(), w_bar.cpu().numpy())
+    mon.close()
+
+
+def test_sync_from_mean_unaligned():
+    """w_bar, w_prev and xi off the 16-byte grid and an odd row stride: the element-wise paths of
+    both kernels; the padding between rows must stay untouched."""
+    say("[case] sync-from-mean unaligned")
+    import paper_2405_20988_amd as F
+    K, d, l, m = 6, 10_007, 5, 250
+    stride = d + 5
+    g = torch.Generator(device=DEV)
+    g.manual_seed(6)
+    coef = S.hash_coefficients(6, l)
+    for dtype, tdt in (("f32", torch.float32), ("bf16", torch.bfloat16)):
+        buf = torch.full((K * stride + 3,), 9.0, device=DEV, dtype=tdt)
+        w_t0 = torch.zeros(d + 1, device=DEV)[1:]
+        xi = torch.zeros(d + 1, device=DEV)[1:]
+        w_prev = torch.zeros(d + 1, device=DEV)[1:]
+        w_bar = torch.zeros(d + 1, device=DEV)[1:]
+        w_t0.copy_(torch.randn(d, generator=g, device=DEV) * 0.05)
+        xi.copy_(torch.randn(d, generator=g, device=DEV) / d ** 0.5)
+        full = buf[3:].view(K, stride)
+        w = full[:, :d]
+        w.copy_((w_t0 + torch.randn((K, d), generator=g, device=DEV) * 1e-3).to(tdt))
+        wc = w.contiguous()
+        w0_host = w_t0.cpu().numpy().copy()
+        mon = F.FdaMonitor(K, d, dtype, 3, l, m, 0.06, coef, row_stride=stride, device=DEV)
+        from paper_2405_20988_amd import binding as B
+        st = torch.cuda.current_stream().cuda_stream
+        B.fda_mean_state(mon.ctx, w.data_ptr(), w_t0.data_ptr(), xi.data_ptr(), mon.mean.data_ptr(),
+                         w_bar.data_ptr(), st)
+        ref = O.mean_state(S.slab_to_numpy(wc), dtype, w0_host, xi.cpu().numpy(), coef, m)
+        check_mean(mon, ref)
+        B.fda_sync_from_mean(mon.ctx, w.data_ptr(), w_t0.data_ptr(), w_prev.data_ptr(), xi.data_ptr(),
+                             w_bar.data_ptr(), None, st)
+        torch.cuda.synchronize()
+        sref = O.sync(S.slab_to_numpy(wc), dtype, w0_host)
+        scale = np.abs(O.widen(S.slab_to_numpy(wc), dtype)).max(axis=0)
+        assert (np.abs(w_t0.cpu().numpy().astype(np.float64) - sref["mean"]) <= RTOL * scale).all()
+        assert np.array_equal(w_prev.cpu().numpy(), w0_host)
+        assert (full[:, d:] == 9.0).all() and (buf[:3] == 9.0).all()
+        rows = S.slab_to_numpy(w.contiguous())
+        assert (rows == rows[0]).all()
+        want_xi = O.update_xi(w_t0.cpu().numpy(), w_prev.cpu().numpy())
+        assert np.abs(xi.cpu().numpy() - want_xi).max() <= RTOL * np.abs(want_xi).max()
+        mon.close()
