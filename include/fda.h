@@ -241,6 +241,27 @@ int fda_update_xi(fda_ctx* ctx, const float* w_t0, const float* w_prev, float* x
                   const int32_t* pred_dev, void* stream);
 
 /*
+ * Algorithm 1, lines 6-9 as one enqueue with no host round trip: the state, the estimate, and --
+ * predicated on the device-side decision of the variant `decide_by` -- the synchronization and
+ * the refresh of xi.  Exactly the calls above, in order:
+ *   flags == 0:                    fda_local_state(state[K][S]), fda_estimate_variance,
+ *                                  fda_sync, fda_update_xi
+ *   flags & FDA_STEP_MEAN_STATE:   fda_mean_state(state[S]), fda_estimate_variance_mean, then
+ *                                  fda_sync + fda_update_xi, or, with w_bar != NULL (which
+ *                                  fda_mean_state then fills), fda_sync_from_mean
+ *   decide_by   FDA_VARIANT_LINEAR or FDA_VARIANT_SKETCH (must be one of the context's variants)
+ *   xi          read by the state pass (if LINEAR) and rewritten when the step synchronizes; with
+ *               xi == NULL (allowed without LINEAR) no xi is maintained
+ *   w_prev      DEVICE [d] fp32, required when xi is given
+ *   w_bar       DEVICE [d] fp32 or NULL (only used with FDA_STEP_MEAN_STATE)
+ *   out_dev / out_host  as in fda_estimate_variance (out_host != NULL makes the call wait)
+ */
+#define FDA_STEP_MEAN_STATE 1
+int fda_step(fda_ctx* ctx, void* w, float* w_t0, float* w_prev, float* xi, float* state, float* w_bar,
+             double theta, double tie_tol, int32_t decide_by, int32_t flags, fda_estimate* out_dev,
+             fda_estimate* out_host, void* stream);
+
+/*
  * Diagnostic: which kind of LDS sketch cell the last fda_local_state of this context ended
  * up using -- 0: 32-bit integers (the normal case), 1: 64-bit integers (a drift was too large
  * for, or a sum did not fit, the 32-bit cells), 2: fp64 (the drifts' dynamic range is beyond

@@ -88,12 +88,14 @@ def load_library():
     lib.fda_estimate_variance_mean.argtypes = [vp, vp, C.c_double, C.c_double, vp,
                                                C.POINTER(FdaEstimate), vp]
     lib.fda_last_mean_state_path.argtypes = [vp, C.POINTER(C.c_int32), vp]
+    lib.fda_step.argtypes = [vp, vp, vp, vp, vp, vp, vp, C.c_double, C.c_double, C.c_int32, C.c_int32, vp,
+                             C.POINTER(FdaEstimate), vp]
     lib.fda_sync.argtypes = [vp, vp, vp, vp, i32p, vp]
     lib.fda_update_xi.argtypes = [vp, vp, vp, vp, i32p, vp]
     lib.fda_last_state_path.argtypes = [vp, C.POINTER(C.c_int32), vp]
     lib.fda_profile_enable.argtypes = [vp, C.c_int]
     lib.fda_profile_read.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(C.c_int64), C.c_int]
-    for name in ("fda_sync_from_mean", "fda_mean_state", "fda_estimate_variance_mean", "fda_last_mean_state_path",
+    for name in ("fda_step", "fda_sync_from_mean", "fda_mean_state", "fda_estimate_variance_mean", "fda_last_mean_state_path",
                  "fda_last_state_path", "fda_profile_enable", "fda_profile_read", "fda_plan", "fda_workspace_bytes", "fda_create", "fda_destroy",
                  "fda_state_floats", "fda_get_plan", "fda_local_state",
                  "fda_estimate_variance", "fda_sync", "fda_update_xi"):
@@ -207,6 +209,20 @@ def fda_sync(ctx: int, w: int, w_t0: int, w_prev: int | None, pred_dev: int | No
 def fda_update_xi(ctx: int, w_t0: int, w_prev: int, xi: int, pred_dev: int | None = None,
                   stream: int = 0) -> None:
     _check(load_library().fda_update_xi(ctx, w_t0, w_prev, xi, pred_dev, stream), "fda_update_xi")
+
+
+FDA_STEP_MEAN_STATE = 1
+
+
+def fda_step(ctx: int, w: int, w_t0: int, w_prev: int | None, xi: int | None, state: int,
+             w_bar: int | None, theta: float, tie_tol: float, decide_by: int, flags: int, out_dev: int,
+             want_host: bool = False, stream: int = 0):
+    """Algorithm 1 lines 6-9 as one enqueue; returns the host copy of the result if want_host."""
+    host = FdaEstimate() if want_host else None
+    _check(load_library().fda_step(ctx, w, w_t0, w_prev, xi, state, w_bar, theta, tie_tol, decide_by,
+                                   flags, out_dev, C.byref(host) if want_host else None, stream),
+           "fda_step")
+    return host
 
 
 def fda_profile_enable(ctx: int, on: bool) -> None:

@@ -3,6 +3,7 @@
 #include <hip/hip_runtime.h>
 
 #include <cstdarg>
+#include <cstddef>
 #include <cstdio>
 #include <cstring>
 #include <new>
@@ -820,6 +821,47 @@ int fda_update_xi(fda_ctx* ctx, const float* w_t0, const float* w_prev, float* x
   hipLaunchKernelGGL(fda::xi_scale_kernel, dim3((unsigned)sblocks), dim3(fda::kSmallThreads), 0, st,
                      w_t0, w_prev, xi, pred_dev, (long long)d.d, partial, (int)blocks);
   FDA_HIP(hipGetLastError());
+  return FDA_OK;
+}
+
+int fda_step(fda_ctx* ctx, void* w, float* w_t0, float* w_prev, float* xi, float* state, float* w_bar,
+             double theta, double tie_tol, int32_t decide_by, int32_t flags, fda_estimate* out_dev,
+             fda_estimate* out_host, void* stream) {
+  if (ctx == nullptr || out_dev == nullptr) return fail(FDA_EINVAL, "NULL argument");
+  if ((decide_by != FDA_VARIANT_LINEAR && decide_by != FDA_VARIANT_SKETCH) ||
+      !(ctx->desc.variants & decide_by))
+    return fail(FDA_EINVAL, "decide_by must be one of the context's variants");
+  if ((flags & ~FDA_STEP_MEAN_STATE) != 0) return fail(FDA_EINVAL, "unknown flags");
+  if (xi != nullptr && w_prev == nullptr) return fail(FDA_EINVAL, "w_prev is required when xi is given");
+  const bool mean = (flags & FDA_STEP_MEAN_STATE) != 0;
+  if (!mean && w_bar != nullptr) return fail(FDA_EINVAL, "w_bar needs FDA_STEP_MEAN_STATE");
+  const int32_t* pred = reinterpret_cast<const int32_t*>(
+      reinterpret_cast<const unsigned char*>(out_dev) +
+      (decide_by == FDA_VARIANT_LINEAR ? offsetof(fda_estimate, sync_linear)
+                                       : offsetof(fda_estimate, sync_sketch)));
+  int rc;
+  if (mean) {
+    rc = fda_mean_state(ctx, w, w_t0, xi, state, w_bar, stream);
+    if (rc != FDA_OK) return rc;
+    rc = fda_estimate_variance_mean(ctx, state, theta, tie_tol, out_dev, nullptr, stream);
+  } else {
+    rc = fda_local_state(ctx, w, w_t0, xi, state, stream);
+    if (rc != FDA_OK) return rc;
+    rc = fda_estimate_variance(ctx, state, theta, tie_tol, out_dev, nullptr, stream);
+  }
+  if (rc != FDA_OK) return rc;
+  if (w_bar != nullptr) {
+    rc = fda_sync_from_mean(ctx, w, w_t0, w_prev, xi, w_bar, pred, stream);
+  } else {
+    rc = fda_sync(ctx, w, w_t0, w_prev, pred, stream);
+    if (rc == FDA_OK && xi != nullptr) rc = fda_update_xi(ctx, w_t0, w_prev, xi, pred, stream);
+  }
+  if (rc != FDA_OK) return rc;
+  if (out_host != nullptr) {
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    FDA_HIP(hipMemcpyAsync(out_host, out_dev, sizeof(fda_estimate), hipMemcpyDeviceToHost, st));
+    FDA_HIP(hipStreamSynchronize(st));
+  }
   return FDA_OK;
 }
 

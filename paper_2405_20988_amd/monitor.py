@@ -86,6 +86,17 @@ class FdaMonitor:
         B.fda_update_xi(self.ctx, w_t0.data_ptr(), w_prev.data_ptr(), xi.data_ptr(),
                         self.pred_ptr(pred), self._stream())
 
+    def step(self, w, w_t0, w_prev, xi, theta, decide_by="sketch", mean=False, w_bar=None,
+             tie_tol=1e-5, want_host=False):
+        """Algorithm 1 lines 6-9 in one call (fda_step)."""
+        ptr = lambda t: None if t is None else t.data_ptr()
+        by = B.FDA_VARIANT_SKETCH if decide_by == "sketch" else B.FDA_VARIANT_LINEAR
+        st = self.mean if mean else self.state
+        return B.fda_step(self.ctx, w.data_ptr(), w_t0.data_ptr(), ptr(w_prev), ptr(xi), st.data_ptr(),
+                          ptr(w_bar), float(theta), float(tie_tol), by,
+                          B.FDA_STEP_MEAN_STATE if mean else 0, self.est_dev.data_ptr(), want_host,
+                          self._stream())
+
     def last_state_path(self):
         return B.fda_last_state_path(self.ctx, self._stream())
 
