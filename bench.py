@@ -54,6 +54,8 @@ def main():
     ap.add_argument("--config", default="cfg5", help="cfg1..cfg5 (default: the largest, cfg5)")
     ap.add_argument("--variants", type=int, default=3, help="1 linear, 2 sketch, 3 both")
     ap.add_argument("--d", type=int, default=None, help="override d (for quick checks)")
+    ap.add_argument("--l", type=int, default=None, help="override the sketch rows (sketch-size sweeps)")
+    ap.add_argument("--m", type=int, default=None, help="override the sketch width (sketch-size sweeps)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--wbar", action="store_true",
                     help="mean-state mode: also emit the average model from the state pass and "
@@ -95,7 +97,8 @@ def main():
                           "launches": 5}))
         return
 
-    wl = S.make(args.config, device=dev, seed=0, d=args.d)
+    over = {k: v for k, v in (("l", args.l), ("m", args.m)) if v is not None}
+    wl = S.make(args.config, device=dev, seed=0, d=args.d, **over)
     K, d = wl.K, wl.d
     esz = 4 if wl.dtype == "f32" else 2
     mon = F.FdaMonitor(K, d, wl.dtype, args.variants, wl.l, wl.m, wl.eps, wl.hash_coef, device=dev)
@@ -138,6 +141,8 @@ def main():
     kern_ms_avg = kernel_ms / max(launches, 1)
     achieved = abytes / (kern_ms_avg * 1e-3) / 1e9
     workload = args.config if args.d is None else f"{args.config}-d{d}"
+    if over:
+        workload += f"-sketch{wl.l}x{wl.m}"
     roofline = {"bound": "hbm", "kernel": "state_kernel", "achieved": round(achieved, 1),
                 "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
                 "traffic": traffic_from_profile(workload), "algorithmic_bytes": abytes,
@@ -242,7 +247,7 @@ def main():
         from oracle import fda_oracle as O
         ds = min(args.cpu_sample, d)
         # regenerate a small slab of the same recipe on the CPU for the sample (same distributions)
-        wls = S.make(args.config, device="cpu", seed=0, d=ds)
+        wls = S.make(args.config, device="cpu", seed=0, d=ds, **over)
         w_host = S.slab_to_numpy(wls.w)
         w0_host, xi_host = wls.w_t0.numpy(), wls.xi.numpy()
         c0 = time.perf_counter()

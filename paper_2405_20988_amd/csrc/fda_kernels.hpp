@@ -297,7 +297,7 @@ state_kernel(const StateParams prm) {
 
   double S64 = 1.0;
   float S32 = 1.0f, amax = 0.0f;
-  uint32_t wrapped = 0u;          // bit 31: an add of this lane found a 32-bit cell outside the safe band
+  uint32_t seen_lo = 0x80000000u, seen_hi = 0x80000000u;   // range of the 32-bit cell values this lane's adds returned
   if (prm.do_sk) { S64 = prm.scale->S64; S32 = prm.scale->S32; }
 
   // SC: this workgroup also produces the scalar components; SK: it accumulates sketch rows.
@@ -395,12 +395,16 @@ state_kernel(const StateParams prm) {
             for (int k = 0; k < KC; ++k) old[k] = atomicAdd(cell + k, (q[k] ^ sgn) - sgn);   // +q or -q
             // Every add is below 2^30 in magnitude (ScaleInfo::bound32), so a cell cannot wrap
             // in an add that found it inside [2^30, 3*2^30): if every value ever returned was
-            // inside that band, no cell wrapped.  old - 2^30 has bit 31 set exactly outside the
-            // band.  The values of the row before are examined only now, with this row's adds
-            // already on their way, so the LDS round trip hides behind the next batch.
+            // inside that band, no cell wrapped.  Only the smallest and the largest returned value
+            // are kept (three-operand min / max: one instruction per add).  The values of the row
+            // before are examined only now, with this row's adds already on their way, so the
+            // LDS round trip hides behind the next batch.
             if (have_pending) {
 #pragma unroll
-              for (int k = 0; k < KC; ++k) wrapped |= pend_old[k] - 0x40000000u;
+              for (int k = 0; k < KC; ++k) {
+                seen_lo = min(seen_lo, pend_old[k]);
+                seen_hi = max(seen_hi, pend_old[k]);
+              }
             }
 #pragma unroll
             for (int k = 0; k < KC; ++k) pend_old[k] = old[k];
@@ -441,7 +445,10 @@ state_kernel(const StateParams prm) {
       if constexpr (SK && CELL == kCellI32) {
         if (have_pending) {
 #pragma unroll
-          for (int k = 0; k < KC; ++k) wrapped |= pend_old[k] - 0x40000000u;
+          for (int k = 0; k < KC; ++k) {
+            seen_lo = min(seen_lo, pend_old[k]);
+            seen_hi = max(seen_hi, pend_old[k]);
+          }
         }
       }
       if constexpr (SC) {
@@ -491,7 +498,7 @@ state_kernel(const StateParams prm) {
         if (bad32 || bad64) prm.scale->flag32 = 1;
         if (bad64) prm.scale->overflow64 = 1;
       }
-      if (wrapped >> 31) prm.scale->flag32 = 1;
+      if (seen_lo < 0x40000000u || seen_hi >= 0xC0000000u) prm.scale->flag32 = 1;
     }
   }
 
