@@ -33,10 +33,10 @@ def algorithmic_bytes(K, d, elem_bytes, variants):
     return K * d * elem_bytes + 4 * d + (4 * d if variants & 1 else 0)
 
 
-def traffic_from_profile(workload):
-    """HBM bytes per state-kernel launch measured with rocprofv3 --pmc (FETCH_SIZE and
+def traffic_from_profile(workload, kernel="state_kernel"):
+    """HBM bytes per launch of a kernel measured with rocprofv3 --pmc (FETCH_SIZE and
     WRITE_SIZE runs, scaled by a copy kernel), if a summary for this workload is committed."""
-    path = os.path.join(ROOT, "profiles", f"state_kernel_{workload}_traffic.txt")
+    path = os.path.join(ROOT, "profiles", f"{kernel}_{workload}_traffic.txt")
     try:
         for line in open(path):
             if line.startswith("traffic_bytes_per_launch="):
@@ -189,6 +189,7 @@ def main():
                  "unit": "worker-params/s", "kernel": "mean_state_kernel", "kernel_ms": round(mk, 4),
                  "achieved": round(abytes / (mk * 1e-3) / 1e9, 1), "peak": HBM_PEAK_GBS,
                  "frac": round(abytes / (mk * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+                 "traffic": None if args.wbar else traffic_from_profile(workload, "mean_state_kernel"),
                  "h_sketch": est_m.h_sketch, "h_linear": est_m.h_linear}
 
     # forced synchronization + xi refresh, timed separately (it rewrites the slab, so last)
