@@ -39,8 +39,8 @@ constexpr double kAtomicCost = 3.0;        // select the signed value, issue the
 constexpr double kDecodeCost = 5.0;        // unpack one table entry into an LDS address and a sign
 constexpr double kSharedByteCost = 0.5;    // per byte of w_t0 / xi / table re-read by another workgroup
 constexpr int kMaxEstBlocksPerRow = 128;   // 32768 / 256: workgroups of estimate_kernel per sketch row
-constexpr int kScaleBlocks = 64;
-constexpr int kScaleSamples = 16384;       // sampled coordinates per worker for the scale (64 workgroups)
+constexpr int kScaleSamples = 16384;       // sampled coordinates per worker for the scale
+constexpr int kScaleBlocks = kScaleSamples * fda::kScaleSlices / fda::kSmallThreads;   // its workgroups
 constexpr int kXiBlocks = 1024;
 constexpr int64_t kAlign = 256;
 
@@ -405,7 +405,7 @@ int prepare_sketch(fda_ctx* ctx, const void* w, const float* w_t0, fda::ScaleInf
     ctx->counted = true;
   }
   const int samples = (int)(d.d < kScaleSamples ? d.d : kScaleSamples);
-  const int sblocks = (samples + fda::kSmallThreads - 1) / fda::kSmallThreads;
+  const int sblocks = (samples * fda::kScaleSlices + fda::kSmallThreads - 1) / fda::kSmallThreads;
   unsigned int* ticket = reinterpret_cast<unsigned int*>(ctx->ws + pl.off_ticket);
   if (d.dtype == FDA_F32)
     hipLaunchKernelGGL(fda::scale_kernel<float>, dim3(sblocks), dim3(fda::kSmallThreads), 0, st,

@@ -154,10 +154,15 @@ __device__ inline ScaleInfo choose_scale(float amax, double mean, const unsigned
   return s;
 }
 
-// Largest and mean |w_kj - w_t0_j| over `samples` evenly spaced coordinates of every worker
-// (one coordinate per thread, all workers), reduced per workgroup; the workgroup that finishes
-// last combines the per-workgroup results in a fixed order, chooses the scales and clears the
-// flags.  `ticket` counts finished workgroups and is left at zero.
+// Largest and mean |w_kj - w_t0_j| over `samples` coordinates of every worker: evenly spaced runs
+// of 8 consecutive coordinates (a run shares its cache lines, so the scattered reads cost an
+// eighth of what single coordinates would).  A thread takes one sampled coordinate and every
+// kScaleSlices-th worker (the loads of one thread are independent HBM misses: few per thread,
+// several in flight); per-workgroup maximum and sum;
+// the workgroup that finishes last combines the per-workgroup results in a fixed order, chooses
+// the scales and clears the flags.  `ticket` counts finished workgroups and is left at zero.
+constexpr int kScaleSlices = 8;
+
 template <typename T>
 __global__ void __launch_bounds__(kSmallThreads)
 scale_kernel(const T* __restrict__ w, const float* __restrict__ w_t0, int K, long long d,
@@ -170,11 +175,15 @@ scale_kernel(const T* __restrict__ w, const float* __restrict__ w_t0, int K, lon
   float m = 0.0f;
   double sum = 0.0;
   const int t = blockIdx.x * blockDim.x + threadIdx.x;
-  if (t < samples) {
-    const long long j = (long long)t * (d / samples);
+  const int smp = t / kScaleSlices, slice = t - smp * kScaleSlices;
+  if (smp < samples) {
+    // samples is a multiple of 8 and at most d, or equal to d (then every coordinate is taken)
+    const long long j = (samples & 7) ? (long long)smp
+                                      : (long long)(smp >> 3) * (d / (samples >> 3)) + (smp & 7);
     const float base = w_t0[j];
     float part = 0.0f;
-    for (int k = 0; k < K; ++k) {
+#pragma unroll 4
+    for (int k = slice; k < K; k += kScaleSlices) {
       const float u = fabsf(Slab<T>::load_one(w + (long long)k * row_stride + j) - base);
       m = fmaxf(m, u);                         // fmaxf drops NaN
       if (u == u && u < 3.0e38f) part += u;
@@ -195,12 +204,12 @@ scale_kernel(const T* __restrict__ w, const float* __restrict__ w_t0, int K, lon
   __syncthreads();
   if (!last) return;
   __threadfence();
-  if (threadIdx.x < 64) {                      // gridDim.x <= 64: one partial per lane
+  if (threadIdx.x < 64) {                      // lane q takes partials q, q + 64, ...
     float am = 0.0f;
     double sm = 0.0;
-    if (threadIdx.x < gridDim.x) {
-      am = reinterpret_cast<volatile float*>(part_max)[threadIdx.x];
-      sm = reinterpret_cast<volatile double*>(part_sum)[threadIdx.x];
+    for (int q = threadIdx.x; q < (int)gridDim.x; q += 64) {
+      am = fmaxf(am, reinterpret_cast<volatile float*>(part_max)[q]);
+      sm += reinterpret_cast<volatile double*>(part_sum)[q];
     }
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) am = fmaxf(am, __shfl_down(am, o, 64));
@@ -230,17 +239,20 @@ merge_kernel(const double* __restrict__ part_np, const void* __restrict__ part_s
   if (live) {
     const int k = (int)(idx / S), s = (int)(idx - (long long)k * S);
     if (s < 2) {
+#pragma unroll 8
       for (int p = slice; p < P32; p += 8) acc += part_np[((size_t)p * K + k) * 2 + s];
     } else {
       const int c = s - 2;
       if (scale->overflow64 != 0) {
         const double* pd = reinterpret_cast<const double*>(part_sk);
+#pragma unroll 8
         for (int p = slice; p < P64; p += 8) acc += pd[((size_t)p * K + k) * cells + c];
       } else {
         const bool narrow = scale->flag32 == 0;
         const int P = narrow ? P32 : P64;
         unit = narrow ? scale->invS32 : scale->invS64;
         const long long* pi = reinterpret_cast<const long long*>(part_sk);
+#pragma unroll 8
         for (int p = slice; p < P; p += 8) acc += (double)pi[((size_t)p * K + k) * cells + c];
       }
     }
@@ -272,16 +284,19 @@ merge_mean_kernel(const double* __restrict__ part_np, const void* __restrict__ p
   if (live) {
     if (s < 2 || s == S) {
       const int q = s < 2 ? s : 2;
+#pragma unroll 8
       for (int p = slice; p < P; p += 8) acc += part_np[(size_t)p * 3 + q];
     } else {
       const int c = s - 2;
       if (scale->flagm != 0) {
         const double* pd = reinterpret_cast<const double*>(part_sk);
+#pragma unroll 8
         for (int p = slice; p < P; p += 8) acc += pd[(size_t)p * cells + c];
       } else {
         unit = scale->invSm;
         const long long* pi = reinterpret_cast<const long long*>(part_sk);
         long long isum = 0;                       // exact
+#pragma unroll 8
         for (int p = slice; p < P; p += 8) isum += pi[(size_t)p * cells + c];
         acc = (double)isum;
       }

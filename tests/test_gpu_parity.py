@@ -519,10 +519,12 @@ def test_drifts_outside_the_sampled_range(dtype):
         mon.local_state(w, w_t0_used, xi)
         ref = O.local_state(S.slab_to_numpy(w), dtype, w_t0_used.cpu().numpy(), xi.cpu().numpy(), coef, m)
         check_state(mon, ref)
-        # the 32-bit cells cannot hold these; fp32 slabs need the fp64 cells, a bf16 slab's
-        # rounding residue narrows the range enough for the 64-bit integers
-        assert mon.last_state_path() == (2 if dtype == "f32" else 1) or kind == "sparse"
+        # the 32-bit cells cannot hold these; fp32 spikes 10^6 times the rest need the fp64 cells
+        # (with a bf16 slab the rounding residue narrows the range: which of the two wider kinds
+        # takes over there depends on what the sample of the scale happens to see)
         assert mon.last_state_path() >= 1
+        if dtype == "f32" and kind == "spikes":
+            assert mon.last_state_path() == 2
         mon.close()
 
 
