@@ -112,6 +112,13 @@ typedef struct fda_plan_info {
   int64_t lds_bytes;        /* LDS per workgroup                                            */
   int64_t workspace_bytes;  /* device scratch the context needs                             */
   int64_t state_floats;     /* floats per worker state: 2 + l*m with SKETCH, else 2         */
+  /* the mean-state pass (fda_mean_state): every workgroup reads all K workers */
+  int32_t mean_row_groups;       /* sketch-row groups (1 unless l*m 8-byte cells exceed LDS)  */
+  int32_t mean_rows_per_group;   /* largest group                                            */
+  int32_t mean_partitions;       /* coordinate partitions                                    */
+  int32_t mean_workgroups_per_cu;/* resident workgroups per CU the launch is sized for       */
+  int64_t mean_chunk;            /* coordinates per partition                                */
+  int64_t mean_lds_bytes;        /* LDS per workgroup                                        */
 } fda_plan_info;
 
 const char* fda_strerror(int code);

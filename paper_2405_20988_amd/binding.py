@@ -49,7 +49,10 @@ class FdaPlanInfo(C.Structure):
                 ("row_groups", C.c_int32), ("rows_per_group", C.c_int32),
                 ("partitions", C.c_int32), ("threads", C.c_int32), ("chunk", C.c_int64),
                 ("lds_bytes", C.c_int64), ("workspace_bytes", C.c_int64),
-                ("state_floats", C.c_int64)]
+                ("state_floats", C.c_int64),
+                ("mean_row_groups", C.c_int32), ("mean_rows_per_group", C.c_int32),
+                ("mean_partitions", C.c_int32), ("mean_workgroups_per_cu", C.c_int32),
+                ("mean_chunk", C.c_int64), ("mean_lds_bytes", C.c_int64)]
 
     def as_dict(self) -> dict:
         return {name: getattr(self, name) for name, _ in self._fields_}

@@ -247,6 +247,12 @@ void export_plan(const Plan& pl, fda_plan_info* out) {
   out->lds_bytes = pl.narrow.lds_bytes;
   out->workspace_bytes = pl.ws_bytes;
   out->state_floats = pl.S;
+  out->mean_row_groups = pl.mean.R;
+  out->mean_rows_per_group = pl.mean.rcnt_max;
+  out->mean_partitions = pl.mean.P;
+  out->mean_workgroups_per_cu = pl.mean.occ;
+  out->mean_chunk = pl.mean.chunk;
+  out->mean_lds_bytes = pl.mean.lds_bytes;
 }
 
 int device_shape(int* cus, int64_t* lds) {

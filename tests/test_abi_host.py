@@ -35,7 +35,7 @@ def test_struct_layouts_match_header():
     assert C.sizeof(F.FdaEstimate) == 64
     assert F.FdaEstimate.sync_linear.offset == 40 and F.FdaEstimate.sync_sketch.offset == 44
     assert C.sizeof(F.FdaDesc) == 56
-    assert C.sizeof(F.FdaPlanInfo) == 56
+    assert C.sizeof(F.FdaPlanInfo) == 88
 
 
 def test_strerror():
@@ -98,9 +98,38 @@ def test_plan_of_the_five_configs(name):
     # the partial buffers fit in the workspace
     need = p.partitions * c["K"] * (16 + 8 * c["l"] * c["m"])
     assert p.workspace_bytes >= need
+    # the mean-state pass: one row group, two workgroups per CU, one round, partials fit too
+    assert p.mean_row_groups == 1 and p.mean_rows_per_group == c["l"]
+    assert p.mean_workgroups_per_cu == 2 and 2 * p.mean_lds_bytes <= 163840
+    assert p.mean_partitions % 8 == 0 and p.mean_partitions <= 512
+    assert p.mean_partitions * p.mean_chunk >= c["d"] and p.mean_chunk % (p.threads * 4) == 0
+    assert p.workspace_bytes >= p.mean_partitions * (24 + 8 * c["l"] * c["m"])
     # sketch bytes the paper quotes for 5 x 250: l * m * 4 = 5 kB (Section 3.3)
     if (c["l"], c["m"]) == (5, 250):
         assert (p.state_floats - 2) * 4 == 5000
+
+
+def test_plan_of_the_mean_state_pass_splits_rows_only_when_it_must():
+    coef16 = S.hash_coefficients(0, 16)
+    # 16 rows: more than the 8 row slots of a workgroup -> two row groups of 8
+    desc, keep = make_desc(8, 10**6, F.FDA_F32, 3, 16, 64, 0.06, coef16)
+    p = F.fda_plan(desc, 256, 163840)
+    assert (p.mean_row_groups, p.mean_rows_per_group) == (2, 8)
+    assert p.mean_row_groups * p.mean_partitions <= 2 * 256
+    # 3 x 19000 8-byte cells: one row per workgroup, one workgroup per CU
+    desc, keep = make_desc(3, 10**6, F.FDA_F32, 3, 3, 19_000, 0.06, coef16[:3])
+    p = F.fda_plan(desc, 256, 163840)
+    assert (p.mean_row_groups, p.mean_rows_per_group, p.mean_workgroups_per_cu) == (3, 1, 1)
+    assert p.mean_lds_bytes <= 163840
+    # a tiny vector: no more partitions than tiles (rounded up to the 8 XCDs)
+    desc, keep = make_desc(4, 5000, F.FDA_F32, 3, 5, 250, 0.06, coef16[:5])
+    p = F.fda_plan(desc, 256, 163840)
+    assert p.mean_partitions == 8 and p.mean_chunk == 2048
+    # a sketch row that does not fit in LDS with 8-byte cells is refused
+    desc, keep = make_desc(4, 10**6, F.FDA_F32, 3, 2, 30_000, 0.06, coef16[:2])
+    with pytest.raises(F.FdaError) as e:
+        F.fda_plan(desc, 256, 163840)
+    assert e.value.code == -2
 
 
 def test_plan_linear_only_needs_no_sketch():
