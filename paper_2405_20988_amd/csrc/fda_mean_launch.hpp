@@ -9,7 +9,7 @@
 namespace fda {
 constexpr int kMeanMaxLR = 8;                // sketch-row slots of one workgroup: 1..8
 constexpr int kMeanBatchF32 = 4;             // slab rows per batch: 4 x 16 bytes per lane ...
-constexpr int kMeanBatchBF16 = 8;            // ... or 8 x 8 bytes
+constexpr int kMeanBatchBF16 = 4;            // ... or 4 x 8 bytes
 
 #define FDA_MEAN_LAUNCHER(t, c) \
   hipError_t launch_mean_##t##_##c(int LR, const MeanParams* prm, size_t lds, hipStream_t st)

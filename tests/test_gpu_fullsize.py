@@ -31,7 +31,8 @@ def row_to_numpy(wl, k):
     return r.numpy()
 
 
-@pytest.mark.parametrize("name,workers,rows", [("cfg3", [0, 17, 29], [0, 3]),
+@pytest.mark.parametrize("name,workers,rows", [("cfg2", [0, 9, 15], [0, 4]),
+                                                ("cfg3", [0, 17, 29], [0, 3]),
                                                 ("cfg4", [0, 31, 59], [1, 4]),
                                                 ("cfg5", [0, 7], [2])])
 def test_full_size_sampled_outputs(name, workers, rows):
