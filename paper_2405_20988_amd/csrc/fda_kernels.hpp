@@ -30,7 +30,7 @@ struct HashCoef {
 enum CellKind { kCellI32 = 0, kCellI64 = 1, kCellF64 = 2 };
 
 // Fixed-point scales of one fda_local_state call, chosen on the device from a sample of the
-// drifts (scale_*_kernel) and read by the state and merge kernels, and the flags that send a
+// drifts (scale_kernel) and read by the state and merge kernels, and the flags that send a
 // call from the 32-bit integer cells to the 64-bit ones and from those to fp64 cells.
 struct ScaleInfo {
   double S64, invS64;     // 64-bit cells: a drift u is added as the integer round(u * S64)
@@ -198,7 +198,7 @@ __device__ __forceinline__ float raw_elem(const uint32_t (&r)[2], int v) {      
 // How the sketch cells accumulate is dictated by the LDS of gfx950.  Measured per CU and clock
 // on random cells: ds_add_f32 0.33 lanes, ds_add_f64 2.8, ds_add_u64 5.5, ds_add_rtn_u32 10.4.
 // So the cells are integers and a drift u is added as round(u * 2^e), with 2^e chosen per call
-// from a sample of the drifts (scale_finalize_kernel).  Integer addition is exact: the result
+// from a sample of the drifts (scale_kernel).  Integer addition is exact: the result
 // does not depend on the order in which lanes and workgroups add, run-to-run bit-identical.
 //   kCellI32  32-bit cells, started at 2^31; every add is below 2^30 in magnitude and returns
 //             the old value, which must lie in [2^30, 3*2^30): then no add can have wrapped.

@@ -3,10 +3,12 @@
 //
 //   hash_table_kernel, cell_count_kernel   once per context: the tabulated hash and the largest
 //                    number of coordinates a workgroup can put into one sketch cell
-//   scale_*_kernel   per call: the fixed-point unit of the integer sketch cells
+//   scale_kernel     per call: the fixed-point unit of the integer sketch cells
 //   merge_kernel     fixed-order fp64 sum of the per-workgroup partials -> state[K][S]
+//   merge_mean_kernel  the same for the partials of mean_state_kernel -> mean_state[S]
 //   estimate_kernel  Algorithm 1 lines 7-8: mean state, M2, H (Thm 1, Thm 2), decision
 //   sync_kernel      Algorithm 1 line 9: fused mean over workers + broadcast to all rows
+//   sync_from_mean_kernel  the same from an average model that is already there, with xi
 //   xi_norm_kernel / xi_scale_kernel   Section 3.2: the normalized model difference
 #pragma once
 #include "fda_kernels.hpp"
