@@ -136,3 +136,27 @@ def test_plan_linear_only_needs_no_sketch():
     desc, keep = make_desc(60, 10**6, F.FDA_F32, F.FDA_VARIANT_LINEAR)
     p = F.fda_plan(desc, 256, 163840)
     assert p.state_floats == 2 and p.worker_groups == 10 and p.row_groups == 1
+
+
+def test_header_is_plain_c(tmp_path):
+    """include/fda.h is the boundary: it must compile as C99 and as C++ on its own, and the struct
+    sizes the binding mirrors must be the compiler's."""
+    import shutil
+    import subprocess
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    src = tmp_path / "hdr.c"
+    src.write_text('#include "fda.h"\n#include <stdio.h>\n'
+                   'int main(void) { printf("%d %d %d\\n", (int)sizeof(fda_desc), (int)sizeof(fda_estimate),'
+                   ' (int)sizeof(fda_plan_info)); return 0; }\n')
+    gcc = shutil.which("gcc")
+    if gcc is None:
+        pytest.skip("no C compiler")
+    exe = tmp_path / "hdr"
+    subprocess.run([gcc, "-std=c99", "-Wall", "-Wextra", "-Werror", "-pedantic", "-I", os.path.join(root, "include"),
+                    str(src), "-o", str(exe)], check=True)
+    sizes = subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.split()
+    assert [int(x) for x in sizes] == [C.sizeof(F.FdaDesc), C.sizeof(F.FdaEstimate), C.sizeof(F.FdaPlanInfo)]
+    gxx = shutil.which("g++")
+    if gxx is not None:
+        subprocess.run([gxx, "-std=c++11", "-Wall", "-Wextra", "-Werror", "-pedantic", "-x", "c++", "-fsyntax-only",
+                        "-I", os.path.join(root, "include"), str(src)], check=True)
