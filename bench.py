@@ -232,7 +232,9 @@ def main():
         "value": value, "unit": "worker-params/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None,
-        "dtype": "f32" if wl.dtype == "f32" else "bf16-storage/f32-arithmetic",
+        # the arithmetic type: drifts, norms and projections in fp32 (fp64 across tiles), sketch cells
+        # as exact integers of fp32-rounded terms; the slab's storage type is in config.slab_dtype
+        "dtype": "f32",
         "data": "synthetic",
         "config": {"workload": workload, "K": K, "d": d, "slab_dtype": wl.dtype,
                    "sketch": f"{wl.l}x{wl.m}", "variants": args.variants,
