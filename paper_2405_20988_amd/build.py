@@ -14,12 +14,14 @@ CSRC = os.path.join(PKG, "csrc")
 LIB_DIR = os.path.join(PKG, "lib")
 OBJ_DIR = os.path.join(PKG, "_build")
 LIB_PATH = os.path.join(LIB_DIR, "libfda.so")
+EXAMPLE_SRC = os.path.join(CSRC, "fda_c_example.c")
+EXAMPLE_PATH = os.path.join(LIB_DIR, "fda_c_example")
 UNITS = (["fda_api"] +
          ["fda_state_narrow_%s_kc%d" % (t, k) for t in ("f32", "bf16") for k in (1, 2, 3, 4, 5, 6, 8)] +
          ["fda_state_wide_%s_%s" % (t, c) for t in ("f32", "bf16") for c in ("i64", "f64")] +
          ["fda_mean_%s_%s" % (t, c) for t in ("f32", "bf16") for c in ("i64", "f64")])
 SOURCES = [os.path.join(CSRC, u + ".hip") for u in UNITS]
-DEPENDS = SOURCES + [os.path.join(CSRC, n) for n in
+DEPENDS = SOURCES + [EXAMPLE_SRC] + [os.path.join(CSRC, n) for n in
                      ("fda_kernels.hpp", "fda_small_kernels.hpp", "fda_state_launch.hpp", "fda_state_narrow.inc",
                       "fda_state_wide.inc", "fda_mean_kernel.hpp", "fda_mean_launch.hpp", "fda_mean.inc")] + \
     [os.path.join(ROOT, "include", "fda.h")]
@@ -57,10 +59,27 @@ def build_library(verbose: bool = False) -> str:
         list(pool.map(_run, [cmds[i] for i in order]))
     link = [hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB_PATH] + objs
     _run(link)
+    build_c_example()
     if verbose:
         for c in cmds + [link]:
             print(" ".join(c))
     return LIB_PATH
+
+
+def build_c_example() -> str | None:
+    """The plain C caller of the library (csrc/fda_c_example.c), built with the host C compiler
+    against the HIP runtime; returns its path, or None without a C compiler."""
+    cc = shutil.which("gcc") or shutil.which("cc")
+    if cc is None:
+        return None
+    rocm = os.path.dirname(os.path.dirname(os.path.realpath(hipcc())))
+    if not os.path.exists(os.path.join(rocm, "include", "hip", "hip_runtime_api.h")):
+        rocm = "/opt/rocm"
+    _run([cc, "-std=c99", "-O2", "-Wall", "-Wextra", "-D__HIP_PLATFORM_AMD__",
+          "-I" + os.path.join(rocm, "include"), "-I" + os.path.join(ROOT, "include"), EXAMPLE_SRC,
+          "-o", EXAMPLE_PATH, "-L" + LIB_DIR, "-lfda", "-L" + os.path.join(rocm, "lib"), "-lamdhip64", "-lm",
+          "-Wl,-rpath,$ORIGIN", "-Wl,-rpath," + os.path.join(rocm, "lib")])
+    return EXAMPLE_PATH
 
 
 def is_stale() -> bool:
