@@ -147,6 +147,14 @@ def main():
                 "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
                 "traffic": traffic_from_profile(workload), "algorithmic_bytes": abytes,
                 "kernel_ms": round(kern_ms_avg, 4), "launches": launches}
+    if args.variants & 2:
+        # what actually bounds this kernel: one LDS atomic add per (worker, sketch row, coordinate);
+        # the ceiling is the rate measured for returning 32-bit LDS atomics on random cells of this chip
+        props = torch.cuda.get_device_properties(0)
+        adds = float(wl.l) * K * d
+        roofline["lds_atomic_adds_per_clk_per_cu"] = round(
+            adds / (kern_ms_avg * 1e-3) / props.multi_processor_count / 2.4e9, 2)
+        roofline["lds_atomic_ceiling_per_clk_per_cu"] = 10.4
 
     # The same step with the average state computed directly (fda_mean_state: sketch of the mean
     # drift, by linearity) instead of the K per-worker states -- labelled separately, never `value`.
