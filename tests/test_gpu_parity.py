@@ -571,3 +571,37 @@ def test_sketch_cell_paths():
     assert sk[0, 0].tolist() == [0.0, 0.0, 0.5 * d, 0.0]
     assert n[0] == 0.25 * d
     mon.close()
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_sync_propagates_nonfinite_values(dtype):
+    """A NaN or an infinity in one worker's parameters must reach the average (and every row)
+    instead of being rounded away -- in particular through the bf16 rounding of the stored rows."""
+    say(f"[case] sync with non-finite parameters {dtype}")
+    import paper_2405_20988_amd as F
+    K, d = 4, 4099
+    tdt = torch.float32 if dtype == "f32" else torch.bfloat16
+    g = torch.Generator(device=DEV)
+    g.manual_seed(31)
+    w = (torch.randn((K, d), generator=g, device=DEV) * 0.05).to(tdt)
+    w[1, 5] = float("nan")
+    w[2, 77] = float("inf")
+    w[3, 78] = float("-inf")
+    w[0, 4000] = float("inf")
+    w[1, 4000] = float("-inf")                     # inf - inf: NaN
+    w_t0 = torch.zeros(d, device=DEV)
+    mon = F.FdaMonitor(K, d, dtype, 1, device=DEV)
+    ref = O.sync(S.slab_to_numpy(w), dtype, w_t0.cpu().numpy())
+    mon.sync(w, w_t0, None)
+    torch.cuda.synchronize()
+    got = w_t0.cpu().numpy()
+    want = ref["mean"]
+    assert np.array_equal(np.isnan(got), np.isnan(want))
+    assert np.array_equal(np.isposinf(got), np.isposinf(want)) and np.array_equal(np.isneginf(got), np.isneginf(want))
+    fin = np.isfinite(want)
+    assert np.allclose(got[fin], want[fin], rtol=RTOL, atol=1e-7)
+    rows = w.float().cpu().numpy()
+    assert np.isnan(rows[:, 5]).all() and np.isnan(rows[:, 4000]).all()
+    assert np.isposinf(rows[:, 77]).all() and np.isneginf(rows[:, 78]).all()
+    assert np.isfinite(rows[:, :5]).all()
+    mon.close()
