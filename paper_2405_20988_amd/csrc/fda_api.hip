@@ -513,16 +513,23 @@ int fda_create(fda_ctx** ctx, const fda_desc* desc, void* workspace, size_t work
     delete c;
     return fail(FDA_EHIP, "hipGetDevice failed");
   }
-  rc = dispatch_any(desc->dtype, fda::kCellI32, pl.narrow, nullptr, nullptr);
-  if (rc == FDA_OK) rc = dispatch_mean(desc->dtype, fda::kCellI64, pl.mean, nullptr, nullptr);
+  // The dynamic-LDS limit of a kernel is one setting per process: raise it to everything the
+  // device allows, so that a context created later with a smaller sketch cannot lower it under
+  // what an earlier context's launches need.
+  Split narrow_max = pl.narrow, wide_max = pl.wide;
+  MeanSplit mean_max = pl.mean;
+  narrow_max.lds_bytes = wide_max.lds_bytes = mean_max.lds_bytes = lds;
+  rc = dispatch_any(desc->dtype, fda::kCellI32, narrow_max, nullptr, nullptr);
+  if (rc == FDA_OK) rc = dispatch_mean(desc->dtype, fda::kCellI64, mean_max, nullptr, nullptr);
   if (rc == FDA_OK && (desc->variants & FDA_VARIANT_SKETCH))
-    rc = dispatch_mean(desc->dtype, fda::kCellF64, pl.mean, nullptr, nullptr);
+    rc = dispatch_mean(desc->dtype, fda::kCellF64, mean_max, nullptr, nullptr);
   if (rc == FDA_OK && (desc->variants & FDA_VARIANT_SKETCH)) {
-    rc = dispatch_any(desc->dtype, fda::kCellI64, pl.wide, nullptr, nullptr);
-    if (rc == FDA_OK) rc = dispatch_any(desc->dtype, fda::kCellF64, pl.wide, nullptr, nullptr);
+    rc = dispatch_any(desc->dtype, fda::kCellI64, wide_max, nullptr, nullptr);
+    if (rc == FDA_OK) rc = dispatch_any(desc->dtype, fda::kCellF64, wide_max, nullptr, nullptr);
     if (rc == FDA_OK &&
         hipFuncSetAttribute(reinterpret_cast<const void*>(fda::cell_count_kernel),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, desc->m * 4) != hipSuccess)
+                            hipFuncAttributeMaxDynamicSharedMemorySize,
+                            (int)lds - 1024) != hipSuccess)   // the kernel also has a little static LDS
       rc = fail(FDA_EHIP, "hipFuncSetAttribute(cell_count_kernel) failed");
   }
   if (rc != FDA_OK) {

@@ -149,3 +149,27 @@ def test_step_under_graph_capture(mode):
         assert np.array_equal(bits(st_g), bits(st_e)), r
     mon_g.close()
     mon_e.close()
+
+
+def test_contexts_with_different_sketch_sizes_coexist():
+    """Two contexts that use the same kernels with very different amounts of LDS, created large
+    first and then small: the later one must not shrink what the earlier one may launch with."""
+    say("[case] a large-sketch context stays usable after a small-sketch one is created")
+    from oracle import fda_oracle as O
+    big = S.make("cfg5", device=DEV, seed=14, d=100_003)           # 7 x 1000: 140 KB of LDS
+    mon_big = monitor_for(big)
+    small = S.make("cfg5", device=DEV, seed=15, d=50_001, K=4, l=7, m=8)   # same kernels (4 workers x 7
+    assert mon_big.plan["workers_per_group"] == 4                           # rows per workgroup), ~1 KB of LDS
+    mon_small = monitor_for(small)
+    assert (mon_small.plan["workers_per_group"], mon_small.plan["rows_per_group"]) == (4, 7)
+    for mon, wl in ((mon_small, small), (mon_big, big), (mon_small, small)):
+        mon.local_state(wl.w, wl.w_t0, wl.xi)
+        mon.mean_state(wl.w, wl.w_t0, wl.xi)
+        torch.cuda.synchronize()
+        ref = O.local_state(S.slab_to_numpy(wl.w), wl.dtype, wl.w_t0.cpu().numpy(), wl.xi.cpu().numpy(),
+                            wl.hash_coef, wl.m)
+        n, _, _ = mon.state_numpy()
+        assert np.allclose(n, ref["n"], rtol=1e-5)
+        assert mon.mean_numpy()[0] == pytest.approx(float(ref["n"].mean()), rel=1e-5)
+    mon_big.close()
+    mon_small.close()
