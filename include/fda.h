@@ -137,7 +137,9 @@ int fda_workspace_bytes(const fda_desc* desc, size_t* bytes);
  * aligned, of at least fda_workspace_bytes() bytes, owned by the caller and left with the
  * context until fda_destroy.  On failure *ctx is set to NULL.
  * All calls of one context use that workspace for their partial results: enqueue them on one
- * stream (or order them yourself); calls of one context that overlap on the device race. */
+ * stream (or order them yourself); calls of one context that overlap on the device race.  A
+ * context is used by one host thread at a time, with the device it was created on current
+ * (anything else is FDA_EINVAL). */
 int fda_create(fda_ctx** ctx, const fda_desc* desc, void* workspace, size_t workspace_bytes);
 int fda_destroy(fda_ctx* ctx);
 

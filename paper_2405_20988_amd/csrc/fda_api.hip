@@ -425,10 +425,21 @@ int prepare_sketch(fda_ctx* ctx, const void* w, const float* w_t0, fda::ScaleInf
   return FDA_OK;
 }
 
+// Launches go to the current device: it must be the one the context (and its workspace) lives on.
+int check_device(const fda_ctx* ctx) {
+  int dev = -1;
+  FDA_HIP(hipGetDevice(&dev));
+  if (dev != ctx->device)
+    return fail(FDA_EINVAL, "the context was created on device %d but device %d is current", ctx->device, dev);
+  return FDA_OK;
+}
+
 // The argument checks fda_local_state and fda_mean_state share.
 int check_state_args(const fda_ctx* ctx, const void* w, const float* w_t0, const float* xi, const float* out) {
   if (ctx == nullptr || w == nullptr || w_t0 == nullptr || out == nullptr)
     return fail(FDA_EINVAL, "NULL argument");
+  int rcd = check_device(ctx);
+  if (rcd != FDA_OK) return rcd;
   const fda_desc& d = ctx->desc;
   if ((d.variants & FDA_VARIANT_LINEAR) && xi == nullptr)
     return fail(FDA_EINVAL, "xi is NULL but FDA_VARIANT_LINEAR is requested");
@@ -732,6 +743,8 @@ static int estimate_rows(fda_ctx* ctx, const float* state, int rows, double thet
   if (ctx == nullptr || state == nullptr || out_dev == nullptr)
     return fail(FDA_EINVAL, "NULL argument");
   if (reinterpret_cast<uintptr_t>(out_dev) % 8 != 0) return fail(FDA_EINVAL, "out_dev must be 8-byte aligned");
+  int rcd = check_device(ctx);
+  if (rcd != FDA_OK) return rcd;
   if (!(tie_tol >= 0.0)) return fail(FDA_EINVAL, "tie_tol must be >= 0");
   const fda_desc& d = ctx->desc;
   hipStream_t st = static_cast<hipStream_t>(stream);
@@ -765,6 +778,8 @@ int fda_estimate_variance_mean(fda_ctx* ctx, const float* mean_state, double the
 int fda_sync(fda_ctx* ctx, void* w, float* w_t0, float* w_prev, const int32_t* pred_dev,
              void* stream) {
   if (ctx == nullptr || w == nullptr || w_t0 == nullptr) return fail(FDA_EINVAL, "NULL argument");
+  int rcd = check_device(ctx);
+  if (rcd != FDA_OK) return rcd;
   const fda_desc& d = ctx->desc;
   const int esz = d.dtype == FDA_F32 ? 4 : 2;
   hipStream_t st = static_cast<hipStream_t>(stream);
@@ -791,6 +806,8 @@ int fda_sync_from_mean(fda_ctx* ctx, void* w, float* w_t0, float* w_prev, float*
                        const float* w_bar, const int32_t* pred_dev, void* stream) {
   if (ctx == nullptr || w == nullptr || w_t0 == nullptr || w_bar == nullptr)
     return fail(FDA_EINVAL, "NULL argument");
+  int rcd = check_device(ctx);
+  if (rcd != FDA_OK) return rcd;
   const fda_desc& d = ctx->desc;
   const int esz = d.dtype == FDA_F32 ? 4 : 2;
   hipStream_t st = static_cast<hipStream_t>(stream);
@@ -819,6 +836,8 @@ int fda_update_xi(fda_ctx* ctx, const float* w_t0, const float* w_prev, float* x
                   const int32_t* pred_dev, void* stream) {
   if (ctx == nullptr || w_t0 == nullptr || w_prev == nullptr || xi == nullptr)
     return fail(FDA_EINVAL, "NULL argument");
+  int rcd = check_device(ctx);
+  if (rcd != FDA_OK) return rcd;
   const fda_desc& d = ctx->desc;
   hipStream_t st = static_cast<hipStream_t>(stream);
   double* partial = reinterpret_cast<double*>(ctx->ws + ctx->plan.off_xi);
