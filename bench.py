@@ -124,14 +124,18 @@ def main():
     torch.cuda.synchronize()
     F.fda_profile_enable(mon.ctx, True)
     F.fda_profile_read(mon.ctx, reset=True)
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for _ in range(args.steps):
+    marks[0].record()
+    for i in range(args.steps):
         step()
+        marks[i + 1].record()
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     kernel_ms, launches = F.fda_profile_read(mon.ctx, reset=True)
     F.fda_profile_enable(mon.ctx, False)
+    per_step = sorted(marks[i].elapsed_time(marks[i + 1]) for i in range(args.steps))
     est = mon.estimate_variance(theta)
     assert (est.sync_sketch if args.variants & 2 else est.sync_linear) == 0
     ms_per_step = (t1 - t0) * 1e3 / args.steps
@@ -228,7 +232,16 @@ def main():
     torch.cuda.synchronize()
     fused_ms = ev0.elapsed_time(ev1) / reps
     fused_bytes = K * d * esz + 4 * d * 5
-    sync_info = {"sync_from_mean_ms": round(fused_ms, 4),
+    # what a run pays per step when it synchronizes every `period` steps (the synthetic runs of the
+    # two configurations that have a step count synchronize about 5 times in 100 steps, resp. every
+    # 4-5 steps); never part of `value`
+    period = {"cfg2": 20.0, "cfg5": 4.5}.get(args.config)
+    amortized = None
+    if period is not None:
+        amortized = {"sync_every_steps": period,
+                     "ms_per_step_incl_syncs": round(ms_per_step + (sync_ms + xi_ms) / period, 4),
+                     "mean_state_mode_ms_per_step_incl_syncs": round(mean_ms + (sync_ms + xi_ms) / period, 4)}
+    sync_info = {"amortized": amortized, "sync_from_mean_ms": round(fused_ms, 4),
                  "sync_from_mean_GBps": round(fused_bytes / fused_ms / 1e6, 1),
                  "sync_from_mean_algorithmic_bytes": fused_bytes,
                  "sync_ms": round(sync_ms, 4), "sync_GBps": round(sync_bytes / sync_ms / 1e6, 1),
@@ -238,7 +251,9 @@ def main():
     out = {
         "metric": "worker-params/s (K*d per step) for local-state+variance check",
         "value": value, "unit": "worker-params/s", "n_gpus": 1, "steps": args.steps,
-        "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True,
+        "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+        "ms_per_step_median": round(per_step[len(per_step) // 2], 4), "ms_per_step_min": round(per_step[0], 4),
+        "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None,
         # the arithmetic type: drifts, norms and projections in fp32 (fp64 across tiles), sketch cells
         # as exact integers of fp32-rounded terms; the slab's storage type is in config.slab_dtype
