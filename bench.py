@@ -216,6 +216,10 @@ def main():
     torch.cuda.synchronize()
     sync_ms = ev0.elapsed_time(ev1) / reps
     sync_bytes = 2 * K * d * esz + 4 * d * (3 if w_prev is not None else 1)
+    # after the forced synchronizations w_prev equals w_t0; a model change that is not zero makes
+    # the refresh of xi do its real work
+    w_prev.add_(torch.randn_like(w_prev) * 1e-3)
+    torch.cuda.synchronize()
     ev0.record()
     for _ in range(reps):
         mon.update_xi(wl.w_t0, w_prev, wl.xi, pred=None)

@@ -41,7 +41,7 @@ constexpr double kSharedByteCost = 0.5;    // per byte of w_t0 / xi / table re-r
 constexpr int kMaxEstBlocksPerRow = 128;   // 32768 / 256: workgroups of estimate_kernel per sketch row
 constexpr int kScaleSamples = 16384;       // sampled coordinates per worker for the scale
 constexpr int kScaleBlocks = kScaleSamples * fda::kScaleSlices / fda::kSmallThreads;   // its workgroups
-constexpr int kXiBlocks = 1024;
+constexpr int kXiBlocks = 4096;
 constexpr int64_t kAlign = 256;
 
 int64_t round_up(int64_t x, int64_t a) { return (x + a - 1) / a * a; }
@@ -841,17 +841,20 @@ int fda_update_xi(fda_ctx* ctx, const float* w_t0, const float* w_prev, float* x
   const fda_desc& d = ctx->desc;
   hipStream_t st = static_cast<hipStream_t>(stream);
   double* partial = reinterpret_cast<double*>(ctx->ws + ctx->plan.off_xi);
-  long long blocks = (d.d + fda::kSmallThreads * 8 - 1) / (fda::kSmallThreads * 8);
+  const int vec_ok = aligned16(w_t0) && aligned16(w_prev) && aligned16(xi);
+  const long long items = vec_ok ? (d.d + 3) / 4 : d.d;       // what one thread takes per loop trip
+  long long blocks = (items + fda::kSmallThreads * 4 - 1) / (fda::kSmallThreads * 4);
   if (blocks > kXiBlocks) blocks = kXiBlocks;
   if (blocks < 1) blocks = 1;
   hipLaunchKernelGGL(fda::xi_norm_kernel, dim3((unsigned)blocks), dim3(fda::kSmallThreads), 0, st,
-                     w_t0, w_prev, pred_dev, (long long)d.d, partial);
+                     w_t0, w_prev, pred_dev, (long long)d.d, vec_ok, partial);
   FDA_HIP(hipGetLastError());
-  long long sblocks = (d.d + fda::kSmallThreads - 1) / fda::kSmallThreads;
+  long long sblocks = (items + fda::kSmallThreads - 1) / fda::kSmallThreads;
   const long long cap = (long long)ctx->cus * 16;
   if (sblocks > cap) sblocks = cap;
+  if (sblocks < 1) sblocks = 1;
   hipLaunchKernelGGL(fda::xi_scale_kernel, dim3((unsigned)sblocks), dim3(fda::kSmallThreads), 0, st,
-                     w_t0, w_prev, xi, pred_dev, (long long)d.d, partial, (int)blocks);
+                     w_t0, w_prev, xi, pred_dev, (long long)d.d, vec_ok, partial, (int)blocks);
   FDA_HIP(hipGetLastError());
   return FDA_OK;
 }

@@ -512,20 +512,22 @@ sync_kernel(T* __restrict__ w, float* __restrict__ w_t0, float* __restrict__ w_p
 // ----------------------------------------------------------------------------------------
 __global__ void __launch_bounds__(kSmallThreads)
 xi_norm_kernel(const float* __restrict__ w_t0, const float* __restrict__ w_prev,
-               const int32_t* __restrict__ pred, long long d, double* __restrict__ partial) {
+               const int32_t* __restrict__ pred, long long d, int vec_ok, double* __restrict__ partial) {
   __shared__ double scratch[kSmallThreads / 64];
   if (pred != nullptr && *pred == 0) return;
   double acc = 0.0;
   const long long step = (long long)gridDim.x * blockDim.x;
-  long long j = (long long)blockIdx.x * blockDim.x + threadIdx.x;
-  while (j < d) {
-    float part = 0.0f;                       // a short fp32 run, then fp64
-#pragma unroll
-    for (int t = 0; t < 8; ++t) {
-      if (j < d) { const float df = w_t0[j] - w_prev[j]; part = fmaf(df, df, part); }
-      j += step;
-    }
-    acc += (double)part;
+  const long long t0 = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  const long long nvec = vec_ok ? d / 4 : 0;             // whole 16-byte vectors
+  for (long long v = t0; v < nvec; v += step) {
+    const float4 a = reinterpret_cast<const float4*>(w_t0)[v];
+    const float4 b = reinterpret_cast<const float4*>(w_prev)[v];
+    const float dx = a.x - b.x, dy = a.y - b.y, dz = a.z - b.z, dw = a.w - b.w;
+    acc += (double)fmaf(dx, dx, fmaf(dy, dy, fmaf(dz, dz, dw * dw)));   // a short fp32 run, then fp64
+  }
+  for (long long j = nvec * 4 + t0; j < d; j += step) {  // the tail, or everything without vectors
+    const float df = w_t0[j] - w_prev[j];
+    acc += (double)(df * df);
   }
   const double s = block_sum(acc, scratch);
   if (threadIdx.x == 0) partial[blockIdx.x] = s;
@@ -533,7 +535,7 @@ xi_norm_kernel(const float* __restrict__ w_t0, const float* __restrict__ w_prev,
 
 __global__ void __launch_bounds__(kSmallThreads)
 xi_scale_kernel(const float* __restrict__ w_t0, const float* __restrict__ w_prev,
-                float* __restrict__ xi, const int32_t* __restrict__ pred, long long d,
+                float* __restrict__ xi, const int32_t* __restrict__ pred, long long d, int vec_ok,
                 const double* __restrict__ partial, int npartial) {
   __shared__ double scratch[kSmallThreads / 64];
   __shared__ float scale_sh;
@@ -547,8 +549,17 @@ xi_scale_kernel(const float* __restrict__ w_t0, const float* __restrict__ w_prev
   }
   __syncthreads();
   const float scale = scale_sh;
-  for (long long j = (long long)blockIdx.x * blockDim.x + threadIdx.x; j < d;
-       j += (long long)gridDim.x * blockDim.x) {
+  const long long step = (long long)gridDim.x * blockDim.x;
+  const long long t0 = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  const long long nvec = vec_ok ? d / 4 : 0;
+  for (long long v = t0; v < nvec; v += step) {
+    const float4 a = reinterpret_cast<const float4*>(w_t0)[v];
+    const float4 b = reinterpret_cast<const float4*>(w_prev)[v];
+    float4 o = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+    if (scale != 0.0f) o = make_float4((a.x - b.x) * scale, (a.y - b.y) * scale, (a.z - b.z) * scale, (a.w - b.w) * scale);
+    reinterpret_cast<float4*>(xi)[v] = o;
+  }
+  for (long long j = nvec * 4 + t0; j < d; j += step) {
     const float df = w_t0[j] - w_prev[j];
     xi[j] = (scale == 0.0f) ? 0.0f : df * scale;
   }
