@@ -40,7 +40,7 @@ constexpr double kDecodeCost = 5.0;        // unpack one table entry into an LDS
 constexpr double kSharedByteCost = 0.5;    // per byte of w_t0 / xi / table re-read by another workgroup
 constexpr int kMaxEstBlocksPerRow = 128;   // 32768 / 256: workgroups of estimate_kernel per sketch row
 constexpr int kScaleSamples = 16384;       // sampled coordinates per worker for the scale
-constexpr int kScaleBlocks = kScaleSamples * fda::kScaleSlices / fda::kSmallThreads;   // its workgroups
+constexpr int kScaleBlocks = kScaleSamples * fda::kScaleMaxSlices / fda::kSmallThreads;   // its workgroups, at most
 constexpr int kXiBlocks = 4096;
 constexpr int64_t kAlign = 256;
 
@@ -411,16 +411,18 @@ int prepare_sketch(fda_ctx* ctx, const void* w, const float* w_t0, fda::ScaleInf
     ctx->counted = true;
   }
   const int samples = (int)(d.d < kScaleSamples ? d.d : kScaleSamples);
-  const int sblocks = (samples * fda::kScaleSlices + fda::kSmallThreads - 1) / fda::kSmallThreads;
+  int slices = (d.K + 7) / 8;                 // about eight workers per thread
+  if (slices > fda::kScaleMaxSlices) slices = fda::kScaleMaxSlices;
+  const int sblocks = (samples * slices + fda::kSmallThreads - 1) / fda::kSmallThreads;
   unsigned int* ticket = reinterpret_cast<unsigned int*>(ctx->ws + pl.off_ticket);
   if (d.dtype == FDA_F32)
     hipLaunchKernelGGL(fda::scale_kernel<float>, dim3(sblocks), dim3(fda::kSmallThreads), 0, st,
                        static_cast<const float*>(w), w_t0, d.K, (long long)d.d, (long long)d.row_stride,
-                       samples, smax, ssum, ticket, nmax, scale);
+                       samples, slices, smax, ssum, ticket, nmax, scale);
   else
     hipLaunchKernelGGL(fda::scale_kernel<fda::bf16_t>, dim3(sblocks), dim3(fda::kSmallThreads), 0, st,
                        static_cast<const fda::bf16_t*>(w), w_t0, d.K, (long long)d.d,
-                       (long long)d.row_stride, samples, smax, ssum, ticket, nmax, scale);
+                       (long long)d.row_stride, samples, slices, smax, ssum, ticket, nmax, scale);
   FDA_HIP(hipGetLastError());
   return FDA_OK;
 }

@@ -159,16 +159,16 @@ __device__ inline ScaleInfo choose_scale(float amax, double mean, const unsigned
 // Largest and mean |w_kj - w_t0_j| over `samples` coordinates of every worker: evenly spaced runs
 // of 8 consecutive coordinates (a run shares its cache lines, so the scattered reads cost an
 // eighth of what single coordinates would).  A thread takes one sampled coordinate and every
-// kScaleSlices-th worker (the loads of one thread are independent HBM misses: few per thread,
+// slices-th worker (the loads of one thread are independent HBM misses: about eight per thread,
 // several in flight); per-workgroup maximum and sum;
 // the workgroup that finishes last combines the per-workgroup results in a fixed order, chooses
 // the scales and clears the flags.  `ticket` counts finished workgroups and is left at zero.
-constexpr int kScaleSlices = 8;
+constexpr int kScaleMaxSlices = 8;          // a sampled coordinate's workers are split over 1..8 threads
 
 template <typename T>
 __global__ void __launch_bounds__(kSmallThreads)
 scale_kernel(const T* __restrict__ w, const float* __restrict__ w_t0, int K, long long d,
-             long long row_stride, int samples, float* __restrict__ part_max,
+             long long row_stride, int samples, int slices, float* __restrict__ part_max,
              double* __restrict__ part_sum, unsigned int* __restrict__ ticket,
              const unsigned int* __restrict__ nmax, ScaleInfo* __restrict__ out) {
   __shared__ float sh[kSmallThreads / 64];
@@ -177,7 +177,7 @@ scale_kernel(const T* __restrict__ w, const float* __restrict__ w_t0, int K, lon
   float m = 0.0f;
   double sum = 0.0;
   const int t = blockIdx.x * blockDim.x + threadIdx.x;
-  const int smp = t / kScaleSlices, slice = t - smp * kScaleSlices;
+  const int smp = t / slices, slice = t - smp * slices;
   if (smp < samples) {
     // samples is a multiple of 8 and at most d, or equal to d (then every coordinate is taken)
     const long long j = (samples & 7) ? (long long)smp
@@ -185,7 +185,7 @@ scale_kernel(const T* __restrict__ w, const float* __restrict__ w_t0, int K, lon
     const float base = w_t0[j];
     float part = 0.0f;
 #pragma unroll 4
-    for (int k = slice; k < K; k += kScaleSlices) {
+    for (int k = slice; k < K; k += slices) {
       const float u = fabsf(Slab<T>::load_one(w + (long long)k * row_stride + j) - base);
       m = fmaxf(m, u);                         // fmaxf drops NaN
       if (u == u && u < 3.0e38f) part += u;
@@ -390,6 +390,7 @@ estimate_kernel(const float* __restrict__ state, int K, int l, int m, int varian
     double sq = 0.0;
     if (col < m) {
       double c = 0.0;
+#pragma unroll 8
       for (int k = 0; k < K; ++k) c += (double)state[(size_t)k * S + 2 + i * m + col];
       c /= (double)K;
       sq = c * c;
