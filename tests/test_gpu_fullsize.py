@@ -102,3 +102,63 @@ def test_full_size_sampled_outputs(name, workers, rows):
     assert est_m.h_sketch == pytest.approx(est.h_sketch, rel=1e-5)
     assert est_m.h_linear == pytest.approx(est.h_linear, rel=1e-5)
     mon.close()
+
+
+def test_longest_vector_the_hash_allows():
+    """d just below the hash prime 2^31 - 1 (the largest the key space allows): 64-bit indexing, the
+    table offsets and the modular arithmetic at the top of the key range.  The drift is zero except
+    at a few probe coordinates (first, last, around multiples of 2^30 and of the tile), so the oracle
+    only has to hash the probes; everything else of the state must be exactly zero."""
+    import paper_2405_20988_amd as F
+    d = (1 << 31) - 1 - 64 - 1            # the largest accepted length
+    K, l, m = 2, 2, 1000
+    say(f"[case] longest vector d={d}")
+    coef = S.hash_coefficients(99, l)
+    w_t0 = torch.zeros(d, device=DEV)
+    xi = torch.zeros(d, device=DEV)
+    w = torch.zeros((K, d), device=DEV, dtype=torch.bfloat16)
+    probes = [0, 1, 2047, 2048, (1 << 30) - 1, 1 << 30, (1 << 30) + 4097, 2_000_000_003, d - 2049, d - 2, d - 1]
+    vals = {}
+    for t, j in enumerate(probes):
+        k = t % K
+        v = float((t % 5) - 2) * 0.25 or 0.75         # exact in bf16
+        w[k, j] = v
+        xi[j] = 0.5 if t % 2 else -0.25
+        vals[(k, j)] = v
+    with pytest.raises(F.FdaError):                   # one more coordinate is refused
+        F.FdaMonitor(K, d + 1, "bf16", 3, l, m, 0.03, coef, device=DEV)
+    mon = F.FdaMonitor(K, d, "bf16", 3, l, m, 0.03, coef, device=DEV)
+    say(f"       plan {mon.plan}")
+    jj = np.array(probes, dtype=np.uint64)
+    want_n = np.zeros(K)
+    want_p = np.zeros(K)
+    want_sk = np.zeros((K, l, m))
+    xi_host = {j: (0.5 if t % 2 else -0.25) for t, j in enumerate(probes)}
+    hashed = [O.bucket_and_sign(coef[i], jj, m) for i in range(l)]
+    for t, j in enumerate(probes):
+        k = t % K
+        v = vals[(k, j)]
+        want_n[k] += v * v
+        want_p[k] += v * xi_host[j]
+        for i in range(l):
+            want_sk[k, i, int(hashed[i][0][t])] += float(hashed[i][1][t]) * v
+    for which in ("workers", "mean"):
+        if which == "workers":
+            mon.local_state(w, w_t0, xi)
+            n, p, sk = mon.state_numpy()
+            assert np.array_equal(n.astype(np.float64), want_n) and np.array_equal(p.astype(np.float64), want_p)
+            assert np.array_equal(sk.astype(np.float64), want_sk)
+        else:
+            mon.mean_state(w, w_t0, xi)
+            nb, pb, skb = mon.mean_numpy()
+            assert nb == want_n.mean() and pb == want_p.mean()
+            assert np.array_equal(skb.astype(np.float64), want_sk.mean(axis=0))
+        torch.cuda.synchronize()
+    # the synchronization at this length: the probes are averaged, everything else stays zero
+    mon.sync(w, w_t0, None)
+    torch.cuda.synchronize()
+    for t, j in enumerate(probes):
+        assert float(w_t0[j]) == vals[(t % K, j)] / K
+        assert float(w[0, j]) == float(w[1, j]) == float(torch.tensor(vals[(t % K, j)] / K).to(torch.bfloat16))
+    assert float(w_t0.abs().sum()) == pytest.approx(sum(abs(v) for v in vals.values()) / K, rel=1e-6)
+    mon.close()
