@@ -87,6 +87,7 @@ MEAN_CASES = [
     ("cfg1", 30_001, {"l": 16, "m": 64}),     # two row groups of 8 rows
     ("cfg1", 30_001, {"l": 1, "m": 1}),
     ("cfg2", 20_000, {"K": 3, "l": 3, "m": 19_000}),   # one row per row group: the sketch fills LDS
+    ("cfg1", 5_000, {"K": 300, "l": 3, "m": 64}),      # many workers: 75 batches of rows per tile
 ]
 
 

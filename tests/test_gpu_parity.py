@@ -91,6 +91,7 @@ STATE_CASES = [
     ("cfg1", 30_001, {"l": 16, "m": 64}),
     ("cfg1", 30_001, {"l": 1, "m": 1}),
     ("cfg2", 20_000, {"K": 3, "l": 1, "m": 19_000}),   # one worker per group: sketch fills LDS
+    ("cfg1", 5_000, {"K": 300, "l": 3, "m": 64}),      # many workers: 38 worker groups
 ]
 
 
