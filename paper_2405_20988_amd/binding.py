@@ -63,14 +63,20 @@ def library_path() -> str:
 
 
 def load_library():
-    """Load libfda.so (built in-tree by paper_2405_20988_amd.build).  Raises if absent."""
+    """Load libfda.so (built in-tree by paper_2405_20988_amd.build; built here if it does not exist
+    yet).  Raises if it is absent and cannot be built."""
     global _lib
     if _lib is not None:
         return _lib
     if not os.path.exists(_LIB_PATH):
-        raise FileNotFoundError(
-            f"{_LIB_PATH} is missing: build it with `python -m paper_2405_20988_amd.build` "
-            "(needs hipcc); there is no CPU fallback")
+        # nothing built yet: build once (a stale library is never rebuilt here; rebuild explicitly)
+        try:
+            from .build import build_library
+            build_library()
+        except Exception as exc:
+            raise FileNotFoundError(
+                f"{_LIB_PATH} is missing and could not be built ({exc}): build it with "
+                "`python -m paper_2405_20988_amd.build` (needs hipcc); there is no CPU fallback") from exc
     lib = C.CDLL(_LIB_PATH)
     vp, i32p = C.c_void_p, C.c_void_p
     lib.fda_strerror.restype = C.c_char_p
