@@ -287,7 +287,10 @@ int fda_last_mean_state_path(fda_ctx* ctx, int32_t* path, void* stream);
  * bracket their streaming kernel -- the pass over the slab, Algorithm 1 line 6 -- with HIP
  * events on the caller's stream.  fda_profile_read waits for the recorded events and returns the
  * accumulated kernel time in milliseconds and the number of launches it covers since the
- * last reset.  Events are created on first enable and destroyed with the context.
+ * last reset.  Events are created on first enable and destroyed with the context.  Leave it off
+ * while a stream is being captured into a HIP graph (the entry points themselves can be captured:
+ * they allocate nothing and record no memset; make the first call of a context outside the capture,
+ * since that one also tabulates the hash).
  */
 int fda_profile_enable(fda_ctx* ctx, int on);
 int fda_profile_read(fda_ctx* ctx, double* state_kernel_ms, int64_t* launches, int reset);
