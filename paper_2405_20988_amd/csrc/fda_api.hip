@@ -266,7 +266,9 @@ int device_shape(int* cus, int64_t* lds) {
   return FDA_OK;
 }
 
-bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
+// Whole-vector loads and stores need dword alignment only: fp32 data always has it; a bf16 slab has
+// it when its base is 4-byte aligned and its rows are an even number of elements apart.
+bool aligned4(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 3) == 0; }
 
 // Route a launch (or, with prm == nullptr, the LDS-limit setup) to the translation unit that
 // holds the kernel for this slab type, cell kind and shape.
@@ -643,8 +645,7 @@ int fda_local_state(fda_ctx* ctx, const void* w, const float* w_t0, const float*
     prm.K = d.K; prm.l = sk ? d.l : 0; prm.m = sk ? d.m : 0;
     prm.G = sp.G; prm.R = sp.R; prm.P = sp.P; prm.stride = sp.stride;
     prm.do_lin = lin; prm.do_sk = sk;
-    prm.vec_ok = aligned16(w) && aligned16(w_t0) && (!lin || aligned16(xi)) &&
-                 (d.row_stride * esz) % 16 == 0;
+    prm.vec_ok = aligned4(w) && (d.row_stride * esz) % 4 == 0;
     prm.part_np = reinterpret_cast<double*>(ctx->ws + pl.off_np);
     prm.part_sk = ctx->ws + pl.off_sk;
     prm.scale = reinterpret_cast<fda::ScaleInfo*>(ctx->ws + pl.off_scale);
@@ -706,9 +707,7 @@ int fda_mean_state(fda_ctx* ctx, const void* w, const float* w_t0, const float* 
   prm.K = d.K; prm.l = sk ? d.l : 0; prm.m = sk ? d.m : 0;
   prm.R = ms.R; prm.P = ms.P;
   prm.do_lin = lin; prm.do_sk = sk;
-  // whole-vector loads: 16 bytes of w_t0 / xi, and 16 (fp32) or 8 (bf16) bytes of a slab row
-  prm.vec_ok = aligned16(w_t0) && (!lin || aligned16(xi)) && (w_bar == nullptr || aligned16(w_bar)) &&
-               reinterpret_cast<uintptr_t>(w) % (4 * esz) == 0 && (d.row_stride * esz) % (4 * esz) == 0;
+  prm.vec_ok = aligned4(w) && (d.row_stride * esz) % 4 == 0;
   prm.w_bar = w_bar;
   prm.part_np = reinterpret_cast<double*>(ctx->ws + pl.off_np);
   prm.part_sk = ctx->ws + pl.off_sk;
@@ -785,8 +784,7 @@ int fda_sync(fda_ctx* ctx, void* w, float* w_t0, float* w_prev, const int32_t* p
   const fda_desc& d = ctx->desc;
   const int esz = d.dtype == FDA_F32 ? 4 : 2;
   hipStream_t st = static_cast<hipStream_t>(stream);
-  const int vec_ok = aligned16(w) && aligned16(w_t0) && (w_prev == nullptr || aligned16(w_prev)) &&
-                     (d.row_stride * esz) % 16 == 0;
+  const int vec_ok = aligned4(w) && (d.row_stride * esz) % 4 == 0;
   const int V = ctx->plan.vec;
   const long long nvec = (d.d + V - 1) / V;
   long long blocks = (nvec + fda::kSmallThreads - 1) / fda::kSmallThreads;
@@ -813,9 +811,7 @@ int fda_sync_from_mean(fda_ctx* ctx, void* w, float* w_t0, float* w_prev, float*
   const fda_desc& d = ctx->desc;
   const int esz = d.dtype == FDA_F32 ? 4 : 2;
   hipStream_t st = static_cast<hipStream_t>(stream);
-  const int vec_ok = aligned16(w) && aligned16(w_t0) && aligned16(w_bar) &&
-                     (w_prev == nullptr || aligned16(w_prev)) && (xi == nullptr || aligned16(xi)) &&
-                     (d.row_stride * esz) % 16 == 0;
+  const int vec_ok = aligned4(w) && (d.row_stride * esz) % 4 == 0;
   const int V = ctx->plan.vec;
   const long long nvec = (d.d + V - 1) / V;
   long long blocks = (nvec + fda::kSmallThreads - 1) / fda::kSmallThreads;
@@ -843,7 +839,7 @@ int fda_update_xi(fda_ctx* ctx, const float* w_t0, const float* w_prev, float* x
   const fda_desc& d = ctx->desc;
   hipStream_t st = static_cast<hipStream_t>(stream);
   double* partial = reinterpret_cast<double*>(ctx->ws + ctx->plan.off_xi);
-  const int vec_ok = aligned16(w_t0) && aligned16(w_prev) && aligned16(xi);
+  const int vec_ok = 1;                                       // fp32 vectors: always dword-aligned
   const long long items = vec_ok ? (d.d + 3) / 4 : d.d;       // what one thread takes per loop trip
   long long blocks = (items + fda::kSmallThreads * 4 - 1) / (fda::kSmallThreads * 4);
   if (blocks > kXiBlocks) blocks = kXiBlocks;

@@ -62,7 +62,7 @@ struct StateParams {
   int stride;             // LDS cells per bucket (>= worker slots of the group, odd)
   int do_lin;
   int do_sk;
-  int vec_ok;             // all pointers / strides allow 16-byte loads
+  int vec_ok;             // all pointers / strides are dword-aligned: whole-vector loads
   double* part_np;        // [P][K][2]
   void* part_sk;          // [P][K][l*m] 8-byte words: int64 (integer cells) or double (fp64 cells)
   ScaleInfo* scale;
@@ -72,17 +72,25 @@ struct StateParams {
 
 struct bf16_t { uint16_t bits; };
 
+// Vectors of 2 or 4 dwords that only promise 4-byte alignment.  gfx950 executes 8- and 16-byte
+// global loads and stores at any dword-aligned address, so a slab whose rows start off the 16-byte
+// grid (d not a multiple of 4 elements) still moves whole vectors.
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4), aligned(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2), aligned(4)));
+typedef float f32x4 __attribute__((ext_vector_type(4), aligned(4)));
+
 // ---- slab element access ---------------------------------------------------------------
 template <typename T> struct Slab;
 template <> struct Slab<float> {
   static constexpr int V = 4;                // elements per 16-byte load
   static __device__ __forceinline__ void load_vec(const float* p, float (&x)[4]) {
-    float4 t = *reinterpret_cast<const float4*>(p);
+    const f32x4 t = *reinterpret_cast<const f32x4*>(p);
     x[0] = t.x; x[1] = t.y; x[2] = t.z; x[3] = t.w;
   }
   static __device__ __forceinline__ float load_one(const float* p) { return *p; }
   static __device__ __forceinline__ void store_vec(float* p, const float (&x)[4]) {
-    *reinterpret_cast<float4*>(p) = make_float4(x[0], x[1], x[2], x[3]);
+    const f32x4 t = {x[0], x[1], x[2], x[3]};
+    *reinterpret_cast<f32x4*>(p) = t;
   }
   static __device__ __forceinline__ void store_one(float* p, float x) { *p = x; }
 };
@@ -94,7 +102,7 @@ __device__ __forceinline__ uint32_t f32_to_bf16_rne(float x) {
 template <> struct Slab<bf16_t> {
   static constexpr int V = 8;
   static __device__ __forceinline__ void load_vec(const bf16_t* p, float (&x)[8]) {
-    uint4 t = *reinterpret_cast<const uint4*>(p);
+    const u32x4 t = *reinterpret_cast<const u32x4*>(p);
     x[0] = __uint_as_float(t.x << 16); x[1] = __uint_as_float(t.x & 0xffff0000u);
     x[2] = __uint_as_float(t.y << 16); x[3] = __uint_as_float(t.y & 0xffff0000u);
     x[4] = __uint_as_float(t.z << 16); x[5] = __uint_as_float(t.z & 0xffff0000u);
@@ -104,12 +112,12 @@ template <> struct Slab<bf16_t> {
     return __uint_as_float((uint32_t)p->bits << 16);
   }
   static __device__ __forceinline__ void store_vec(bf16_t* p, const float (&x)[8]) {
-    uint4 t;
+    u32x4 t;
     t.x = f32_to_bf16_rne(x[0]) | (f32_to_bf16_rne(x[1]) << 16);
     t.y = f32_to_bf16_rne(x[2]) | (f32_to_bf16_rne(x[3]) << 16);
     t.z = f32_to_bf16_rne(x[4]) | (f32_to_bf16_rne(x[5]) << 16);
     t.w = f32_to_bf16_rne(x[6]) | (f32_to_bf16_rne(x[7]) << 16);
-    *reinterpret_cast<uint4*>(p) = t;
+    *reinterpret_cast<u32x4*>(p) = t;
   }
   static __device__ __forceinline__ void store_one(bf16_t* p, float x) {
     p->bits = (uint16_t)f32_to_bf16_rne(x);
@@ -120,15 +128,17 @@ template <int V>
 __device__ __forceinline__ void load_f32_vec(const float* p, float (&x)[V]) {
 #pragma unroll
   for (int q = 0; q < V; q += 4) {
-    float4 t = *reinterpret_cast<const float4*>(p + q);
+    const f32x4 t = *reinterpret_cast<const f32x4*>(p + q);
     x[q] = t.x; x[q + 1] = t.y; x[q + 2] = t.z; x[q + 3] = t.w;
   }
 }
 template <int V>
 __device__ __forceinline__ void store_f32_vec(float* p, const float (&x)[V]) {
 #pragma unroll
-  for (int q = 0; q < V; q += 4)
-    *reinterpret_cast<float4*>(p + q) = make_float4(x[q], x[q + 1], x[q + 2], x[q + 3]);
+  for (int q = 0; q < V; q += 4) {
+    const f32x4 t = {x[q], x[q + 1], x[q + 2], x[q + 3]};
+    *reinterpret_cast<f32x4*>(p + q) = t;
+  }
 }
 
 __device__ __forceinline__ double wave_sum(double v) {
@@ -312,10 +322,10 @@ state_kernel(const StateParams prm) {
 #pragma unroll
       for (int k = 0; k < KC; ++k) {
         if constexpr (sizeof(T) == 4) {
-          const uint4 q = *reinterpret_cast<const uint4*>(wrow[k] + j0);
+          const u32x4 q = *reinterpret_cast<const u32x4*>(wrow[k] + j0);
           t.w[k][0] = q.x; t.w[k][1] = q.y; t.w[k][2] = q.z; t.w[k][3] = q.w;
         } else {
-          const uint2 q = *reinterpret_cast<const uint2*>(wrow[k] + j0);
+          const u32x2 q = *reinterpret_cast<const u32x2*>(wrow[k] + j0);
           t.w[k][0] = q.x; t.w[k][1] = q.y;
         }
       }
@@ -327,7 +337,7 @@ state_kernel(const StateParams prm) {
         }
       }
     };
-    // element by element, every access tested: ragged tails and unaligned slabs
+    // element by element, every access tested: ragged tails and slabs without dword alignment
     auto load_slow = [&](Tile& t, long long j0) {
 #pragma unroll
       for (int v = 0; v < V; ++v) {

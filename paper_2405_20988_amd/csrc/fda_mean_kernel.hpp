@@ -153,10 +153,10 @@ mean_state_kernel(const MeanParams prm) {
         const int row = (k0 + k < K) ? k0 + k : K - 1;
         const T* src = wbase + (long long)row * rs + j0;
         if constexpr (sizeof(T) == 4) {
-          const uint4 q = *reinterpret_cast<const uint4*>(src);
+          const u32x4 q = *reinterpret_cast<const u32x4*>(src);
           bt.w[k][0] = q.x; bt.w[k][1] = q.y; bt.w[k][2] = q.z; bt.w[k][3] = q.w;
         } else {
-          const uint2 q = *reinterpret_cast<const uint2*>(src);
+          const u32x2 q = *reinterpret_cast<const u32x2*>(src);
           bt.w[k][0] = q.x; bt.w[k][1] = q.y;
         }
       }

@@ -521,8 +521,8 @@ xi_norm_kernel(const float* __restrict__ w_t0, const float* __restrict__ w_prev,
   const long long t0 = (long long)blockIdx.x * blockDim.x + threadIdx.x;
   const long long nvec = vec_ok ? d / 4 : 0;             // whole 16-byte vectors
   for (long long v = t0; v < nvec; v += step) {
-    const float4 a = reinterpret_cast<const float4*>(w_t0)[v];
-    const float4 b = reinterpret_cast<const float4*>(w_prev)[v];
+    const f32x4 a = reinterpret_cast<const f32x4*>(w_t0)[v];
+    const f32x4 b = reinterpret_cast<const f32x4*>(w_prev)[v];
     const float dx = a.x - b.x, dy = a.y - b.y, dz = a.z - b.z, dw = a.w - b.w;
     acc += (double)fmaf(dx, dx, fmaf(dy, dy, fmaf(dz, dz, dw * dw)));   // a short fp32 run, then fp64
   }
@@ -554,11 +554,11 @@ xi_scale_kernel(const float* __restrict__ w_t0, const float* __restrict__ w_prev
   const long long t0 = (long long)blockIdx.x * blockDim.x + threadIdx.x;
   const long long nvec = vec_ok ? d / 4 : 0;
   for (long long v = t0; v < nvec; v += step) {
-    const float4 a = reinterpret_cast<const float4*>(w_t0)[v];
-    const float4 b = reinterpret_cast<const float4*>(w_prev)[v];
-    float4 o = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
-    if (scale != 0.0f) o = make_float4((a.x - b.x) * scale, (a.y - b.y) * scale, (a.z - b.z) * scale, (a.w - b.w) * scale);
-    reinterpret_cast<float4*>(xi)[v] = o;
+    const f32x4 a = reinterpret_cast<const f32x4*>(w_t0)[v];
+    const f32x4 b = reinterpret_cast<const f32x4*>(w_prev)[v];
+    f32x4 o = {0.0f, 0.0f, 0.0f, 0.0f};
+    if (scale != 0.0f) o = (a - b) * scale;
+    reinterpret_cast<f32x4*>(xi)[v] = o;
   }
   for (long long j = nvec * 4 + t0; j < d; j += step) {
     const float df = w_t0[j] - w_prev[j];
