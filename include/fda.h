@@ -157,9 +157,8 @@ int fda_get_plan(const fda_ctx* ctx, fda_plan_info* out);
  *          state[k][1] = <xi, w_k - w_t0> (0 without LINEAR),
  *          state[k][2 + i*m + b] = sum over coordinates j in bucket b of row i of
  *          sign_i(j) (w_kj - w_t0_j)   (absent without SKETCH)
- * Whole-vector loads need dword alignment only: an fp32 slab always has it (any d, any
- * row_stride); a bf16 slab has it when its base is 4-byte aligned and row_stride is even.  Anything
- * else is handled element by element (slow, not an error).
+ * Pointers need the alignment of their element type only (2 bytes for a bf16 slab, 4 for everything
+ * fp32; anything less is FDA_EINVAL): whole-vector loads are used for any d and any row_stride.
  * Sketch cells are accumulated as integers (a drift u enters as round(u * 2^e), 2^e chosen
  * per call so that the rounding is at most 2^-19 of the mean |u|), and everything across
  * workgroups is merged in a fixed order: the state is bit-identical from run to run.

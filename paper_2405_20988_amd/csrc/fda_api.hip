@@ -266,9 +266,10 @@ int device_shape(int* cus, int64_t* lds) {
   return FDA_OK;
 }
 
-// Whole-vector loads and stores need dword alignment only: fp32 data always has it; a bf16 slab has
-// it when its base is 4-byte aligned and its rows are an even number of elements apart.
-bool aligned4(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 3) == 0; }
+// Whole-vector loads and stores only need the alignment of the element type, which every entry point
+// checks of its pointers: the vector path is always available (the element-wise path of the kernels
+// serves the ragged end of a vector).
+constexpr int kVecOk = 1;
 
 // Route a launch (or, with prm == nullptr, the LDS-limit setup) to the translation unit that
 // holds the kernel for this slab type, cell kind and shape.
@@ -635,7 +636,6 @@ int fda_local_state(fda_ctx* ctx, const void* w, const float* w_t0, const float*
   const Plan& pl = ctx->plan;
   const bool lin = (d.variants & FDA_VARIANT_LINEAR) != 0;
   const bool sk = (d.variants & FDA_VARIANT_SKETCH) != 0;
-  const int esz = d.dtype == FDA_F32 ? 4 : 2;
   hipStream_t st = static_cast<hipStream_t>(stream);
 
   auto params_for = [&](const Split& sp) {
@@ -645,7 +645,7 @@ int fda_local_state(fda_ctx* ctx, const void* w, const float* w_t0, const float*
     prm.K = d.K; prm.l = sk ? d.l : 0; prm.m = sk ? d.m : 0;
     prm.G = sp.G; prm.R = sp.R; prm.P = sp.P; prm.stride = sp.stride;
     prm.do_lin = lin; prm.do_sk = sk;
-    prm.vec_ok = aligned4(w) && (d.row_stride * esz) % 4 == 0;
+    prm.vec_ok = kVecOk;
     prm.part_np = reinterpret_cast<double*>(ctx->ws + pl.off_np);
     prm.part_sk = ctx->ws + pl.off_sk;
     prm.scale = reinterpret_cast<fda::ScaleInfo*>(ctx->ws + pl.off_scale);
@@ -693,7 +693,6 @@ int fda_mean_state(fda_ctx* ctx, const void* w, const float* w_t0, const float* 
   const MeanSplit& ms = pl.mean;
   const bool lin = (d.variants & FDA_VARIANT_LINEAR) != 0;
   const bool sk = (d.variants & FDA_VARIANT_SKETCH) != 0;
-  const int esz = d.dtype == FDA_F32 ? 4 : 2;
   // a cell's integer sum stays below K * chunk * 2^30 in magnitude
   if (sk && (double)d.K * (double)ms.chunk >= 8589934592.0)
     return fail(FDA_ERANGE, "K * coordinates per workgroup must stay below 2^33");
@@ -707,7 +706,7 @@ int fda_mean_state(fda_ctx* ctx, const void* w, const float* w_t0, const float* 
   prm.K = d.K; prm.l = sk ? d.l : 0; prm.m = sk ? d.m : 0;
   prm.R = ms.R; prm.P = ms.P;
   prm.do_lin = lin; prm.do_sk = sk;
-  prm.vec_ok = aligned4(w) && (d.row_stride * esz) % 4 == 0;
+  prm.vec_ok = kVecOk;
   prm.w_bar = w_bar;
   prm.part_np = reinterpret_cast<double*>(ctx->ws + pl.off_np);
   prm.part_sk = ctx->ws + pl.off_sk;
@@ -782,9 +781,12 @@ int fda_sync(fda_ctx* ctx, void* w, float* w_t0, float* w_prev, const int32_t* p
   int rcd = check_device(ctx);
   if (rcd != FDA_OK) return rcd;
   const fda_desc& d = ctx->desc;
-  const int esz = d.dtype == FDA_F32 ? 4 : 2;
+  const uintptr_t esz = d.dtype == FDA_F32 ? 4 : 2;
+  if (reinterpret_cast<uintptr_t>(w) % esz != 0 || reinterpret_cast<uintptr_t>(w_t0) % 4 != 0 ||
+      (w_prev && reinterpret_cast<uintptr_t>(w_prev) % 4 != 0))
+    return fail(FDA_EINVAL, "pointer not aligned to its element type");
   hipStream_t st = static_cast<hipStream_t>(stream);
-  const int vec_ok = aligned4(w) && (d.row_stride * esz) % 4 == 0;
+  const int vec_ok = kVecOk;
   const int V = ctx->plan.vec;
   const long long nvec = (d.d + V - 1) / V;
   long long blocks = (nvec + fda::kSmallThreads - 1) / fda::kSmallThreads;
@@ -809,9 +811,13 @@ int fda_sync_from_mean(fda_ctx* ctx, void* w, float* w_t0, float* w_prev, float*
   int rcd = check_device(ctx);
   if (rcd != FDA_OK) return rcd;
   const fda_desc& d = ctx->desc;
-  const int esz = d.dtype == FDA_F32 ? 4 : 2;
+  const uintptr_t esz = d.dtype == FDA_F32 ? 4 : 2;
+  if (reinterpret_cast<uintptr_t>(w) % esz != 0 || reinterpret_cast<uintptr_t>(w_t0) % 4 != 0 ||
+      reinterpret_cast<uintptr_t>(w_bar) % 4 != 0 || (w_prev && reinterpret_cast<uintptr_t>(w_prev) % 4 != 0) ||
+      (xi && reinterpret_cast<uintptr_t>(xi) % 4 != 0))
+    return fail(FDA_EINVAL, "pointer not aligned to its element type");
   hipStream_t st = static_cast<hipStream_t>(stream);
-  const int vec_ok = aligned4(w) && (d.row_stride * esz) % 4 == 0;
+  const int vec_ok = kVecOk;
   const int V = ctx->plan.vec;
   const long long nvec = (d.d + V - 1) / V;
   long long blocks = (nvec + fda::kSmallThreads - 1) / fda::kSmallThreads;
@@ -837,9 +843,12 @@ int fda_update_xi(fda_ctx* ctx, const float* w_t0, const float* w_prev, float* x
   int rcd = check_device(ctx);
   if (rcd != FDA_OK) return rcd;
   const fda_desc& d = ctx->desc;
+  if (reinterpret_cast<uintptr_t>(w_t0) % 4 != 0 || reinterpret_cast<uintptr_t>(w_prev) % 4 != 0 ||
+      reinterpret_cast<uintptr_t>(xi) % 4 != 0)
+    return fail(FDA_EINVAL, "pointer not aligned to its element type");
   hipStream_t st = static_cast<hipStream_t>(stream);
   double* partial = reinterpret_cast<double*>(ctx->ws + ctx->plan.off_xi);
-  const int vec_ok = 1;                                       // fp32 vectors: always dword-aligned
+  const int vec_ok = kVecOk;
   const long long items = vec_ok ? (d.d + 3) / 4 : d.d;       // what one thread takes per loop trip
   long long blocks = (items + fda::kSmallThreads * 4 - 1) / (fda::kSmallThreads * 4);
   if (blocks > kXiBlocks) blocks = kXiBlocks;

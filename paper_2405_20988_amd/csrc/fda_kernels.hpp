@@ -62,7 +62,7 @@ struct StateParams {
   int stride;             // LDS cells per bucket (>= worker slots of the group, odd)
   int do_lin;
   int do_sk;
-  int vec_ok;             // all pointers / strides are dword-aligned: whole-vector loads
+  int vec_ok;             // whole-vector loads and stores may be used (pointers are element-aligned)
   double* part_np;        // [P][K][2]
   void* part_sk;          // [P][K][l*m] 8-byte words: int64 (integer cells) or double (fp64 cells)
   ScaleInfo* scale;
@@ -72,12 +72,15 @@ struct StateParams {
 
 struct bf16_t { uint16_t bits; };
 
-// Vectors of 2 or 4 dwords that only promise 4-byte alignment.  gfx950 executes 8- and 16-byte
-// global loads and stores at any dword-aligned address, so a slab whose rows start off the 16-byte
-// grid (d not a multiple of 4 elements) still moves whole vectors.
+// Vectors of 2 or 4 dwords that only promise the alignment of the element they are made of (4 bytes
+// for fp32 data, 2 for bf16).  gfx950 executes 8- and 16-byte global loads and stores at any such
+// address, so a slab whose rows start off the 16-byte grid (d not a multiple of the vector width,
+// odd strides) still moves whole vectors.
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4), aligned(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2), aligned(4)));
 typedef float f32x4 __attribute__((ext_vector_type(4), aligned(4)));
+typedef uint32_t u32x4_h __attribute__((ext_vector_type(4), aligned(2)));     // 8 bf16
+typedef uint32_t u32x2_h __attribute__((ext_vector_type(2), aligned(2)));     // 4 bf16
 
 // ---- slab element access ---------------------------------------------------------------
 template <typename T> struct Slab;
@@ -102,7 +105,7 @@ __device__ __forceinline__ uint32_t f32_to_bf16_rne(float x) {
 template <> struct Slab<bf16_t> {
   static constexpr int V = 8;
   static __device__ __forceinline__ void load_vec(const bf16_t* p, float (&x)[8]) {
-    const u32x4 t = *reinterpret_cast<const u32x4*>(p);
+    const u32x4_h t = *reinterpret_cast<const u32x4_h*>(p);
     x[0] = __uint_as_float(t.x << 16); x[1] = __uint_as_float(t.x & 0xffff0000u);
     x[2] = __uint_as_float(t.y << 16); x[3] = __uint_as_float(t.y & 0xffff0000u);
     x[4] = __uint_as_float(t.z << 16); x[5] = __uint_as_float(t.z & 0xffff0000u);
@@ -112,12 +115,12 @@ template <> struct Slab<bf16_t> {
     return __uint_as_float((uint32_t)p->bits << 16);
   }
   static __device__ __forceinline__ void store_vec(bf16_t* p, const float (&x)[8]) {
-    u32x4 t;
+    u32x4_h t;
     t.x = f32_to_bf16_rne(x[0]) | (f32_to_bf16_rne(x[1]) << 16);
     t.y = f32_to_bf16_rne(x[2]) | (f32_to_bf16_rne(x[3]) << 16);
     t.z = f32_to_bf16_rne(x[4]) | (f32_to_bf16_rne(x[5]) << 16);
     t.w = f32_to_bf16_rne(x[6]) | (f32_to_bf16_rne(x[7]) << 16);
-    *reinterpret_cast<u32x4*>(p) = t;
+    *reinterpret_cast<u32x4_h*>(p) = t;
   }
   static __device__ __forceinline__ void store_one(bf16_t* p, float x) {
     p->bits = (uint16_t)f32_to_bf16_rne(x);
@@ -325,7 +328,7 @@ state_kernel(const StateParams prm) {
           const u32x4 q = *reinterpret_cast<const u32x4*>(wrow[k] + j0);
           t.w[k][0] = q.x; t.w[k][1] = q.y; t.w[k][2] = q.z; t.w[k][3] = q.w;
         } else {
-          const u32x2 q = *reinterpret_cast<const u32x2*>(wrow[k] + j0);
+          const u32x2_h q = *reinterpret_cast<const u32x2_h*>(wrow[k] + j0);
           t.w[k][0] = q.x; t.w[k][1] = q.y;
         }
       }

@@ -156,7 +156,7 @@ mean_state_kernel(const MeanParams prm) {
           const u32x4 q = *reinterpret_cast<const u32x4*>(src);
           bt.w[k][0] = q.x; bt.w[k][1] = q.y; bt.w[k][2] = q.z; bt.w[k][3] = q.w;
         } else {
-          const u32x2 q = *reinterpret_cast<const u32x2*>(src);
+          const u32x2_h q = *reinterpret_cast<const u32x2_h*>(src);
           bt.w[k][0] = q.x; bt.w[k][1] = q.y;
         }
       }

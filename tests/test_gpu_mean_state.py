@@ -321,9 +321,8 @@ def test_sync_from_mean_parity(name, d, over):
 
 
 def test_sync_from_mean_unaligned():
-    """w_bar, w_prev and xi off the 16-byte grid and an odd row stride (dword-aligned vectors for the
-    fp32 slab, the element-wise paths for the bf16 slab); the padding between rows must stay
-    untouched."""
+    """w_bar, w_prev and xi off the 16-byte grid and an odd row stride (vector accesses at element
+    alignment); the padding between rows must stay untouched."""
     say("[case] sync-from-mean unaligned")
     import paper_2405_20988_amd as F
     K, d, l, m = 6, 10_007, 5, 250

@@ -310,8 +310,8 @@ def test_xi_zero_difference_gives_zero_vector():
 
 def test_unaligned_and_strided_slab():
     """Pointers off the 16-byte grid and a row stride that is not a multiple of the vector width:
-    dword-aligned vector accesses for the fp32 slab, the element-wise path for the bf16 slab (its
-    rows start on odd 2-byte offsets); results must not change."""
+    the vector accesses only assume the alignment of the element type (the bf16 rows here start on
+    odd 2-byte offsets); results must not change."""
     say("[case] unaligned / strided slab")
     import paper_2405_20988_amd as F
     K, d, l, m = 6, 10_007, 5, 250
