@@ -27,10 +27,13 @@ Readings taken where the paper is silent (all listed again in the design notes):
   * xi with a zero denominator is the zero vector.
 
 Pinned by tests/test_oracle_*.py (closed forms, hand cases, identities, brute
-force).  The numeric *contents* of a sketch are fixed only through the hash
-reading above -- the paper prints no worked sketch -- so sketch cell values are
-"parity unpinned" with respect to the paper itself; their structure (linearity,
-signed-permutation case, tug-of-war case, column sums, unbiasedness) is pinned.
+force), the absolute-sum scales of the tolerances (abs_projections,
+ams_sketch_abs, ams_sketch_counts, u_mean_abs) included: hand values and
+pure-Python loops.  The numeric *contents* of a sketch are fixed only through the
+hash reading above -- the paper prints no worked sketch -- so sketch cell values
+are "parity unpinned" with respect to the paper itself; their structure
+(linearity, signed-permutation case, tug-of-war case, column sums, unbiasedness)
+is pinned.
 """
 from __future__ import annotations
 
@@ -200,8 +203,12 @@ def m2_estimate(sk: np.ndarray) -> float:
 # --------------------------------------------------------------------------- #
 # local state of all K workers (Algorithm 1, line 6)
 # --------------------------------------------------------------------------- #
-def local_state(w, dtype: str, w_t0: np.ndarray, xi, coef, m: int):
+def local_state(w, dtype: str, w_t0: np.ndarray, xi, coef, m: int, scales: bool = True):
     """States of all K workers.
+
+    scales=False leaves out the absolute-sum scales (p_abs, sk_abs, sk_cnt: only the tests'
+    tolerances use them; the method itself is n, p and sk) -- the benchmark's CPU-baseline leg
+    times the method's own work that way.
 
     Returns a dict with
       n[K]        ||u_k||^2                              (Thm 1 / Thm 2, first component)
@@ -220,12 +227,14 @@ def local_state(w, dtype: str, w_t0: np.ndarray, xi, coef, m: int):
     if xi is not None:
         x = np.asarray(xi, np.float32).astype(np.float64)
         out["p"] = projections(u, x)
-        out["p_abs"] = abs_projections(u, x)
+        if scales:
+            out["p_abs"] = abs_projections(u, x)
     if coef is not None:
         K = u.shape[0]
         out["sk"] = np.stack([ams_sketch(u[k], coef, m) for k in range(K)])
-        out["sk_abs"] = np.stack([ams_sketch_abs(u[k], coef, m) for k in range(K)])
-        out["sk_cnt"] = ams_sketch_counts(u.shape[1], coef, m)
+        if scales:
+            out["sk_abs"] = np.stack([ams_sketch_abs(u[k], coef, m) for k in range(K)])
+            out["sk_cnt"] = ams_sketch_counts(u.shape[1], coef, m)
     return out
 
 

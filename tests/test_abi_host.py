@@ -160,3 +160,22 @@ def test_header_is_plain_c(tmp_path):
     if gxx is not None:
         subprocess.run([gxx, "-std=c++11", "-Wall", "-Wextra", "-Werror", "-pedantic", "-x", "c++", "-fsyntax-only",
                         "-I", os.path.join(root, "include"), str(src)], check=True)
+
+
+def test_cell_tolerance_rule():
+    """tests/fda_tolerance.py: cells holding at least half of what their number of average terms
+    would give are held to 1e-5 * sum|u|; only the nearly empty rest gets the extra allowance."""
+    import numpy as np
+    from fda_tolerance import cell_bounds, check_cells
+    sk_abs = np.array([[[10.0, 4.0, 0.0, 5.0]]])          # one worker, one row, four cells
+    sk_cnt = np.array([[10, 10, 10, 10]])
+    bound, dense = cell_bounds(sk_abs, sk_cnt, np.array([1.0]))
+    assert dense.tolist() == [[[True, False, False, True]]]
+    assert np.allclose(bound, 1e-5 * np.array([[[10.0, 14.0, 10.0, 5.0]]]))
+    want = np.zeros((1, 1, 4))
+    worst, frac = check_cells(want + np.array([9e-5, 1.3e-4, 9e-5, 2.5e-5]), want, sk_abs, sk_cnt, np.array([1.0]))
+    assert worst == pytest.approx(0.9) and frac == 0.5
+    with pytest.raises(AssertionError):
+        check_cells(want + np.array([1.1e-4, 0, 0, 0]), want, sk_abs, sk_cnt, np.array([1.0]))
+    with pytest.raises(AssertionError):                   # a dense cell does not get the allowance
+        check_cells(want + np.array([0, 0, 0, 9e-5]), want, sk_abs, sk_cnt, np.array([1.0]))

@@ -8,6 +8,7 @@ import sys
 import numpy as np
 import pytest
 
+from fda_tolerance import cell_bounds
 from oracle import fda_oracle as O
 
 pytestmark = pytest.mark.gpu
@@ -46,8 +47,8 @@ def test_c_example_against_oracle(K, d, l, m, theta):
     for k in range(K):
         assert got[f"sqnorm_{k}"] == pytest.approx(st["n"][k], rel=RTOL)
         assert abs(got[f"proj_{k}"] - st["p"][k]) <= RTOL * st["p_abs"][k]
-    cell_scale = st["sk_abs"][0, 0, 0] + st["sk_cnt"][0, 0] * st["u_mean_abs"][0]
-    assert abs(got["sketch_0_0_0"] - st["sk"][0, 0, 0]) <= RTOL * cell_scale
+    bound, _ = cell_bounds(st["sk_abs"], st["sk_cnt"], st["u_mean_abs"])
+    assert abs(got["sketch_0_0_0"] - st["sk"][0, 0, 0]) <= bound[0, 0, 0]
     nbar = est["mean_sqnorm"]
     assert got["mean_sqnorm"] == pytest.approx(nbar, rel=RTOL)
     for key in ("h_linear", "h_sketch"):

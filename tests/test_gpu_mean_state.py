@@ -5,7 +5,9 @@ average of the per-worker states fda_local_state writes.
 Tolerances as for the per-worker states, with every scale averaged over the workers:
   mean ||u_k||^2       relative 1e-5
   <xi,u_bar>           1e-5 * mean_k sum_j |xi_j u_kj|
-  sketch cell          1e-5 * mean_k (sum_{j in cell} |u_kj| + n_cell * mean_j |u_kj|)
+  sketch cell          1e-5 * mean_k sum_{j in cell} |u_kj| on every cell where that is at least
+                       half of n_cell * mean_kj |u_kj|; the nearly empty rest: 1e-5 * (that +
+                       n_cell * mean_kj |u_kj|)   (tests/fda_tolerance.py states why)
 Integer-valued inputs must match bit for bit after the one division by K.
 """
 import sys
@@ -15,6 +17,7 @@ import pytest
 import torch
 
 import fda_synth as S
+from fda_tolerance import check_cells
 from oracle import fda_oracle as O
 
 pytestmark = pytest.mark.gpu
@@ -48,9 +51,9 @@ def check_mean(mon, ref, variants=3):
     else:
         assert p == 0.0
     if variants & 2:
-        err = np.abs(sk - ref["sk"])
-        scale = ref["sk_abs"] + ref["sk_cnt"] * ref["u_mean_abs"]
-        assert (err <= RTOL * scale + 1e-30).all(), float((err / (scale + 1e-300)).max())
+        worst, dense = check_cells(sk, ref["sk"], ref["sk_abs"], ref["sk_cnt"], ref["u_mean_abs"])
+        say(f"       mean sketch cells: worst error {worst:.3f} of 1e-5 * mean_k sum|u| "
+            f"({100 * dense:.1f} % of the cells are held to that bound)")
 
 
 def check_estimate(est, ref, variants=3):

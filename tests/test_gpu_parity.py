@@ -4,10 +4,10 @@ on the same seeded input bits.
 Tolerances (fp32 kernels against the fp64 oracle):
   ||u_k||^2, M2, sync outputs      relative 1e-5
   <xi,u_k>                         1e-5 * sum_j |xi_j u_kj|          (a cancelling sum)
-  sketch cell                      1e-5 * (sum_{j in cell} |u_kj| + n_cell * mean_j |u_kj|)
-                                   (a cancelling sum, accumulated in fixed point whose unit is
-                                   at most 2^-18 of the mean |u|: each of the n_cell terms is
-                                   rounded by at most 2^-19 of the mean)
+  sketch cell                      1e-5 * sum_{j in cell} |u_kj|     (a cancelling sum) on every cell
+                                   whose sum of |u_kj| is at least half of n_cell * mean_j |u_kj|;
+                                   the nearly empty rest: 1e-5 * (that sum + n_cell * mean_j |u_kj|)
+                                   (tests/fda_tolerance.py states why)
   H                                1e-5 * mean_k ||u_k||^2           (a difference of O(n) terms)
   decision                         identical, except inside the near-tie band
 Integer-valued inputs make every fp32 sum exact, so there everything must be bit-identical;
@@ -20,6 +20,7 @@ import pytest
 import torch
 
 import fda_synth as S
+from fda_tolerance import check_cells
 from oracle import fda_oracle as O
 
 pytestmark = pytest.mark.gpu
@@ -55,9 +56,9 @@ def check_state(mon, ref, variants=3):
     else:
         assert not p.any()
     if variants & 2:
-        err = np.abs(sk - ref["sk"])
-        scale = ref["sk_abs"] + ref["sk_cnt"][None] * ref["u_mean_abs"][:, None, None]
-        assert (err <= RTOL * scale + 1e-30).all(), float((err / (scale + 1e-300)).max())
+        worst, dense = check_cells(sk, ref["sk"], ref["sk_abs"], ref["sk_cnt"], ref["u_mean_abs"])
+        say(f"       sketch cells: worst error {worst:.3f} of 1e-5 * sum|u| "
+            f"({100 * dense:.1f} % of the cells are held to that bound)")
 
 
 def check_estimate(est, ref, variants=3):

@@ -302,6 +302,80 @@ def test_median_even_rows():
 
 
 # --------------------------------------------------------------------------- #
+# the absolute-sum scales every tolerance of a cancelling sum is relative to
+# --------------------------------------------------------------------------- #
+def test_tolerance_scales_hand_case():
+    """abs_projections, ams_sketch_abs, ams_sketch_counts and u_mean_abs (and their averages in
+    mean_state) against values worked by hand: a helper that returned a multiple of the right
+    scale would loosen every GPU assertion built on it, so each is pinned to exact numbers."""
+    g = gold("hand_case_k3_d8.json")
+    coef = np.array(g["hash_coef"], np.uint32)
+    m = g["m"]
+    w = np.array(g["w"], np.float32)
+    w0 = np.array(g["w_t0"], np.float32)
+    xi = np.array(g["xi_a"], np.float32)
+    st = O.local_state(w, "f32", w0, xi, coef, m)
+    assert st["p_abs"].tolist() == g["p_abs_a"]
+    assert (8 * st["u_mean_abs"]).tolist() == g["u_mean_abs_times_8"]
+    assert st["sk_cnt"].tolist() == g["sk_cnt"]
+    assert st["sk_abs"].tolist() == g["sk_abs"]
+    u = np.array(g["u"], np.float64)
+    assert O.abs_projections(u, xi.astype(np.float64)).tolist() == g["p_abs_a"]
+    assert O.ams_sketch_counts(8, coef, m).tolist() == g["sk_cnt"]
+    for k in range(3):
+        assert O.ams_sketch_abs(u[k], coef, m).tolist() == g["sk_abs"][k]
+    ms = O.mean_state(w, "f32", w0, xi, coef, m)
+    assert 3 * ms["p_abs"] == pytest.approx(g["mean_p_abs_a_times_3"], rel=1e-15)
+    assert 24 * ms["u_mean_abs"] == pytest.approx(g["mean_u_mean_abs_times_24"], rel=1e-15)
+    assert np.allclose(3 * ms["sk_abs"], g["mean_sk_abs_times_3"], rtol=0, atol=1e-14)
+    assert ms["sk_cnt"].tolist() == g["sk_cnt"]
+
+
+def test_tolerance_scales_brute_force():
+    """The same helpers against pure-Python loops on random data (big-integer hash)."""
+    rng = np.random.default_rng(19)
+    K, d, l, m = 3, 45, 3, 6
+    coef = rand_coef(rng, l)
+    w0 = rng.normal(size=d).astype(np.float32)
+    w = (w0 + rng.normal(size=(K, d)) * 1e-2).astype(np.float32)
+    xi = rng.normal(size=d).astype(np.float32)
+    st = O.local_state(w, "f32", w0, xi, coef, m)
+    ms = O.mean_state(w, "f32", w0, xi, coef, m)
+    u = [[float(np.float64(w[k][j]) - np.float64(w0[j])) for j in range(d)] for k in range(K)]
+    cnt = [[0] * m for _ in range(l)]
+    sk_abs = [[[0.0] * m for _ in range(l)] for _ in range(K)]
+    for i in range(l):
+        for j in range(d):
+            b = ((sum(int(coef[i][0][e]) * j**e for e in range(4)) % P) * m) >> 31
+            cnt[i][b] += 1
+            for k in range(K):
+                sk_abs[k][i][b] += abs(u[k][j])
+    assert st["sk_cnt"].tolist() == cnt
+    assert np.allclose(st["sk_abs"], np.array(sk_abs), rtol=1e-14, atol=0)
+    for k in range(K):
+        assert st["p_abs"][k] == pytest.approx(sum(abs(float(xi[j]) * u[k][j]) for j in range(d)), rel=1e-14)
+        assert st["u_mean_abs"][k] == pytest.approx(sum(abs(x) for x in u[k]) / d, rel=1e-14)
+    assert np.allclose(ms["sk_abs"], np.array(sk_abs).sum(axis=0) / K, rtol=1e-14, atol=0)
+    assert ms["u_mean_abs"] == pytest.approx(sum(abs(x) for uk in u for x in uk) / (K * d), rel=1e-14)
+    # every cell's count and absolute sum add up to the whole vector
+    assert st["sk_cnt"].sum(axis=1).tolist() == [d] * l
+    for k in range(K):
+        assert np.allclose(st["sk_abs"][k].sum(axis=1), sum(abs(x) for x in u[k]), rtol=1e-13)
+
+
+@pytest.mark.parametrize("helper", ["abs_projections", "ams_sketch_abs", "ams_sketch_counts"])
+def test_a_doubled_tolerance_scale_is_caught(helper, monkeypatch):
+    """Plant the mistake on the CPU: with a helper that returns twice the scale, the hand-case
+    pin and the brute-force pin above must both fail."""
+    real = getattr(O, helper)
+    monkeypatch.setattr(O, helper, lambda *a, **kw: 2 * real(*a, **kw))
+    with pytest.raises(AssertionError):
+        test_tolerance_scales_hand_case()
+    with pytest.raises(AssertionError):
+        test_tolerance_scales_brute_force()
+
+
+# --------------------------------------------------------------------------- #
 # variance identity and the two theorems
 # --------------------------------------------------------------------------- #
 @pytest.mark.parametrize("K,d", [(1, 50), (2, 7), (5, 1000), (30, 333)])
