@@ -34,16 +34,131 @@ def algorithmic_bytes(K, d, elem_bytes, variants):
 
 
 def traffic_from_profile(workload, kernel="state_kernel"):
-    """HBM bytes per launch of a kernel measured with rocprofv3 --pmc (FETCH_SIZE and
-    WRITE_SIZE runs, scaled by a copy kernel), if a summary for this workload is committed."""
-    path = os.path.join(ROOT, "profiles", f"{kernel}_{workload}_traffic.txt")
+    """(HBM bytes per launch of a kernel, the file they come from): measured with rocprofv3 --pmc
+    (FETCH_SIZE and WRITE_SIZE runs, scaled by a copy kernel) and committed as a summary for this
+    workload -- not measured in this run.  (None, None) without such a summary."""
+    rel = os.path.join("profiles", f"{kernel}_{workload}_traffic.txt")
     try:
-        for line in open(path):
+        for line in open(os.path.join(ROOT, rel)):
             if line.startswith("traffic_bytes_per_launch="):
-                return float(line.split("=", 1)[1])
+                return float(line.split("=", 1)[1]), rel
     except OSError:
         pass
-    return None
+    return None, None
+
+
+def _block_state(job):
+    """One coordinate block of the oracle's local state (a worker process of the all-cores leg)."""
+    from threadpoolctl import threadpool_limits
+    from oracle import fda_oracle as O
+    a, b = job
+    g = _CPU_JOB
+    with threadpool_limits(limits=1):
+        st = O.local_state(g["w"][:, a:b], g["dtype"], g["w0"][a:b], None if g["xi"] is None else g["xi"][a:b],
+                           g["coef"], g["m"], scales=False, j0=a)
+    return st["n"], st["p"], st["sk"]
+
+
+_CPU_JOB = None
+
+
+def cpu_baseline(config, over, variants, sample):
+    """The CPU oracle, as it stands, on a bounded sample of the workload: first on ONE core (the process
+    is pinned to one CPU and the numerical libraries are limited to one thread), then on all the cores
+    this process may use, one coordinate block per core in worker processes (norms, projections and
+    sketches of coordinate blocks add up: Section 3.1, linearity).  Only the method's own work is
+    timed (local state + estimate; the oracle's tolerance scales are left out).  Runs before anything
+    touches the GPU, because it forks."""
+    global _CPU_JOB
+    import multiprocessing as mp
+
+    import numpy as np
+    from threadpoolctl import threadpool_limits
+
+    import fda_synth as S
+    from oracle import fda_oracle as O
+
+    c = dict(S.CONFIGS[config])
+    c.update(over)
+    ds = min(sample, c["d"])
+    wls = S.make(config, device="cpu", seed=0, d=ds, **{k: v for k, v in over.items() if k != "d"})
+    job = {"w": S.slab_to_numpy(wls.w), "dtype": wls.dtype, "w0": wls.w_t0.numpy(),
+           "xi": wls.xi.numpy() if variants & 1 else None,
+           "coef": wls.hash_coef if variants & 2 else None, "m": wls.m}
+    K = wls.K
+    allowed = sorted(os.sched_getaffinity(0))
+    cores = min(len(allowed), 16)                   # a one-GPU box grants 16 cores, whatever it shows
+    # ---- one core
+    os.sched_setaffinity(0, {allowed[0]})
+    try:
+        with threadpool_limits(limits=1):
+            c0 = time.perf_counter()
+            st = O.local_state(job["w"], job["dtype"], job["w0"], job["xi"], job["coef"], job["m"], scales=False)
+            e1 = O.estimate_variance(st["n"], st["p"], st["sk"], wls.eps, 0.0)
+            t_one = time.perf_counter() - c0
+    finally:
+        os.sched_setaffinity(0, set(allowed))
+    # ---- all cores: one coordinate block per core
+    _CPU_JOB = job
+    cuts = [ds * q // cores for q in range(cores + 1)]
+    jobs = [(a, b) for a, b in zip(cuts[:-1], cuts[1:]) if b > a]
+    with mp.get_context("fork").Pool(cores) as pool:
+        pool.map(_block_state, [(0, 1)] * cores)    # start the workers before the clock
+        c0 = time.perf_counter()
+        parts = pool.map(_block_state, jobs, chunksize=1)
+        n = sum(q[0] for q in parts)
+        pj = sum(q[1] for q in parts) if variants & 1 else None
+        sk = sum(q[2] for q in parts) if variants & 2 else None
+        e2 = O.estimate_variance(n, pj, sk, wls.eps, 0.0)
+        t_all = time.perf_counter() - c0
+    _CPU_JOB = None
+    for key in ("mean_sqnorm", "h_linear", "h_sketch"):
+        assert abs(e1[key] - e2[key]) <= 1e-9 * abs(e1["mean_sqnorm"]), key
+    return {"value": K * ds / t_all, "unit": "worker-params/s", "cores": len(jobs), "kind": "oracle",
+            "one_core_value": K * ds / t_one, "one_core_seconds": round(t_one, 2),
+            "all_cores_seconds": round(t_all, 2), "cpus_visible": os.cpu_count(),
+            "sample": f"fp64 numpy oracle (local state + estimate, without its tolerance scales) on a "
+                      f"{K} x {ds} slab drawn on the CPU from the same recipe (same distributions and sketch, "
+                      f"not the GPU's bits): pinned to one core {t_one:.1f} s; {len(jobs)} worker processes, one "
+                      f"coordinate block each, {t_all:.1f} s"}
+
+
+def run_calibration(args):
+    """--lds-calibration / --stream-calibration: the rates of the chip the FDA kernels are compared with,
+    from the library's own calibration kernels.  Prints one JSON line."""
+    import torch
+
+    import paper_2405_20988_amd as F
+    F.load_library()
+    torch.cuda.set_device(0)
+    st = torch.cuda.current_stream().cuda_stream
+    sink = torch.zeros(4, dtype=torch.int32, device="cuda:0")
+    out = {}
+    if args.lds_calibration:
+        rates = {}
+        ghz = None
+        for op, opi in F.LDS_OPS.items():
+            for pat, pi in F.LDS_PATTERNS.items():
+                iters = 200 if op == "f32" else 2000
+                r, ghz = F.fda_calib_lds_atomics(opi, pi, iters, sink.data_ptr(), st)
+                rates[f"{op}/{pat}"] = round(r, 2)
+        out["lds_atomic_adds_per_lane_per_clk_per_cu"] = rates
+        out["clock_ghz"] = ghz
+        out["compute_units"] = torch.cuda.get_device_properties(0).multi_processor_count
+    if args.stream_calibration:
+        n = args.stream_calibration << 20
+        src = torch.full((n // 4,), 1.0, dtype=torch.float32, device="cuda:0")
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        ms_r = F.fda_calib_stream(0, src.data_ptr(), sink.data_ptr(), n, 5, st)
+        ms_w = F.fda_calib_stream(1, None, dst.data_ptr(), n, 5, st)
+        ms_c = F.fda_calib_stream(2, src.data_ptr(), dst.data_ptr(), n, 5, st)
+        out["stream_calibration"] = {"bytes": n, "read_GBps": round(n / ms_r / 1e6, 1),
+                                     "write_GBps": round(n / ms_w / 1e6, 1),
+                                     "copy_GBps_read_plus_written": round(2 * n / ms_c / 1e6, 1),
+                                     "read_ms": round(ms_r, 4), "write_ms": round(ms_w, 4),
+                                     "copy_ms": round(ms_c, 4)}
+    print(json.dumps(out))
 
 
 def main():
@@ -64,6 +179,11 @@ def main():
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MiB",
                     help="instead of the benchmark, run a plain device copy of this many MiB five "
                          "times (a kernel of known traffic, to scale rocprofv3's FETCH_SIZE / WRITE_SIZE)")
+    ap.add_argument("--lds-calibration", action="store_true",
+                    help="instead of the benchmark: LDS atomic-add rates of this chip (library calibration kernels)")
+    ap.add_argument("--stream-calibration", type=int, default=0, metavar="MiB",
+                    help="instead of the benchmark: read / fill / copy rates over this many MiB with 16-byte "
+                         "accesses (library calibration kernels)")
     ap.add_argument("--cpu-sample", type=int, default=6_000_000,
                     help="coordinates of the workload the CPU oracle is timed on")
     args = ap.parse_args()
@@ -71,6 +191,16 @@ def main():
         print("bench.py: this build runs on ONE GPU (K workers are simulated as a [K,d] slab on one "
               "device; there are no collectives). Run with --gpus 1.", file=sys.stderr)
         sys.exit(2)
+
+    over = {k: v for k, v in (("l", args.l), ("m", args.m)) if v is not None}
+    calibrating = args.copy_calibration or args.lds_calibration or args.stream_calibration
+    cpu = None
+    if not args.no_cpu_baseline and not calibrating:
+        # first, while nothing has touched the GPU yet (this leg forks worker processes)
+        cpu_over = dict(over)
+        if args.d is not None:
+            cpu_over["d"] = args.d
+        cpu = cpu_baseline(args.config, cpu_over, args.variants, args.cpu_sample)
 
     import numpy as np
     import torch
@@ -97,7 +227,10 @@ def main():
                           "launches": 5}))
         return
 
-    over = {k: v for k, v in (("l", args.l), ("m", args.m)) if v is not None}
+    if args.lds_calibration or args.stream_calibration:
+        run_calibration(args)
+        return
+
     wl = S.make(args.config, device=dev, seed=0, d=args.d, **over)
     K, d = wl.K, wl.d
     esz = 4 if wl.dtype == "f32" else 2
@@ -147,18 +280,25 @@ def main():
     workload = args.config if args.d is None else f"{args.config}-d{d}"
     if over:
         workload += f"-sketch{wl.l}x{wl.m}"
+    traffic, traffic_source = traffic_from_profile(workload if args.variants == 3 else f"{workload}_v{args.variants}")
     roofline = {"bound": "hbm", "kernel": "state_kernel", "achieved": round(achieved, 1),
                 "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
-                "traffic": traffic_from_profile(workload), "algorithmic_bytes": abytes,
+                "traffic": traffic, "traffic_source": traffic_source, "algorithmic_bytes": abytes,
                 "kernel_ms": round(kern_ms_avg, 4), "launches": launches}
     if args.variants & 2:
-        # what actually bounds this kernel: one LDS atomic add per (worker, sketch row, coordinate);
-        # the ceiling is the rate measured for returning 32-bit LDS atomics on random cells of this chip
+        # what actually bounds this kernel: one LDS atomic add per (worker, sketch row, coordinate).
+        # The ceiling is measured here, by the library's calibration kernel: returning 32-bit LDS
+        # atomic adds on random cells, per lane, clock (the device's reported rate) and compute unit.
         props = torch.cuda.get_device_properties(0)
+        sink = torch.zeros(4, dtype=torch.int32, device=dev)
+        ceiling, ghz = F.fda_calib_lds_atomics(F.LDS_OPS["u32_rtn"], F.LDS_PATTERNS["random"], 2000,
+                                               sink.data_ptr(), torch.cuda.current_stream().cuda_stream)
         adds = float(wl.l) * K * d
         roofline["lds_atomic_adds_per_clk_per_cu"] = round(
-            adds / (kern_ms_avg * 1e-3) / props.multi_processor_count / 2.4e9, 2)
-        roofline["lds_atomic_ceiling_per_clk_per_cu"] = 10.4
+            adds / (kern_ms_avg * 1e-3) / props.multi_processor_count / (ghz * 1e9), 2)
+        roofline["lds_atomic_ceiling_per_clk_per_cu"] = round(ceiling, 2)
+        roofline["lds_ceiling_source"] = "fda_calib_lds_atomics(u32_rtn, random), measured in this run"
+        roofline["clock_ghz"] = ghz
 
     # The same step with the average state computed directly (fda_mean_state: sketch of the mean
     # drift, by linearity) instead of the K per-worker states -- labelled separately, never `value`.
@@ -201,7 +341,8 @@ def main():
                  "unit": "worker-params/s", "kernel": "mean_state_kernel", "kernel_ms": round(mk, 4),
                  "achieved": round(abytes / (mk * 1e-3) / 1e9, 1), "peak": HBM_PEAK_GBS,
                  "frac": round(abytes / (mk * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
-                 "traffic": None if args.wbar else traffic_from_profile(workload, "mean_state_kernel"),
+                 "traffic": None if args.wbar else traffic_from_profile(workload, "mean_state_kernel")[0],
+                 "traffic_source": None if args.wbar else traffic_from_profile(workload, "mean_state_kernel")[1],
                  "h_sketch": est_m.h_sketch, "h_linear": est_m.h_linear}
 
     # forced synchronization + xi refresh, timed separately (it rewrites the slab, so last)
@@ -245,7 +386,20 @@ def main():
         amortized = {"sync_every_steps": period,
                      "ms_per_step_incl_syncs": round(ms_per_step + (sync_ms + xi_ms) / period, 4),
                      "mean_state_mode_ms_per_step_incl_syncs": round(mean_ms + (sync_ms + xi_ms) / period, 4)}
-    sync_info = {"amortized": amortized, "sync_from_mean_ms": round(fused_ms, 4),
+    # what this chip sustains for a plain copy with 16-byte accesses (read N, write N), the reference the
+    # synchronization kernels' mix of reads and writes is compared with: measured here
+    cal_n = min(K * d * esz, 2 << 30) // 16 * 16
+    cal_src = torch.zeros(cal_n, dtype=torch.uint8, device=dev)
+    cal_dst = torch.empty_like(cal_src)
+    torch.cuda.synchronize()
+    stream_now = torch.cuda.current_stream().cuda_stream
+    copy_ms = F.fda_calib_stream(2, cal_src.data_ptr(), cal_dst.data_ptr(), cal_n, 3, stream_now)
+    read_ms = F.fda_calib_stream(0, cal_src.data_ptr(), cal_dst.data_ptr(), cal_n, 3, stream_now)
+    del cal_src, cal_dst
+    sync_info = {"amortized": amortized,
+                 "copy_kernel_GBps": round(2 * cal_n / copy_ms / 1e6, 1),
+                 "read_kernel_GBps": round(cal_n / read_ms / 1e6, 1),
+                 "calibration": f"fda_calib_stream over {cal_n} bytes, measured in this run", "sync_from_mean_ms": round(fused_ms, 4),
                  "sync_from_mean_GBps": round(fused_bytes / fused_ms / 1e6, 1),
                  "sync_from_mean_algorithmic_bytes": fused_bytes,
                  "sync_ms": round(sync_ms, 4), "sync_GBps": round(sync_bytes / sync_ms / 1e6, 1),
@@ -273,22 +427,8 @@ def main():
         "sync": sync_info,
     }
 
-    if not args.no_cpu_baseline:
-        from oracle import fda_oracle as O
-        ds = min(args.cpu_sample, d)
-        # regenerate a small slab of the same recipe on the CPU for the sample (same distributions)
-        wls = S.make(args.config, device="cpu", seed=0, d=ds, **over)
-        w_host = S.slab_to_numpy(wls.w)
-        w0_host, xi_host = wls.w_t0.numpy(), wls.xi.numpy()
-        c0 = time.perf_counter()
-        st = O.local_state(w_host, wls.dtype, w0_host, xi_host if args.variants & 1 else None,
-                           wls.hash_coef if args.variants & 2 else None, wls.m)
-        O.estimate_variance(st["n"], st["p"], st["sk"], wls.eps, theta)
-        c1 = time.perf_counter()
-        out["cpu_baseline"] = {"value": K * ds / (c1 - c0), "unit": "worker-params/s", "cores": 1,
-                               "kind": "oracle",
-                               "sample": f"first-principles fp64 numpy oracle (state + estimate) on a "
-                                         f"{K} x {ds} slab of the same recipe, {c1 - c0:.1f} s"}
+    if cpu is not None:
+        out["cpu_baseline"] = cpu
     print(json.dumps(out))
     mon.close()
 

@@ -295,6 +295,31 @@ int fda_last_mean_state_path(fda_ctx* ctx, int32_t* path, void* stream);
 int fda_profile_enable(fda_ctx* ctx, int on);
 int fda_profile_read(fda_ctx* ctx, double* state_kernel_ms, int64_t* launches, int reset);
 
+/*
+ * Measurement aids (no part of the method): kernels of known HBM traffic and of known LDS work, so
+ * that the rates the FDA kernels are compared with are measured on the same device by the same
+ * library.  Both create two HIP events, run one untimed launch, time the rest and wait for `stream`.
+ *
+ * fda_calib_stream: a pass over `bytes` bytes (rounded down to whole 16-byte vectors, one vector per
+ * lane and access) repeated `reps` times;  mode 0 reads src (dst: DEVICE, 4 bytes, a sink that is
+ * practically never written),  mode 1 fills dst (src unused),  mode 2 copies src to dst (reads
+ * `bytes`, writes `bytes`).  src, dst: DEVICE, 16-byte aligned.  *ms_per_rep: HOST, written.
+ *
+ * fda_calib_lds_atomics: one workgroup of 512 threads per compute unit adds into 144 KiB of LDS cells,
+ * `iters` times eight atomic additions per lane to cell addresses fixed at the start.
+ *   op       0: 32-bit integer add returning the old value, 1: 32-bit integer add, 2: 64-bit integer
+ *            add, 3: fp64 add, 4: fp32 add
+ *   pattern  0: every lane its own random cell, 1: lane t on cell t (no conflicts), 2/3/4/5: groups of
+ *            4/8/16/32 lanes on consecutive cells of a random group
+ *   sink_dev DEVICE, 4 bytes (practically never written)
+ * *lane_ops_per_clock_per_cu: HOST, additions per lane, per clock of the device's reported clock rate,
+ * per compute unit;  *clock_ghz (may be NULL): that clock rate.
+ */
+int fda_calib_stream(int mode, const void* src, void* dst, size_t bytes, int reps, void* stream,
+                     double* ms_per_rep);
+int fda_calib_lds_atomics(int op, int pattern, int iters, void* sink_dev, void* stream,
+                          double* lane_ops_per_clock_per_cu, double* clock_ghz);
+
 #ifdef __cplusplus
 }
 #endif

@@ -159,11 +159,15 @@ def bucket_and_sign(coef_row, j: np.ndarray, m: int):
     return bucket, sign
 
 
-def ams_sketch(v: np.ndarray, coef: np.ndarray, m: int) -> np.ndarray:
-    """sk(v) in R^{l x m}: row i, cell b = sum over j with bucket_i(j) = b of sign_i(j) v_j."""
+def ams_sketch(v: np.ndarray, coef: np.ndarray, m: int, j0: int = 0) -> np.ndarray:
+    """sk(v) in R^{l x m}: row i, cell b = sum over j with bucket_i(j) = b of sign_i(j) v_j.
+
+    j0: the coordinate of v[0] (v is the slice [j0, j0 + len(v)) of a longer vector; the sketch of
+    the whole is the sum of the sketches of its slices, by linearity).
+    """
     v = np.asarray(v, np.float64)
     l = coef.shape[0]
-    j = np.arange(v.shape[0], dtype=np.uint64)
+    j = np.arange(j0, j0 + v.shape[0], dtype=np.uint64)
     sk = np.zeros((l, m), np.float64)
     for i in range(l):
         bucket, sign = bucket_and_sign(coef[i], j, m)
@@ -203,8 +207,11 @@ def m2_estimate(sk: np.ndarray) -> float:
 # --------------------------------------------------------------------------- #
 # local state of all K workers (Algorithm 1, line 6)
 # --------------------------------------------------------------------------- #
-def local_state(w, dtype: str, w_t0: np.ndarray, xi, coef, m: int, scales: bool = True):
+def local_state(w, dtype: str, w_t0: np.ndarray, xi, coef, m: int, scales: bool = True, j0: int = 0):
     """States of all K workers.
+
+    j0: the coordinate of column 0 (the inputs are the coordinates [j0, j0 + d) of longer vectors:
+    n, p and sk of the whole are the sums over such blocks).  Only with scales=False.
 
     scales=False leaves out the absolute-sum scales (p_abs, sk_abs, sk_cnt: only the tests'
     tolerances use them; the method itself is n, p and sk) -- the benchmark's CPU-baseline leg
@@ -231,14 +238,16 @@ def local_state(w, dtype: str, w_t0: np.ndarray, xi, coef, m: int, scales: bool 
             out["p_abs"] = abs_projections(u, x)
     if coef is not None:
         K = u.shape[0]
-        out["sk"] = np.stack([ams_sketch(u[k], coef, m) for k in range(K)])
+        if scales and j0 != 0:
+            raise ValueError("the tolerance scales are only computed for whole vectors")
+        out["sk"] = np.stack([ams_sketch(u[k], coef, m, j0) for k in range(K)])
         if scales:
             out["sk_abs"] = np.stack([ams_sketch_abs(u[k], coef, m) for k in range(K)])
             out["sk_cnt"] = ams_sketch_counts(u.shape[1], coef, m)
     return out
 
 
-def mean_state(w, dtype: str, w_t0: np.ndarray, xi, coef, m: int):
+def mean_state(w, dtype: str, w_t0: np.ndarray, xi, coef, m: int, scales: bool = True):
     """The average state of Algorithm 1, line 7, from the average drift.
 
     u_bar = (1/K) sum_k u_k;  the sketch and the inner product are linear (Section 3.1), so the
@@ -246,8 +255,8 @@ def mean_state(w, dtype: str, w_t0: np.ndarray, xi, coef, m: int):
     evaluates exactly that, sketching u_bar itself.  (That it equals the average of
     local_state's per-worker outputs is one of the pinned identities.)
 
-    Returns a dict with n (float), p (float or None), sk[l,m] (or None) and the scales the
-    tolerances use: p_abs = mean_k sum_j |xi_j u_kj|, sk_abs[l,m] = mean_k per-cell sum of
+    Returns a dict with n (float), p (float or None), sk[l,m] (or None) and (unless scales=False) the
+    scales the tolerances use: p_abs = mean_k sum_j |xi_j u_kj|, sk_abs[l,m] = mean_k per-cell sum of
     |u_kj|, sk_cnt[l,m], u_mean_abs = mean over k, j of |u_kj|.
     """
     w64 = widen(w, dtype)
@@ -260,11 +269,13 @@ def mean_state(w, dtype: str, w_t0: np.ndarray, xi, coef, m: int):
     if xi is not None:
         x = np.asarray(xi, np.float32).astype(np.float64)
         out["p"] = float(u_bar @ x)
-        out["p_abs"] = float(abs_projections(u, x).sum() / K)
+        if scales:
+            out["p_abs"] = float(abs_projections(u, x).sum() / K)
     if coef is not None:
         out["sk"] = ams_sketch(u_bar, coef, m)
-        out["sk_abs"] = ams_sketch_abs(np.abs(u).sum(axis=0) / K, coef, m)
-        out["sk_cnt"] = ams_sketch_counts(u.shape[1], coef, m)
+        if scales:
+            out["sk_abs"] = ams_sketch_abs(np.abs(u).sum(axis=0) / K, coef, m)
+            out["sk_cnt"] = ams_sketch_counts(u.shape[1], coef, m)
     return out
 
 

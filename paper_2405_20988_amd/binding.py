@@ -104,7 +104,10 @@ def load_library():
     lib.fda_last_state_path.argtypes = [vp, C.POINTER(C.c_int32), vp]
     lib.fda_profile_enable.argtypes = [vp, C.c_int]
     lib.fda_profile_read.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(C.c_int64), C.c_int]
-    for name in ("fda_step", "fda_sync_from_mean", "fda_mean_state", "fda_estimate_variance_mean", "fda_last_mean_state_path",
+    lib.fda_calib_stream.argtypes = [C.c_int, vp, vp, C.c_size_t, C.c_int, vp, C.POINTER(C.c_double)]
+    lib.fda_calib_lds_atomics.argtypes = [C.c_int, C.c_int, C.c_int, vp, vp, C.POINTER(C.c_double),
+                                          C.POINTER(C.c_double)]
+    for name in ("fda_calib_stream", "fda_calib_lds_atomics", "fda_step", "fda_sync_from_mean", "fda_mean_state", "fda_estimate_variance_mean", "fda_last_mean_state_path",
                  "fda_last_state_path", "fda_profile_enable", "fda_profile_read", "fda_plan", "fda_workspace_bytes", "fda_create", "fda_destroy",
                  "fda_state_floats", "fda_get_plan", "fda_local_state",
                  "fda_estimate_variance", "fda_sync", "fda_update_xi"):
@@ -258,3 +261,23 @@ def fda_last_mean_state_path(ctx: int, stream: int = 0) -> int:
     v = C.c_int32(0)
     _check(load_library().fda_last_mean_state_path(ctx, C.byref(v), stream), "fda_last_mean_state_path")
     return int(v.value)
+
+
+CALIB_READ, CALIB_WRITE, CALIB_COPY = 0, 1, 2
+LDS_OPS = {"u32_rtn": 0, "u32": 1, "u64": 2, "f64": 3, "f32": 4}
+LDS_PATTERNS = {"random": 0, "consecutive": 1, "groups4": 2, "groups8": 3, "groups16": 4, "groups32": 5}
+
+
+def fda_calib_stream(mode: int, src: int | None, dst: int, nbytes: int, reps: int = 5, stream: int = 0) -> float:
+    """Milliseconds per pass of a read (0), fill (1) or copy (2) kernel over nbytes (measurement aid)."""
+    ms = C.c_double(0.0)
+    _check(load_library().fda_calib_stream(mode, src, dst, nbytes, reps, stream, C.byref(ms)), "fda_calib_stream")
+    return float(ms.value)
+
+
+def fda_calib_lds_atomics(op: int, pattern: int, iters: int, sink: int, stream: int = 0):
+    """(LDS atomic additions per lane, clock and compute unit; clock in GHz) of the calibration kernel."""
+    rate, ghz = C.c_double(0.0), C.c_double(0.0)
+    _check(load_library().fda_calib_lds_atomics(op, pattern, iters, sink, stream, C.byref(rate), C.byref(ghz)),
+           "fda_calib_lds_atomics")
+    return float(rate.value), float(ghz.value)

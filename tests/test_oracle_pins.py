@@ -246,6 +246,31 @@ def test_sketch_linearity_and_column_sums():
     assert (np.abs(sks[0]) <= O.ams_sketch_abs(u[0], coef, m) + 1e-18).all()
 
 
+def test_sketch_of_coordinate_blocks_adds_up():
+    """A slice of a vector sketched at its own coordinates (j0): the slices add up to the whole, and
+    a slice equals the sketch of the vector with everything else zeroed."""
+    rng = np.random.default_rng(20)
+    d, l, m, K = 1000, 3, 31, 2
+    coef = rand_coef(rng, l)
+    v = rng.normal(size=d)
+    cuts = [0, 1, 333, 334, 900, d]
+    parts = [O.ams_sketch(v[a:b], coef, m, j0=a) for a, b in zip(cuts[:-1], cuts[1:])]
+    assert np.allclose(sum(parts), O.ams_sketch(v, coef, m), rtol=0, atol=1e-13)
+    z = np.zeros(d)
+    z[333:334] = v[333:334]
+    assert np.array_equal(parts[2], O.ams_sketch(z, coef, m))
+    w0 = rng.normal(size=d).astype(np.float32)
+    w = (w0 + rng.normal(size=(K, d)) * 1e-2).astype(np.float32)
+    xi = rng.normal(size=d).astype(np.float32)
+    whole = O.local_state(w, "f32", w0, xi, coef, m)
+    blocks = [O.local_state(w[:, a:b], "f32", w0[a:b], xi[a:b], coef, m, scales=False, j0=a)
+              for a, b in zip(cuts[:-1], cuts[1:])]
+    for key in ("n", "p", "sk"):
+        assert np.allclose(sum(b[key] for b in blocks), whole[key], rtol=1e-12, atol=1e-15), key
+    with pytest.raises(ValueError):
+        O.local_state(w[:, 5:], "f32", w0[5:], xi[5:], coef, m, j0=5)
+
+
 def test_sketch_pure_python_brute_force():
     rng = np.random.default_rng(7)
     d, l, m = 40, 3, 7
@@ -532,3 +557,23 @@ def test_exact_rational_cross_check_of_h():
     st = O.local_state(w.astype(np.float32), "f32", w0.astype(np.float32), xi_int.astype(np.float32), None, 0)
     pbar = sum(sum(int(xi_int[j]) * u[k][j] for j in range(d)) for k in range(K)) / K
     assert O.h_linear(st["n"], st["p"]) == pytest.approx(float(nbar - pbar * pbar), rel=1e-13, abs=1e-13)
+
+
+def test_fullsize_helpers_equal_the_oracle_sketch(tmp_path):
+    """tests/fullsize_oracle.py (hash every row once, then bincount) against O.ams_sketch itself, and
+    its child-process hashing against the in-process one."""
+    import fullsize_oracle as FO
+    rng = np.random.default_rng(21)
+    d, l, m = 2_500_003, 3, 250
+    coef = rand_coef(rng, l)
+    v = rng.standard_t(3, size=d)
+    hashed = FO.hash_rows(coef, range(l), d, m, threads=4)
+    want = O.ams_sketch(v, coef, m)
+    for i in range(l):
+        assert np.allclose(FO.sketch_row(v, hashed[i], m), want[i], rtol=0, atol=1e-12 * np.abs(v).sum() / m)
+        assert np.allclose(FO.sketch_row_blocks(v, hashed[i], m, threads=4), want[i], rtol=0,
+                           atol=1e-12 * np.abs(v).sum() / m)
+    assert np.array_equal(np.stack([FO.cell_counts(hashed[i], m) for i in range(l)]), O.ams_sketch_counts(d, coef, m))
+    kids = FO.start_hash_processes(coef, [1], d, m, str(tmp_path))
+    files = FO.finish_hash_processes(kids, str(tmp_path))
+    assert np.array_equal(files[1][0], hashed[1][0]) and np.array_equal(files[1][1], hashed[1][1])
