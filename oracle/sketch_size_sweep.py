@@ -7,11 +7,15 @@ relative error of M2(sk(v)) against ||v||^2 depends on (l, m): for every size it
 of |M2 / ||v||^2 - 1| and how often the over-estimate  H = n - M2/(1+eps) >= n - ||v||^2  of
 Theorem 1 fails for eps = 0.06 * sqrt(250 / m)  (the m = O(1/eps^2) scaling of the paper's point).
 
-    python -m oracle.sketch_size_sweep [--d 20000] [--trials 400] [--tail gauss|t3]
+    python -m oracle.sketch_size_sweep [--d 20000] [--trials 400] [--tail gauss|t3] [--json FILE]
+
+tests/golden/sketch_size_sweep.json is this script's output for --trials 300 --json (it calls nothing
+but the oracle).
 """
 from __future__ import annotations
 
 import argparse
+import json
 
 import numpy as np
 
@@ -27,20 +31,43 @@ def main():
     ap.add_argument("--d", type=int, default=20000)
     ap.add_argument("--trials", type=int, default=400)
     ap.add_argument("--tail", choices=("gauss", "t3"), default="gauss")
+    ap.add_argument("--json", default=None, help="also write the table to this file")
     args = ap.parse_args()
-    rng = np.random.default_rng(2405_20988)
-    print(f"d={args.d} trials={args.trials} drift={args.tail}")
-    print(" l     m    eps(m)   q50      q95      q99     P[Thm 1 bound fails]")
-    for l, m in SIZES:
+    rows = sweep(args.d, args.trials, args.tail, SIZES, verbose=True)
+    if args.json:
+        with open(args.json, "w") as f:
+            json.dump({"_citation": "Section 3.3, 'Choice of l and m' (the paper gives the one point l x m = 5 x 250, "
+                                    "eps about 6 %, confidence about 95 %, and skips the sweep); Section 3.1, "
+                                    "m = O(1/eps^2).  Written by `python -m oracle.sketch_size_sweep --trials "
+                                    f"{args.trials} --json` (oracle only).",
+                       "d": args.d, "trials": args.trials, "drift": args.tail, "seed": SEED, "rows": rows}, f, indent=1)
+            f.write("\n")
+
+
+SEED = 2405_20988
+
+
+def sweep(d, trials, tail, sizes, verbose=False):
+    """One row per (l, m): quantiles of |M2 / ||v||^2 - 1| over `trials` vectors and hash draws."""
+    rng = np.random.default_rng(SEED)
+    if verbose:
+        print(f"d={d} trials={trials} drift={tail}")
+        print(" l     m    eps(m)   q50      q95      q99     P[Thm 1 bound fails]")
+    rows = []
+    for l, m in sizes:
         eps = 0.06 * np.sqrt(250.0 / m)
-        rel = np.empty(args.trials)
-        for t in range(args.trials):
+        rel = np.empty(trials)
+        for t in range(trials):
             coef = rng.integers(0, P, size=(l, 2, 4), dtype=np.int64).astype(np.uint32)
-            v = rng.normal(size=args.d) if args.tail == "gauss" else rng.standard_t(3, size=args.d)
+            v = rng.normal(size=d) if tail == "gauss" else rng.standard_t(3, size=d)
             rel[t] = O.m2_estimate(O.ams_sketch(v, coef, m)) / float(v @ v) - 1.0
         q = np.quantile(np.abs(rel), [0.5, 0.95, 0.99])
         fails = float(np.mean(1.0 + rel > 1.0 + eps))          # M2/(1+eps) > ||v||^2
-        print(f"{l:2d} {m:5d}   {eps:.4f}   {q[0]:.4f}   {q[1]:.4f}   {q[2]:.4f}   {fails:.3f}")
+        rows.append({"l": l, "m": m, "eps": round(float(eps), 6), "q50": round(float(q[0]), 5),
+                     "q95": round(float(q[1]), 5), "q99": round(float(q[2]), 5), "bound_fails": round(fails, 4)})
+        if verbose:
+            print(f"{l:2d} {m:5d}   {eps:.4f}   {q[0]:.4f}   {q[1]:.4f}   {q[2]:.4f}   {fails:.3f}")
+    return rows
 
 
 if __name__ == "__main__":

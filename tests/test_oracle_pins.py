@@ -577,3 +577,24 @@ def test_fullsize_helpers_equal_the_oracle_sketch(tmp_path):
     kids = FO.start_hash_processes(coef, [1], d, m, str(tmp_path))
     files = FO.finish_hash_processes(kids, str(tmp_path))
     assert np.array_equal(files[1][0], hashed[1][0]) and np.array_equal(files[1][1], hashed[1][1])
+
+
+def test_sketch_size_sweep():
+    """Section 3.1: the sketch width scales as m = O(1/eps^2), so the error of M2 falls by about
+    sqrt(2) per doubling of m.  Checked on the committed sweep (300 trials per size, written by
+    oracle/sketch_size_sweep.py) and on a fresh, smaller one."""
+    from oracle import sketch_size_sweep as SW
+    g = gold("sketch_size_sweep.json")
+    by = {(r["l"], r["m"]): r for r in g["rows"]}
+    assert g["trials"] == 300 and {(5, 125), (5, 250), (5, 500), (5, 1000), (5, 2000)} <= set(by)
+    for a, b in ((125, 250), (250, 500), (500, 1000), (1000, 2000)):
+        for q in ("q50", "q95"):
+            assert 1.15 <= by[(5, a)][q] / by[(5, b)][q] <= 1.75, (a, b, q)
+    assert 3.2 <= by[(5, 125)]["q50"] / by[(5, 2000)]["q50"] <= 5.0            # four doublings: sqrt(2)^4 = 4
+    # the paper's point: 5 x 250 keeps the median error near 3 % and 95 % of the errors below about 9 %
+    assert by[(5, 250)]["q50"] < 0.06 < by[(5, 250)]["q95"] < 0.12
+    # more rows trim the tail
+    assert by[(9, 250)]["q99"] < by[(5, 250)]["q99"] < by[(1, 250)]["q99"]
+    rows = SW.sweep(4000, 100, "gauss", [(5, 125), (5, 500), (5, 2000)])
+    r = [row["q50"] for row in rows]
+    assert 1.4 <= r[0] / r[1] <= 2.9 and 1.4 <= r[1] / r[2] <= 2.9                # two doublings each: about 2
