@@ -212,6 +212,25 @@ int fda_estimate_variance_mean(fda_ctx* ctx, const float* mean_state, double the
                                fda_estimate* out_dev, fda_estimate* out_host, void* stream);
 
 /*
+ * fda_estimate_variance for callers that cannot allocate and hold no context: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same kernel and same result as
+ * fda_estimate_variance (out_dev is written bit for bit the same), but the per-workgroup partial sums
+ * and the finished-workgroup counter live in a static device array of the library (17 KiB per GPU,
+ * held until the process ends) instead of a context's workspace.  Calls no hipMalloc / hipFree and no
+ * allocating library routine, creates no events, never waits; enqueues a one-workgroup fill kernel
+ * (the counter) and the estimate kernel on `stream`.
+ *   state     DEVICE [K][S] fp32, S = 2 + l*m with FDA_VARIANT_SKETCH, else 2 (l, m then ignored)
+ *   K >= 1;  l in 1..FDA_MAX_SKETCH_ROWS and m in 1..FDA_STATIC_MAX_M: larger is FDA_ERANGE
+ *   variants, eps, theta, tie_tol, out_dev as in fda_create / fda_estimate_variance
+ * All calls on one GPU share that GPU's array: calls that overlap on one GPU (two streams, two
+ * threads) race; order them.  (K = 1 with a mean state gives fda_estimate_variance_mean.)
+ */
+#define FDA_STATIC_MAX_M 32767
+int fda_estimate_variance_static(const float* state, int32_t K, int32_t l, int32_t m, int32_t variants,
+                                 double eps, double theta, double tie_tol, fda_estimate* out_dev,
+                                 void* stream);
+
+/*
  * Algorithm 1, line 9 ("In-place"): every row of the slab becomes the average model.
  *   w        DEVICE slab, rewritten: row k <- (1/K) sum_k' row k'  (fp32 sum in worker
  *            order, divided by K; bf16 slabs store its round-to-nearest-even)

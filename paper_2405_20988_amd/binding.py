@@ -107,7 +107,9 @@ def load_library():
     lib.fda_calib_stream.argtypes = [C.c_int, vp, vp, C.c_size_t, C.c_int, vp, C.POINTER(C.c_double)]
     lib.fda_calib_lds_atomics.argtypes = [C.c_int, C.c_int, C.c_int, vp, vp, C.POINTER(C.c_double),
                                           C.POINTER(C.c_double)]
-    for name in ("fda_calib_stream", "fda_calib_lds_atomics", "fda_step", "fda_sync_from_mean", "fda_mean_state", "fda_estimate_variance_mean", "fda_last_mean_state_path",
+    lib.fda_estimate_variance_static.argtypes = [vp, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_double,
+                                                 C.c_double, C.c_double, vp, vp]
+    for name in ("fda_estimate_variance_static", "fda_calib_stream", "fda_calib_lds_atomics", "fda_step", "fda_sync_from_mean", "fda_mean_state", "fda_estimate_variance_mean", "fda_last_mean_state_path",
                  "fda_last_state_path", "fda_profile_enable", "fda_profile_read", "fda_plan", "fda_workspace_bytes", "fda_create", "fda_destroy",
                  "fda_state_floats", "fda_get_plan", "fda_local_state",
                  "fda_estimate_variance", "fda_sync", "fda_update_xi"):
@@ -190,6 +192,13 @@ def fda_estimate_variance(ctx: int, state: int, theta: float, tie_tol: float, ou
                                                 C.byref(host) if want_host else None, stream),
            "fda_estimate_variance")
     return host
+
+
+def fda_estimate_variance_static(state: int, K: int, l: int, m: int, variants: int, eps: float, theta: float,
+                                 tie_tol: float, out_dev: int, stream: int = 0) -> None:
+    """fda_estimate_variance without a context: its scratch is a static device array of the library."""
+    _check(load_library().fda_estimate_variance_static(state, K, l, m, variants, eps, theta, tie_tol, out_dev,
+                                                       stream), "fda_estimate_variance_static")
 
 
 def fda_mean_state(ctx: int, w: int, w_t0: int, xi: int | None, mean_state: int,

@@ -6,12 +6,23 @@
 #include <cstddef>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <new>
 
 #include "fda.h"
 #include "fda_small_kernels.hpp"
 #include "fda_state_launch.hpp"
 #include "fda_mean_launch.hpp"
+
+// Scratch of fda_estimate_variance_static: the per-workgroup partial sums of estimate_kernel
+// (2 + FDA_MAX_SKETCH_ROWS * 128 doubles) and, 256-aligned behind them, its finished-workgroup
+// counter.  Every GPU the library runs on holds its own copy until the process ends.  In host code
+// this name is only a handle for hipGetSymbolAddress: the address kernels are given is the one
+// static_scratch() looked up for the current device.
+constexpr size_t kStaticPartDoubles = 2 + (size_t)FDA_MAX_SKETCH_ROWS * 128;
+constexpr size_t kStaticTicketOffset = (kStaticPartDoubles * 8 + 255) / 256 * 256;
+constexpr size_t kStaticScratchBytes = kStaticTicketOffset + 256;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
 
 namespace {
 
@@ -316,6 +327,27 @@ int dispatch_mean(int dtype, int cell, const MeanSplit& ms, const fda::MeanParam
 }
 
 constexpr int kProfSlots = 64;
+
+// Device address of `scratch` on the current device, looked up once per device (with that device
+// current) and kept: each GPU has its own copy of the array at its own address.
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+unsigned char* g_scratch_ptr[kMaxDevices] = {};
+
+int static_scratch(unsigned char** out) {
+  int dev = -1;
+  FDA_HIP(hipGetDevice(&dev));
+  if (dev < 0 || dev >= kMaxDevices) return fail(FDA_ERANGE, "device ordinal %d is beyond %d", dev, kMaxDevices - 1);
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (g_scratch_ptr[dev] == nullptr) {
+    void* p = nullptr;
+    FDA_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+    if (p == nullptr) return fail(FDA_EHIP, "hipGetSymbolAddress returned a null address");
+    g_scratch_ptr[dev] = static_cast<unsigned char*>(p);
+  }
+  *out = g_scratch_ptr[dev];
+  return FDA_OK;
+}
 
 }  // namespace
 
@@ -773,6 +805,43 @@ int fda_estimate_variance(fda_ctx* ctx, const float* state, double theta, double
 int fda_estimate_variance_mean(fda_ctx* ctx, const float* mean_state, double theta, double tie_tol,
                                fda_estimate* out_dev, fda_estimate* out_host, void* stream) {
   return estimate_rows(ctx, mean_state, 1, theta, tie_tol, out_dev, out_host, stream);
+}
+
+int fda_estimate_variance_static(const float* state, int32_t K, int32_t l, int32_t m, int32_t variants,
+                                 double eps, double theta, double tie_tol, fda_estimate* out_dev,
+                                 void* stream) {
+  if (state == nullptr || out_dev == nullptr) return fail(FDA_EINVAL, "NULL argument");
+  if (reinterpret_cast<uintptr_t>(state) % 4 != 0 || reinterpret_cast<uintptr_t>(out_dev) % 8 != 0)
+    return fail(FDA_EINVAL, "state must be 4-byte and out_dev 8-byte aligned");
+  if (K < 1) return fail(FDA_EINVAL, "K must be >= 1 (got %d)", K);
+  if ((variants & ~(FDA_VARIANT_LINEAR | FDA_VARIANT_SKETCH)) != 0 || variants == 0)
+    return fail(FDA_EINVAL, "variants must be a non-empty mask of FDA_VARIANT_LINEAR | FDA_VARIANT_SKETCH");
+  if (!(tie_tol >= 0.0)) return fail(FDA_EINVAL, "tie_tol must be >= 0");
+  const bool sk = (variants & FDA_VARIANT_SKETCH) != 0;
+  if (sk) {
+    if (l < 1 || l > FDA_MAX_SKETCH_ROWS)
+      return fail(FDA_ERANGE, "l must be in 1..%d (got %d): the static scratch holds no more rows", FDA_MAX_SKETCH_ROWS, l);
+    if (m < 1 || m > FDA_STATIC_MAX_M)
+      return fail(FDA_ERANGE, "m must be in 1..%d (got %d): the static scratch holds no wider rows", FDA_STATIC_MAX_M, m);
+    if (!(eps > -1.0)) return fail(FDA_EINVAL, "eps must be > -1");
+  }
+  const int bpr = sk ? (m + fda::kEstCols - 1) / fda::kEstCols : 1;
+  const int eblocks = sk ? l * bpr : 1;
+  if ((size_t)(2 + eblocks) > kStaticPartDoubles)
+    return fail(FDA_ERANGE, "internal: %d partial sums do not fit the static scratch", 2 + eblocks);
+  unsigned char* base = nullptr;
+  int rc = static_scratch(&base);
+  if (rc != FDA_OK) return rc;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  unsigned int* ticket = reinterpret_cast<unsigned int*>(base + kStaticTicketOffset);
+  // the counter must start at zero whatever an earlier call left (a fill kernel, not a memset node)
+  hipLaunchKernelGGL(fda::clear_u32_kernel, dim3(1), dim3(64), 0, st, ticket, 1);
+  FDA_HIP(hipGetLastError());
+  hipLaunchKernelGGL(fda::estimate_kernel, dim3(eblocks), dim3(fda::kSmallThreads), 0, st, state, K,
+                     sk ? l : 0, sk ? m : 1, variants, eps, theta, tie_tol,
+                     reinterpret_cast<double*>(base), ticket, out_dev);
+  FDA_HIP(hipGetLastError());
+  return FDA_OK;
 }
 
 int fda_sync(fda_ctx* ctx, void* w, float* w_t0, float* w_prev, const int32_t* pred_dev,
