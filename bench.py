@@ -150,14 +150,16 @@ def run_calibration(args):
         src = torch.full((n // 4,), 1.0, dtype=torch.float32, device="cuda:0")
         dst = torch.empty_like(src)
         torch.cuda.synchronize()
-        ms_r = F.fda_calib_stream(0, src.data_ptr(), sink.data_ptr(), n, 5, st)
-        ms_w = F.fda_calib_stream(1, None, dst.data_ptr(), n, 5, st)
-        ms_c = F.fda_calib_stream(2, src.data_ptr(), dst.data_ptr(), n, 5, st)
-        out["stream_calibration"] = {"bytes": n, "read_GBps": round(n / ms_r / 1e6, 1),
-                                     "write_GBps": round(n / ms_w / 1e6, 1),
-                                     "copy_GBps_read_plus_written": round(2 * n / ms_c / 1e6, 1),
-                                     "read_ms": round(ms_r, 4), "write_ms": round(ms_w, 4),
-                                     "copy_ms": round(ms_c, 4)}
+        cal = {"bytes": n}
+        for hint, add in (("", 0), ("_nontemporal", 4)):
+            ms_r = F.fda_calib_stream(0 + add, src.data_ptr(), sink.data_ptr(), n, 5, st)
+            ms_w = F.fda_calib_stream(1 + add, None, dst.data_ptr(), n, 5, st)
+            ms_c = F.fda_calib_stream(2 + add, src.data_ptr(), dst.data_ptr(), n, 5, st)
+            cal.update({f"read{hint}_GBps": round(n / ms_r / 1e6, 1), f"fill{hint}_GBps": round(n / ms_w / 1e6, 1),
+                        f"copy{hint}_GBps_read_plus_written": round(2 * n / ms_c / 1e6, 1),
+                        f"read{hint}_ms": round(ms_r, 4), f"fill{hint}_ms": round(ms_w, 4),
+                        f"copy{hint}_ms": round(ms_c, 4)})
+        out["stream_calibration"] = cal
     print(json.dumps(out))
 
 
@@ -393,13 +395,13 @@ def main():
     cal_dst = torch.empty_like(cal_src)
     torch.cuda.synchronize()
     stream_now = torch.cuda.current_stream().cuda_stream
-    copy_ms = F.fda_calib_stream(2, cal_src.data_ptr(), cal_dst.data_ptr(), cal_n, 3, stream_now)
-    read_ms = F.fda_calib_stream(0, cal_src.data_ptr(), cal_dst.data_ptr(), cal_n, 3, stream_now)
+    copy_ms = F.fda_calib_stream(6, cal_src.data_ptr(), cal_dst.data_ptr(), cal_n, 3, stream_now)
+    read_ms = F.fda_calib_stream(4, cal_src.data_ptr(), cal_dst.data_ptr(), cal_n, 3, stream_now)
     del cal_src, cal_dst
     sync_info = {"amortized": amortized,
                  "copy_kernel_GBps": round(2 * cal_n / copy_ms / 1e6, 1),
                  "read_kernel_GBps": round(cal_n / read_ms / 1e6, 1),
-                 "calibration": f"fda_calib_stream over {cal_n} bytes, measured in this run", "sync_from_mean_ms": round(fused_ms, 4),
+                 "calibration": f"fda_calib_stream (nontemporal copy / read) over {cal_n} bytes, measured in this run", "sync_from_mean_ms": round(fused_ms, 4),
                  "sync_from_mean_GBps": round(fused_bytes / fused_ms / 1e6, 1),
                  "sync_from_mean_algorithmic_bytes": fused_bytes,
                  "sync_ms": round(sync_ms, 4), "sync_GBps": round(sync_bytes / sync_ms / 1e6, 1),

@@ -320,9 +320,11 @@ int fda_profile_read(fda_ctx* ctx, double* state_kernel_ms, int64_t* launches, i
  * library.  Both create two HIP events, run one untimed launch, time the rest and wait for `stream`.
  *
  * fda_calib_stream: a pass over `bytes` bytes (rounded down to whole 16-byte vectors, one vector per
- * lane and access) repeated `reps` times;  mode 0 reads src (dst: DEVICE, 4 bytes, a sink that is
- * practically never written),  mode 1 fills dst (src unused),  mode 2 copies src to dst (reads
- * `bytes`, writes `bytes`).  src, dst: DEVICE, 16-byte aligned.  *ms_per_rep: HOST, written.
+ * lane and access, every workgroup on a contiguous range) repeated `reps` times;  mode 0 reads src
+ * (dst: DEVICE, 4 bytes, a sink that is practically never written),  mode 1 fills dst (src unused),
+ * mode 2 copies src to dst (reads `bytes`, writes `bytes`);  modes 4, 5, 6: the same with the
+ * nontemporal hint on every load and store.  src, dst: DEVICE, 16-byte aligned.  *ms_per_rep: HOST,
+ * written.
  *
  * fda_calib_lds_atomics: one workgroup of 512 threads per compute unit adds into 144 KiB of LDS cells,
  * `iters` times eight atomic additions per lane to cell addresses fixed at the start.

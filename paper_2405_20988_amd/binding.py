@@ -16,7 +16,8 @@ FDA_F32, FDA_BF16 = 0, 1
 FDA_VARIANT_LINEAR, FDA_VARIANT_SKETCH = 1, 2
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
-_LIB_PATH = os.path.join(_PKG, "lib", "libfda.so")
+# FDA_LIBRARY: load another build of the library instead of the in-tree one (experiments)
+_LIB_PATH = os.environ.get("FDA_LIBRARY") or os.path.join(_PKG, "lib", "libfda.so")
 _lib = None
 
 
@@ -272,13 +273,14 @@ def fda_last_mean_state_path(ctx: int, stream: int = 0) -> int:
     return int(v.value)
 
 
-CALIB_READ, CALIB_WRITE, CALIB_COPY = 0, 1, 2
+CALIB_READ, CALIB_WRITE, CALIB_COPY, CALIB_NONTEMPORAL = 0, 1, 2, 4
 LDS_OPS = {"u32_rtn": 0, "u32": 1, "u64": 2, "f64": 3, "f32": 4}
 LDS_PATTERNS = {"random": 0, "consecutive": 1, "groups4": 2, "groups8": 3, "groups16": 4, "groups32": 5}
 
 
 def fda_calib_stream(mode: int, src: int | None, dst: int, nbytes: int, reps: int = 5, stream: int = 0) -> float:
-    """Milliseconds per pass of a read (0), fill (1) or copy (2) kernel over nbytes (measurement aid)."""
+    """Milliseconds per pass of a read (0), fill (1) or copy (2) kernel over nbytes; +4: with the
+    nontemporal hint on loads and stores (measurement aid)."""
     ms = C.c_double(0.0)
     _check(load_library().fda_calib_stream(mode, src, dst, nbytes, reps, stream, C.byref(ms)), "fda_calib_stream")
     return float(ms.value)

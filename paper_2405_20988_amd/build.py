@@ -35,7 +35,9 @@ def hipcc() -> str:
 
 
 def flags() -> list[str]:
-    return ["-O3", "--offload-arch=gfx950", "-std=c++17", "-fPIC",
+    # FDA_EXTRA_HIPCC_FLAGS: extra compiler options, for experiments with the kernels' compile-time knobs
+    extra = os.environ.get("FDA_EXTRA_HIPCC_FLAGS", "").split()
+    return extra + ["-O3", "--offload-arch=gfx950", "-std=c++17", "-fPIC",
             # packed fp32 instructions are kept off for all device code
             "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
             "-I" + os.path.join(ROOT, "include"), "-I" + CSRC]

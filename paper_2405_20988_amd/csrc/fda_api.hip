@@ -53,6 +53,8 @@ constexpr int kMaxEstBlocksPerRow = 128;   // 32768 / 256: workgroups of estimat
 constexpr int kScaleSamples = 16384;       // sampled coordinates per worker for the scale
 constexpr int kScaleBlocks = kScaleSamples * fda::kScaleMaxSlices / fda::kSmallThreads;   // its workgroups, at most
 constexpr int kXiBlocks = 4096;
+constexpr long long kSyncVectorsPerBlock = 4 * fda::kSmallThreads;   // four trips per workgroup
+constexpr long long kStreamBytes = 512ll << 20;   // slabs beyond this are synchronized with streaming hints
 constexpr int64_t kAlign = 256;
 
 int64_t round_up(int64_t x, int64_t a) { return (x + a - 1) / a * a; }
@@ -856,19 +858,17 @@ int fda_sync(fda_ctx* ctx, void* w, float* w_t0, float* w_prev, const int32_t* p
     return fail(FDA_EINVAL, "pointer not aligned to its element type");
   hipStream_t st = static_cast<hipStream_t>(stream);
   const int vec_ok = kVecOk;
-  const int V = ctx->plan.vec;
+  const int V = fda::kSyncV;
   const long long nvec = (d.d + V - 1) / V;
-  long long blocks = (nvec + fda::kSmallThreads - 1) / fda::kSmallThreads;
-  const long long cap = (long long)ctx->cus * 16;
-  if (blocks > cap) blocks = cap;
-  if (d.dtype == FDA_F32)
-    hipLaunchKernelGGL(fda::sync_kernel<float>, dim3((unsigned)blocks), dim3(fda::kSmallThreads), 0, st,
-                       static_cast<float*>(w), w_t0, w_prev, pred_dev, d.K, (long long)d.d,
-                       (long long)d.row_stride, vec_ok);
-  else
-    hipLaunchKernelGGL(fda::sync_kernel<fda::bf16_t>, dim3((unsigned)blocks), dim3(fda::kSmallThreads), 0,
-                       st, static_cast<fda::bf16_t*>(w), w_t0, w_prev, pred_dev, d.K, (long long)d.d,
-                       (long long)d.row_stride, vec_ok);
+  const long long blocks = (nvec + kSyncVectorsPerBlock - 1) / kSyncVectorsPerBlock;
+  const bool hinted = (long long)d.K * d.d * (d.dtype == FDA_F32 ? 4 : 2) > kStreamBytes;
+  const dim3 grid((unsigned)blocks), block(fda::kSmallThreads);
+#define FDA_SYNC_LAUNCH(T, S)                                                                          \
+  hipLaunchKernelGGL((fda::sync_kernel<T, S>), grid, block, 0, st, static_cast<T*>(w), w_t0, w_prev,   \
+                     pred_dev, d.K, (long long)d.d, (long long)d.row_stride, vec_ok)
+  if (d.dtype == FDA_F32) { if (hinted) FDA_SYNC_LAUNCH(float, true); else FDA_SYNC_LAUNCH(float, false); }
+  else { if (hinted) FDA_SYNC_LAUNCH(fda::bf16_t, true); else FDA_SYNC_LAUNCH(fda::bf16_t, false); }
+#undef FDA_SYNC_LAUNCH
   FDA_HIP(hipGetLastError());
   return FDA_OK;
 }
@@ -887,20 +887,18 @@ int fda_sync_from_mean(fda_ctx* ctx, void* w, float* w_t0, float* w_prev, float*
     return fail(FDA_EINVAL, "pointer not aligned to its element type");
   hipStream_t st = static_cast<hipStream_t>(stream);
   const int vec_ok = kVecOk;
-  const int V = ctx->plan.vec;
+  const int V = fda::kSyncV;
   const long long nvec = (d.d + V - 1) / V;
-  long long blocks = (nvec + fda::kSmallThreads - 1) / fda::kSmallThreads;
-  const long long cap = (long long)ctx->cus * 16;
-  if (blocks > cap) blocks = cap;
+  const long long blocks = (nvec + kSyncVectorsPerBlock - 1) / kSyncVectorsPerBlock;
+  const bool hinted = (long long)d.K * d.d * (d.dtype == FDA_F32 ? 4 : 2) > kStreamBytes;
+  const dim3 grid((unsigned)blocks), block(fda::kSmallThreads);
   const double* dnorm = reinterpret_cast<const double*>(ctx->ws + ctx->plan.off_dnorm);
-  if (d.dtype == FDA_F32)
-    hipLaunchKernelGGL(fda::sync_from_mean_kernel<float>, dim3((unsigned)blocks), dim3(fda::kSmallThreads),
-                       0, st, static_cast<float*>(w), w_t0, w_prev, xi, w_bar, dnorm, pred_dev, d.K,
-                       (long long)d.d, (long long)d.row_stride, vec_ok);
-  else
-    hipLaunchKernelGGL(fda::sync_from_mean_kernel<fda::bf16_t>, dim3((unsigned)blocks),
-                       dim3(fda::kSmallThreads), 0, st, static_cast<fda::bf16_t*>(w), w_t0, w_prev, xi,
-                       w_bar, dnorm, pred_dev, d.K, (long long)d.d, (long long)d.row_stride, vec_ok);
+#define FDA_SYNC_LAUNCH(T, S)                                                                          \
+  hipLaunchKernelGGL((fda::sync_from_mean_kernel<T, S>), grid, block, 0, st, static_cast<T*>(w), w_t0, \
+                     w_prev, xi, w_bar, dnorm, pred_dev, d.K, (long long)d.d, (long long)d.row_stride, vec_ok)
+  if (d.dtype == FDA_F32) { if (hinted) FDA_SYNC_LAUNCH(float, true); else FDA_SYNC_LAUNCH(float, false); }
+  else { if (hinted) FDA_SYNC_LAUNCH(fda::bf16_t, true); else FDA_SYNC_LAUNCH(fda::bf16_t, false); }
+#undef FDA_SYNC_LAUNCH
   FDA_HIP(hipGetLastError());
   return FDA_OK;
 }

@@ -16,37 +16,62 @@ constexpr int kLdsWords = 36864;            // 144 KiB of cells, the size class 
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
-// ---- streaming kernels: every access is one 16-byte vector per lane, four in flight per lane ----
+// ---- streaming kernels: one 16-byte vector per lane and access; workgroup b owns the contiguous range
+// [b * per, (b + 1) * per) of vectors and walks it 8 x 4 KiB per trip; NT: nontemporal hint ----
+template <bool NT>
+__device__ __forceinline__ u32x4 ld(const u32x4* p) {
+  if constexpr (NT) return __builtin_nontemporal_load(p);
+  else return *p;
+}
+template <bool NT>
+__device__ __forceinline__ void st(u32x4* p, u32x4 v) {
+  if constexpr (NT) __builtin_nontemporal_store(v, p);
+  else *p = v;
+}
+constexpr int kUnroll = 8;
+
+template <bool NT>
 __global__ void __launch_bounds__(kThreads)
 calib_read_kernel(const u32x4* __restrict__ src, long long nvec, uint32_t* __restrict__ sink) {
-  const long long step = (long long)gridDim.x * kThreads;
-  long long i = (long long)blockIdx.x * kThreads + threadIdx.x;
+  const long long per = (nvec + gridDim.x - 1) / gridDim.x;
+  const long long beg = (long long)blockIdx.x * per, end = beg + per < nvec ? beg + per : nvec;
+  long long i = beg + threadIdx.x;
   u32x4 acc = {0u, 0u, 0u, 0u};
-  for (; i + 3 * step < nvec; i += 4 * step) {
-    const u32x4 a = src[i], b = src[i + step], c = src[i + 2 * step], e = src[i + 3 * step];
-    acc ^= a ^ b ^ c ^ e;
+  for (; i + (kUnroll - 1) * kThreads < end; i += kUnroll * kThreads) {
+    u32x4 v[kUnroll];
+#pragma unroll
+    for (int q = 0; q < kUnroll; ++q) v[q] = ld<NT>(src + i + q * kThreads);
+#pragma unroll
+    for (int q = 0; q < kUnroll; ++q) acc ^= v[q];
   }
-  for (; i < nvec; i += step) acc ^= src[i];
+  for (; i < end; i += kThreads) acc ^= ld<NT>(src + i);
   const uint32_t folded = acc.x ^ acc.y ^ acc.z ^ acc.w;
   if (folded == 0x9e3779b9u) *sink = folded;           // keeps the loads alive; practically never taken
 }
 
+template <bool NT>
 __global__ void __launch_bounds__(kThreads)
 calib_write_kernel(u32x4* __restrict__ dst, long long nvec, uint32_t value) {
-  const long long step = (long long)gridDim.x * kThreads;
+  const long long per = (nvec + gridDim.x - 1) / gridDim.x;
+  const long long beg = (long long)blockIdx.x * per, end = beg + per < nvec ? beg + per : nvec;
   const u32x4 v = {value, value, value, value};
-  for (long long i = (long long)blockIdx.x * kThreads + threadIdx.x; i < nvec; i += step) dst[i] = v;
+  for (long long i = beg + threadIdx.x; i < end; i += kThreads) st<NT>(dst + i, v);
 }
 
+template <bool NT>
 __global__ void __launch_bounds__(kThreads)
 calib_copy_kernel(const u32x4* __restrict__ src, u32x4* __restrict__ dst, long long nvec) {
-  const long long step = (long long)gridDim.x * kThreads;
-  long long i = (long long)blockIdx.x * kThreads + threadIdx.x;
-  for (; i + 3 * step < nvec; i += 4 * step) {
-    const u32x4 a = src[i], b = src[i + step], c = src[i + 2 * step], e = src[i + 3 * step];
-    dst[i] = a; dst[i + step] = b; dst[i + 2 * step] = c; dst[i + 3 * step] = e;
+  const long long per = (nvec + gridDim.x - 1) / gridDim.x;
+  const long long beg = (long long)blockIdx.x * per, end = beg + per < nvec ? beg + per : nvec;
+  long long i = beg + threadIdx.x;
+  for (; i + (kUnroll - 1) * kThreads < end; i += kUnroll * kThreads) {
+    u32x4 v[kUnroll];
+#pragma unroll
+    for (int q = 0; q < kUnroll; ++q) v[q] = ld<NT>(src + i + q * kThreads);
+#pragma unroll
+    for (int q = 0; q < kUnroll; ++q) st<NT>(dst + i + q * kThreads, v[q]);
   }
-  for (; i < nvec; i += step) dst[i] = src[i];
+  for (; i < end; i += kThreads) st<NT>(dst + i, ld<NT>(src + i));
 }
 
 // ---- LDS atomic additions --------------------------------------------------------------------
@@ -135,7 +160,9 @@ extern "C" {
 
 int fda_calib_stream(int mode, const void* src, void* dst, size_t bytes, int reps, void* stream,
                      double* ms_per_rep) {
-  if (ms_per_rep == nullptr || reps < 1 || bytes < 16 || mode < 0 || mode > 2) return FDA_EINVAL;
+  if (ms_per_rep == nullptr || reps < 1 || bytes < 16 || mode < 0 || mode > 6 || mode == 3) return FDA_EINVAL;
+  const bool nt = mode >= 4;
+  mode &= 3;
   if ((mode != 1 && src == nullptr) || dst == nullptr) return FDA_EINVAL;
   if (reinterpret_cast<uintptr_t>(dst) % 16 != 0 || (src && reinterpret_cast<uintptr_t>(src) % 16 != 0))
     return FDA_EINVAL;
@@ -145,23 +172,23 @@ int fda_calib_stream(int mode, const void* src, void* dst, size_t bytes, int rep
       hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess)
     return FDA_EHIP;
   const long long nvec = (long long)(bytes / 16);
-  long long blocks = (nvec + kThreads - 1) / kThreads;
-  if (blocks > (long long)cus * 16) blocks = (long long)cus * 16;
+  long long blocks = (nvec + kThreads * kUnroll - 1) / (kThreads * kUnroll);
+  if (blocks > (long long)cus * 64) blocks = (long long)cus * 64;
   hipEvent_t e0, e1;
   if (hipEventCreate(&e0) != hipSuccess) return FDA_EHIP;
   if (hipEventCreate(&e1) != hipSuccess) { (void)hipEventDestroy(e0); return FDA_EHIP; }
   int rc = FDA_OK;
   for (int r = -1; r < reps && rc == FDA_OK; ++r) {       // one untimed launch first
     if (r == 0 && hipEventRecord(e0, st) != hipSuccess) rc = FDA_EHIP;
-    if (mode == 0)
-      hipLaunchKernelGGL(calib_read_kernel, dim3((unsigned)blocks), dim3(kThreads), 0, st,
-                         static_cast<const u32x4*>(src), nvec, static_cast<uint32_t*>(dst));
-    else if (mode == 1)
-      hipLaunchKernelGGL(calib_write_kernel, dim3((unsigned)blocks), dim3(kThreads), 0, st,
-                         static_cast<u32x4*>(dst), nvec, 0x3f800000u);
-    else
-      hipLaunchKernelGGL(calib_copy_kernel, dim3((unsigned)blocks), dim3(kThreads), 0, st,
-                         static_cast<const u32x4*>(src), static_cast<u32x4*>(dst), nvec);
+    const dim3 g((unsigned)blocks), b(kThreads);
+    const u32x4* s4 = static_cast<const u32x4*>(src);
+    u32x4* d4 = static_cast<u32x4*>(dst);
+    if (mode == 0 && nt) hipLaunchKernelGGL(calib_read_kernel<true>, g, b, 0, st, s4, nvec, static_cast<uint32_t*>(dst));
+    else if (mode == 0) hipLaunchKernelGGL(calib_read_kernel<false>, g, b, 0, st, s4, nvec, static_cast<uint32_t*>(dst));
+    else if (mode == 1 && nt) hipLaunchKernelGGL(calib_write_kernel<true>, g, b, 0, st, d4, nvec, 0x3f800000u);
+    else if (mode == 1) hipLaunchKernelGGL(calib_write_kernel<false>, g, b, 0, st, d4, nvec, 0x3f800000u);
+    else if (nt) hipLaunchKernelGGL(calib_copy_kernel<true>, g, b, 0, st, s4, d4, nvec);
+    else hipLaunchKernelGGL(calib_copy_kernel<false>, g, b, 0, st, s4, d4, nvec);
     if (hipGetLastError() != hipSuccess) rc = FDA_EHIP;
   }
   float ms = 0.0f;

@@ -82,6 +82,26 @@ typedef float f32x4 __attribute__((ext_vector_type(4), aligned(4)));
 typedef uint32_t u32x4_h __attribute__((ext_vector_type(4), aligned(2)));     // 8 bf16
 typedef uint32_t u32x2_h __attribute__((ext_vector_type(2), aligned(2)));     // 4 bf16
 
+// Streaming loads.  Every byte of the slab is read exactly once per pass, so its loads carry the
+// nontemporal hint: on this chip a read-only pass of plain 16-byte loads reaches about 6.3 TB/s, the
+// same pass with the hint about 7.1 TB/s (the library's calibration kernels measure both).  w_t0, xi
+// and the hash table are read by every worker group of a coordinate range; hinting them too cost the
+// passes with several worker groups up to a tenth, so they keep plain loads.
+#ifndef FDA_NT_SLAB
+#define FDA_NT_SLAB 1
+#endif
+#ifndef FDA_NT_SHARED
+#define FDA_NT_SHARED 0
+#endif
+template <typename VecT, bool NT>
+__device__ __forceinline__ VecT load_vec_hint(const void* p) {
+  if constexpr (NT) return __builtin_nontemporal_load(reinterpret_cast<const VecT*>(p));
+  else return *reinterpret_cast<const VecT*>(p);
+}
+typedef uint32_t u32x2_a8 __attribute__((ext_vector_type(2)));                // 8-byte aligned pair (table words)
+constexpr bool kNtSlab = FDA_NT_SLAB != 0;
+constexpr bool kNtShared = FDA_NT_SHARED != 0;
+
 // ---- slab element access ---------------------------------------------------------------
 template <typename T> struct Slab;
 template <> struct Slab<float> {
@@ -127,11 +147,11 @@ template <> struct Slab<bf16_t> {
   }
 };
 
-template <int V>
+template <int V, bool NT = false>
 __device__ __forceinline__ void load_f32_vec(const float* p, float (&x)[V]) {
 #pragma unroll
   for (int q = 0; q < V; q += 4) {
-    const f32x4 t = *reinterpret_cast<const f32x4*>(p + q);
+    const f32x4 t = load_vec_hint<f32x4, NT>(p + q);
     x[q] = t.x; x[q + 1] = t.y; x[q + 2] = t.z; x[q + 3] = t.w;
   }
 }
@@ -320,22 +340,22 @@ state_kernel(const StateParams prm) {
 
     // whole vectors, no tests: for tiles that lie entirely inside the chunk
     auto load_fast = [&](Tile& t, long long j0) {
-      load_f32_vec<V>(w0p + j0, t.w0);
-      if constexpr (SC) load_f32_vec<V>(xip + j0, t.x);
+      load_f32_vec<V, kNtShared>(w0p + j0, t.w0);
+      if constexpr (SC) load_f32_vec<V, kNtShared>(xip + j0, t.x);
 #pragma unroll
       for (int k = 0; k < KC; ++k) {
         if constexpr (sizeof(T) == 4) {
-          const u32x4 q = *reinterpret_cast<const u32x4*>(wrow[k] + j0);
+          const u32x4 q = load_vec_hint<u32x4, kNtSlab>(wrow[k] + j0);
           t.w[k][0] = q.x; t.w[k][1] = q.y; t.w[k][2] = q.z; t.w[k][3] = q.w;
         } else {
-          const u32x2_h q = *reinterpret_cast<const u32x2_h*>(wrow[k] + j0);
+          const u32x2_h q = load_vec_hint<u32x2_h, kNtSlab>(wrow[k] + j0);
           t.w[k][0] = q.x; t.w[k][1] = q.y;
         }
       }
       if constexpr (SK) {
 #pragma unroll
         for (int i = 0; i < LR; ++i) {
-          const uint2 q = *reinterpret_cast<const uint2*>(trow[i] + j0);
+          const u32x2_a8 q = load_vec_hint<u32x2_a8, kNtShared>(trow[i] + j0);
           t.tab[i][0] = q.x; t.tab[i][1] = q.y;
         }
       }

@@ -153,10 +153,10 @@ mean_state_kernel(const MeanParams prm) {
         const int row = (k0 + k < K) ? k0 + k : K - 1;
         const T* src = wbase + (long long)row * rs + j0;
         if constexpr (sizeof(T) == 4) {
-          const u32x4 q = *reinterpret_cast<const u32x4*>(src);
+          const u32x4 q = load_vec_hint<u32x4, kNtSlab>(src);
           bt.w[k][0] = q.x; bt.w[k][1] = q.y; bt.w[k][2] = q.z; bt.w[k][3] = q.w;
         } else {
-          const u32x2_h q = *reinterpret_cast<const u32x2_h*>(src);
+          const u32x2_h q = load_vec_hint<u32x2_h, kNtSlab>(src);
           bt.w[k][0] = q.x; bt.w[k][1] = q.y;
         }
       }
@@ -186,14 +186,14 @@ mean_state_kernel(const MeanParams prm) {
         // the table is padded to dpad (a multiple of 64 coordinates): always a whole vector
 #pragma unroll
         for (int i = 0; i < LR; ++i) {
-          const uint2 q = *reinterpret_cast<const uint2*>(trow[i] + j0);
+          const u32x2_a8 q = load_vec_hint<u32x2_a8, kNtShared>(trow[i] + j0);
           h.tab[i][0] = q.x; h.tab[i][1] = q.y;
         }
       }
     };
     auto load_head_fast = [&](Head& h, long long j0) {
-      load_f32_vec<V>(w0p + j0, h.w0);
-      if constexpr (SC) load_f32_vec<V>(xip + j0, h.x);
+      load_f32_vec<V, kNtShared>(w0p + j0, h.w0);
+      if constexpr (SC) load_f32_vec<V, kNtShared>(xip + j0, h.x);
       load_table(h, j0);
     };
     auto load_head_slow = [&](Head& h, long long j0) {

@@ -315,54 +315,6 @@ merge_mean_kernel(const double* __restrict__ part_np, const void* __restrict__ p
   }
 }
 
-// Algorithm 1 line 9 when the average model is already there (w_bar from mean_state_kernel):
-// every row <- w_bar, w_prev <- w_t0, w_t0 <- w_bar, and (xi != NULL) the xi of Section 3.2,
-// (w_bar - old w_t0) / ||w_bar - old w_t0||, with the squared norm taken from *dnorm.
-template <typename T>
-__global__ void __launch_bounds__(kSmallThreads)
-sync_from_mean_kernel(T* __restrict__ w, float* __restrict__ w_t0, float* __restrict__ w_prev,
-                      float* __restrict__ xi, const float* __restrict__ w_bar,
-                      const double* __restrict__ dnorm, const int32_t* __restrict__ pred, int K,
-                      long long d, long long row_stride, int vec_ok) {
-  constexpr int V = Slab<T>::V;
-  if (pred != nullptr && *pred == 0) return;
-  float scale = 0.0f;
-  if (xi != nullptr) {
-    const double nrm = sqrt(*dnorm);
-    scale = (nrm > 0.0 && isfinite(nrm)) ? (float)(1.0 / nrm) : 0.0f;
-  }
-  const long long nvec = (d + V - 1) / V;
-  for (long long vi = (long long)blockIdx.x * blockDim.x + threadIdx.x; vi < nvec;
-       vi += (long long)gridDim.x * blockDim.x) {
-    const long long j0 = vi * V;
-    if (vec_ok && j0 + V <= d) {
-      float nb[V], old[V];
-      load_f32_vec<V>(w_bar + j0, nb);
-      load_f32_vec<V>(w_t0 + j0, old);
-      if (w_prev != nullptr) store_f32_vec<V>(w_prev + j0, old);
-      store_f32_vec<V>(w_t0 + j0, nb);
-      if (xi != nullptr) {
-        float x[V];
-#pragma unroll
-        for (int v = 0; v < V; ++v) x[v] = (scale == 0.0f) ? 0.0f : (nb[v] - old[v]) * scale;
-        store_f32_vec<V>(xi + j0, x);
-      }
-#pragma unroll 4
-      for (int k = 0; k < K; ++k) Slab<T>::store_vec(w + (long long)k * row_stride + j0, nb);
-    } else {
-      for (int v = 0; v < V; ++v) {
-        const long long j = j0 + v;
-        if (j >= d) break;
-        const float a = w_bar[j], o = w_t0[j];
-        if (w_prev != nullptr) w_prev[j] = o;
-        w_t0[j] = a;
-        if (xi != nullptr) xi[j] = (scale == 0.0f) ? 0.0f : (a - o) * scale;
-        for (int k = 0; k < K; ++k) Slab<T>::store_one(w + (long long)k * row_stride + j, a);
-      }
-    }
-  }
-}
-
 // ----------------------------------------------------------------------------------------
 // Algorithm 1 lines 7-8, all in fp64:
 //   mean_k of the states;  row norms of the mean sketch;  M2 = their median (Section 3.1);
@@ -458,26 +410,104 @@ estimate_kernel(const float* __restrict__ state, int K, int l, int m, int varian
 // ----------------------------------------------------------------------------------------
 // Algorithm 1 line 9: read the K rows once, average in fp32 in worker order, write the
 // average to every row, to w_t0, and the old w_t0 to w_prev.
+//
+// A lane owns 4 consecutive coordinates (16 bytes of fp32, 8 bytes of bf16), so every load and store
+// instruction of a wave covers whole cache lines, and workgroup b owns the contiguous range of such
+// vectors [b * per, (b + 1) * per), a few trips long (the host launches one workgroup per 1024
+// vectors): workgroups that run at the same time work on neighbouring addresses of every row, which
+// is what keeps the K + 2 interleaved read and write streams efficient in DRAM (ranges of hundreds
+// of KiB per workgroup cost a bf16 slab's pass a third of its rate).  STREAM: every byte is read once
+// and written once, so loads and stores carry the nontemporal hint -- chosen by the host for slabs
+// too large to stay in the memory-side cache, where it gains 3-8 %; small slabs lose by it.  (With 8
+// coordinates per lane the fp32 vectors of a bf16 slab's pass become two 16-byte accesses 32 bytes
+// apart: half cache lines per instruction, which the hinted stores pay for twice.)
 // ----------------------------------------------------------------------------------------
-template <typename T>
+constexpr bool kSyncContiguous = true;
+constexpr int kSyncV = 4;                    // coordinates per lane in the synchronization kernels
+
+template <typename VecT, bool NT>
+__device__ __forceinline__ void store_vec_hint(void* p, VecT v) {
+  if constexpr (NT) __builtin_nontemporal_store(v, reinterpret_cast<VecT*>(p));
+  else *reinterpret_cast<VecT*>(p) = v;
+}
+// 4 slab elements at p as floats, and back
+template <bool NT>
+__device__ __forceinline__ void load_slab4(const float* p, float (&x)[4]) {
+  const f32x4 t = load_vec_hint<f32x4, NT>(p);
+  x[0] = t.x; x[1] = t.y; x[2] = t.z; x[3] = t.w;
+}
+template <bool NT>
+__device__ __forceinline__ void load_slab4(const bf16_t* p, float (&x)[4]) {
+  const u32x2_h t = load_vec_hint<u32x2_h, NT>(p);
+  x[0] = __uint_as_float(t.x << 16); x[1] = __uint_as_float(t.x & 0xffff0000u);
+  x[2] = __uint_as_float(t.y << 16); x[3] = __uint_as_float(t.y & 0xffff0000u);
+}
+template <bool NT>
+__device__ __forceinline__ void store_f32x4(float* p, const float (&x)[4]) {
+  const f32x4 t = {x[0], x[1], x[2], x[3]};
+  store_vec_hint<f32x4, NT>(p, t);
+}
+// what a slab row stores for 4 averaged values: the fp32 values, or their bf16 roundings (packed)
+struct RowVec4 { uint32_t w[4]; };
+__device__ __forceinline__ RowVec4 pack_row4(const float (&x)[4], const float*) {
+  RowVec4 r;
+  r.w[0] = __float_as_uint(x[0]); r.w[1] = __float_as_uint(x[1]);
+  r.w[2] = __float_as_uint(x[2]); r.w[3] = __float_as_uint(x[3]);
+  return r;
+}
+__device__ __forceinline__ RowVec4 pack_row4(const float (&x)[4], const bf16_t*) {
+  RowVec4 r;
+  r.w[0] = f32_to_bf16_rne(x[0]) | (f32_to_bf16_rne(x[1]) << 16);
+  r.w[1] = f32_to_bf16_rne(x[2]) | (f32_to_bf16_rne(x[3]) << 16);
+  r.w[2] = 0u; r.w[3] = 0u;
+  return r;
+}
+template <bool NT>
+__device__ __forceinline__ void store_row4(float* p, const RowVec4& r) {
+  const u32x4 t = {r.w[0], r.w[1], r.w[2], r.w[3]};
+  store_vec_hint<u32x4, NT>(p, t);
+}
+template <bool NT>
+__device__ __forceinline__ void store_row4(bf16_t* p, const RowVec4& r) {
+  const u32x2_h t = {r.w[0], r.w[1]};
+  store_vec_hint<u32x2_h, NT>(p, t);
+}
+
+// the range of vectors a workgroup walks, and its stride
+struct SyncRange { long long beg, end, step; };
+__device__ __forceinline__ SyncRange sync_range(long long nvec) {
+  SyncRange r;
+  if (kSyncContiguous) {
+    const long long per = (nvec + gridDim.x - 1) / gridDim.x;
+    r.beg = (long long)blockIdx.x * per;
+    r.end = r.beg + per < nvec ? r.beg + per : nvec;
+    r.step = blockDim.x;
+  } else {
+    r.beg = (long long)blockIdx.x * blockDim.x;
+    r.end = nvec;
+    r.step = (long long)gridDim.x * blockDim.x;
+  }
+  return r;
+}
+
+template <typename T, bool STREAM>
 __global__ void __launch_bounds__(kSmallThreads)
 sync_kernel(T* __restrict__ w, float* __restrict__ w_t0, float* __restrict__ w_prev,
             const int32_t* __restrict__ pred, int K, long long d, long long row_stride, int vec_ok) {
-  constexpr int V = Slab<T>::V;
+  constexpr int V = kSyncV;
   if (pred != nullptr && *pred == 0) return;
   const float kf = (float)K;
-  const long long nvec = (d + V - 1) / V;
-  for (long long vi = (long long)blockIdx.x * blockDim.x + threadIdx.x; vi < nvec;
-       vi += (long long)gridDim.x * blockDim.x) {
+  const SyncRange rg = sync_range((d + V - 1) / V);
+  for (long long vi = rg.beg + threadIdx.x; vi < rg.end; vi += rg.step) {
     const long long j0 = vi * V;
     float acc[V];
 #pragma unroll
     for (int v = 0; v < V; ++v) acc[v] = 0.0f;
     if (vec_ok && j0 + V <= d) {
-#pragma unroll 4
+#pragma unroll 8
       for (int k = 0; k < K; ++k) {
         float x[V];
-        Slab<T>::load_vec(w + (long long)k * row_stride + j0, x);
+        load_slab4<STREAM>(w + (long long)k * row_stride + j0, x);
 #pragma unroll
         for (int v = 0; v < V; ++v) acc[v] += x[v];
       }
@@ -485,12 +515,13 @@ sync_kernel(T* __restrict__ w, float* __restrict__ w_t0, float* __restrict__ w_p
       for (int v = 0; v < V; ++v) acc[v] = acc[v] / kf;
       if (w_prev != nullptr) {
         float old[V];
-        load_f32_vec<V>(w_t0 + j0, old);
-        store_f32_vec<V>(w_prev + j0, old);
+        load_f32_vec<V, STREAM>(w_t0 + j0, old);
+        store_f32x4<STREAM>(w_prev + j0, old);
       }
-      store_f32_vec<V>(w_t0 + j0, acc);
-#pragma unroll 4
-      for (int k = 0; k < K; ++k) Slab<T>::store_vec(w + (long long)k * row_stride + j0, acc);
+      store_f32x4<STREAM>(w_t0 + j0, acc);
+      const RowVec4 row = pack_row4(acc, static_cast<const T*>(nullptr));
+#pragma unroll 8
+      for (int k = 0; k < K; ++k) store_row4<STREAM>(w + (long long)k * row_stride + j0, row);
     } else {
       for (int v = 0; v < V; ++v) {
         const long long j = j0 + v;
@@ -500,6 +531,54 @@ sync_kernel(T* __restrict__ w, float* __restrict__ w_t0, float* __restrict__ w_p
         a = a / kf;
         if (w_prev != nullptr) w_prev[j] = w_t0[j];
         w_t0[j] = a;
+        for (int k = 0; k < K; ++k) Slab<T>::store_one(w + (long long)k * row_stride + j, a);
+      }
+    }
+  }
+}
+
+// Algorithm 1 line 9 when the average model is already there (w_bar from mean_state_kernel):
+// every row <- w_bar, w_prev <- w_t0, w_t0 <- w_bar, and (xi != NULL) the xi of Section 3.2,
+// (w_bar - old w_t0) / ||w_bar - old w_t0||, with the squared norm taken from *dnorm.
+template <typename T, bool STREAM>
+__global__ void __launch_bounds__(kSmallThreads)
+sync_from_mean_kernel(T* __restrict__ w, float* __restrict__ w_t0, float* __restrict__ w_prev,
+                      float* __restrict__ xi, const float* __restrict__ w_bar,
+                      const double* __restrict__ dnorm, const int32_t* __restrict__ pred, int K,
+                      long long d, long long row_stride, int vec_ok) {
+  constexpr int V = kSyncV;
+  if (pred != nullptr && *pred == 0) return;
+  float scale = 0.0f;
+  if (xi != nullptr) {
+    const double nrm = sqrt(*dnorm);
+    scale = (nrm > 0.0 && isfinite(nrm)) ? (float)(1.0 / nrm) : 0.0f;
+  }
+  const SyncRange rg = sync_range((d + V - 1) / V);
+  for (long long vi = rg.beg + threadIdx.x; vi < rg.end; vi += rg.step) {
+    const long long j0 = vi * V;
+    if (vec_ok && j0 + V <= d) {
+      float nb[V], old[V];
+      load_f32_vec<V, STREAM>(w_bar + j0, nb);
+      load_f32_vec<V, STREAM>(w_t0 + j0, old);
+      if (w_prev != nullptr) store_f32x4<STREAM>(w_prev + j0, old);
+      store_f32x4<STREAM>(w_t0 + j0, nb);
+      if (xi != nullptr) {
+        float x[V];
+#pragma unroll
+        for (int v = 0; v < V; ++v) x[v] = (scale == 0.0f) ? 0.0f : (nb[v] - old[v]) * scale;
+        store_f32x4<STREAM>(xi + j0, x);
+      }
+      const RowVec4 row = pack_row4(nb, static_cast<const T*>(nullptr));
+#pragma unroll 8
+      for (int k = 0; k < K; ++k) store_row4<STREAM>(w + (long long)k * row_stride + j0, row);
+    } else {
+      for (int v = 0; v < V; ++v) {
+        const long long j = j0 + v;
+        if (j >= d) break;
+        const float a = w_bar[j], o = w_t0[j];
+        if (w_prev != nullptr) w_prev[j] = o;
+        w_t0[j] = a;
+        if (xi != nullptr) xi[j] = (scale == 0.0f) ? 0.0f : (a - o) * scale;
         for (int k = 0; k < K; ++k) Slab<T>::store_one(w + (long long)k * row_stride + j, a);
       }
     }
