@@ -74,9 +74,13 @@ struct Plan {
   Split wide;       // 8-byte cells: the 64-bit integer and fp64 passes
   MeanSplit mean;   // fda_mean_state
   int vec;          // elements per 16-byte slab load
+  int fb;           // bits per field of the tabulated hash
+  int words;        // 16-bit words per record of the table the 32-bit-cell pass streams
+  int mean_words;   // ... and of the mean-state pass's table
+  bool shared_table;  // both passes split the rows alike and stream one table
   int64_t cells, S, dpad;
   int64_t off_np, off_sk, off_xi, off_scale, off_smax, off_ssum, off_nmax, off_dnorm, off_est, off_ticket, off_table,
-      ws_bytes;
+      off_mean_table, ws_bytes;
 };
 
 int validate(const fda_desc* d) {
@@ -245,7 +249,16 @@ int make_plan(const fda_desc* d, int cus, int64_t lds_cu, Plan* pl) {
   pl->off_ticket = round_up(pl->off_est + (2 + (int64_t)FDA_MAX_SKETCH_ROWS * kMaxEstBlocksPerRow) * 8, kAlign);
   pl->off_table = round_up(pl->off_ticket + 8, kAlign);
   pl->dpad = round_up(d->d, 64);
-  pl->ws_bytes = round_up(pl->off_table + (sk ? (int64_t)d->l * pl->dpad * 2 : 0), kAlign);
+  // the tabulated hash: per row group one record per coordinate with a field per row slot
+  pl->fb = fda::field_bits_for(sk ? d->m : 1);
+  pl->words = (pl->narrow.LR * pl->fb + 15) / 16;
+  pl->mean_words = (pl->mean.rcnt_max * pl->fb + 15) / 16;
+  pl->shared_table = pl->narrow.R == pl->mean.R && pl->narrow.LR == pl->mean.rcnt_max;
+  const int64_t table_bytes = sk ? (int64_t)pl->narrow.R * pl->dpad * pl->words * 2 : 0;
+  const int64_t mean_table_bytes =
+      sk && !pl->shared_table ? (int64_t)pl->mean.R * pl->dpad * pl->mean_words * 2 : 0;
+  pl->off_mean_table = pl->shared_table ? pl->off_table : round_up(pl->off_table + table_bytes, kAlign);
+  pl->ws_bytes = round_up(pl->off_mean_table + mean_table_bytes + (pl->shared_table ? table_bytes : 0), kAlign);
   return FDA_OK;
 }
 
@@ -286,12 +299,12 @@ constexpr int kVecOk = 1;
 
 // Route a launch (or, with prm == nullptr, the LDS-limit setup) to the translation unit that
 // holds the kernel for this slab type, cell kind and shape.
-int dispatch_any(int dtype, int cell, const Split& sp, const fda::StateParams* prm, hipStream_t st) {
+int dispatch_any(int dtype, int cell, const Split& sp, int FB, const fda::StateParams* prm, hipStream_t st) {
   const int KC = sp.KC, LR = sp.LR;
   const size_t lds = (size_t)sp.lds_bytes;
   hipError_t e = hipErrorInvalidValue;
   if (cell == fda::kCellI32) {
-#define FDA_CASE(t, kc) case kc: e = fda::launch_narrow_##t##_kc##kc(LR, prm, lds, st); break
+#define FDA_CASE(t, kc) case kc: e = fda::launch_narrow_##t##_kc##kc(LR, FB, prm, lds, st); break
     if (dtype == FDA_F32) {
       switch (KC) { FDA_CASE(f32, 1); FDA_CASE(f32, 2); FDA_CASE(f32, 3); FDA_CASE(f32, 4);
                     FDA_CASE(f32, 5); FDA_CASE(f32, 6); FDA_CASE(f32, 8); }
@@ -313,15 +326,15 @@ int dispatch_any(int dtype, int cell, const Split& sp, const fda::StateParams* p
   return FDA_OK;
 }
 
-int dispatch_mean(int dtype, int cell, const MeanSplit& ms, const fda::MeanParams* prm, hipStream_t st) {
+int dispatch_mean(int dtype, int cell, const MeanSplit& ms, int FB, const fda::MeanParams* prm, hipStream_t st) {
   const size_t lds = (size_t)ms.lds_bytes;
   hipError_t e;
   if (dtype == FDA_F32)
-    e = cell == fda::kCellI64 ? fda::launch_mean_f32_i64(ms.rcnt_max, prm, lds, st)
-                              : fda::launch_mean_f32_f64(ms.rcnt_max, prm, lds, st);
+    e = cell == fda::kCellI64 ? fda::launch_mean_f32_i64(ms.rcnt_max, FB, prm, lds, st)
+                              : fda::launch_mean_f32_f64(ms.rcnt_max, FB, prm, lds, st);
   else
-    e = cell == fda::kCellI64 ? fda::launch_mean_bf16_i64(ms.rcnt_max, prm, lds, st)
-                              : fda::launch_mean_bf16_f64(ms.rcnt_max, prm, lds, st);
+    e = cell == fda::kCellI64 ? fda::launch_mean_bf16_i64(ms.rcnt_max, FB, prm, lds, st)
+                              : fda::launch_mean_bf16_f64(ms.rcnt_max, FB, prm, lds, st);
   if (e == hipErrorInvalidValue)
     return fail(FDA_EINVAL, "internal: no mean-state kernel for %d rows per workgroup", ms.rcnt_max);
   if (e != hipSuccess) return fail(FDA_EHIP, "mean-state kernel launch failed: %s", hipGetErrorString(e));
@@ -361,6 +374,8 @@ struct fda_ctx {
   int device;
   int cus;
   bool counted = false;       // cell_count_kernel has been enqueued for this context
+  bool table_built = false;       // the hash table of the 32-bit-cell pass has been enqueued
+  bool mean_table_built = false;  // ... of the mean-state pass (the same table when the plan shares it)
   bool tickets_cleared = false;
   // optional timing of the state kernel (fda_profile_enable)
   bool prof_on = false;
@@ -417,7 +432,21 @@ int prof_end(fda_ctx* c, hipStream_t st, int slot) {
 
 // Before the first sketch of a context: the hash table and the cell counts.  Then, per call, the
 // fixed-point units from a sample of the drifts (this also clears the flags in *scale).
-int prepare_sketch(fda_ctx* ctx, const void* w, const float* w_t0, fda::ScaleInfo* scale, hipStream_t st) {
+int build_table(fda_ctx* ctx, int R, int slots, int words, int64_t off, hipStream_t st) {
+  const fda_desc& d = ctx->desc;
+  const Plan& pl = ctx->plan;
+  const long long groups = pl.dpad / 4;
+  hipLaunchKernelGGL(fda::hash_table_kernel,
+                     dim3((unsigned)((groups + fda::kSmallThreads - 1) / fda::kSmallThreads), (unsigned)R),
+                     dim3(fda::kSmallThreads), 0, st, ctx->coef, d.l, R, slots, d.m, pl.fb, words,
+                     (long long)d.d, (long long)pl.dpad, reinterpret_cast<uint16_t*>(ctx->ws + off));
+  FDA_HIP(hipGetLastError());
+  return FDA_OK;
+}
+
+// for_mean: the call is fda_mean_state (else fda_local_state): which table must exist
+int prepare_sketch(fda_ctx* ctx, const void* w, const float* w_t0, fda::ScaleInfo* scale, bool for_mean,
+                   hipStream_t st) {
   const fda_desc& d = ctx->desc;
   const Plan& pl = ctx->plan;
   int rc0 = clear_tickets_once(ctx, st);
@@ -438,14 +467,20 @@ int prepare_sketch(fda_ctx* ctx, const void* w, const float* w_t0, fda::ScaleInf
                        (size_t)d.m * 4, st, ctx->coef, d.l, d.m, (long long)d.d,
                        (long long)pl.wide.chunk, nmax + 1);
     FDA_HIP(hipGetLastError());
-    // ... and the hash of every (row, coordinate), tabulated
-    const long long groups = pl.dpad / 8;
-    hipLaunchKernelGGL(fda::hash_table_kernel,
-                       dim3((unsigned)((groups + fda::kSmallThreads - 1) / fda::kSmallThreads), d.l),
-                       dim3(fda::kSmallThreads), 0, st, ctx->coef, d.m, (long long)d.d,
-                       (long long)pl.dpad, reinterpret_cast<uint16_t*>(ctx->ws + pl.off_table));
-    FDA_HIP(hipGetLastError());
     ctx->counted = true;
+  }
+  // ... and the hash of every (row, coordinate), tabulated for the pass that is about to run
+  if (!for_mean && !ctx->table_built) {
+    int rc = build_table(ctx, pl.narrow.R, pl.narrow.LR, pl.words, pl.off_table, st);
+    if (rc != FDA_OK) return rc;
+    ctx->table_built = true;
+    if (pl.shared_table) ctx->mean_table_built = true;
+  }
+  if (for_mean && !ctx->mean_table_built) {
+    int rc = build_table(ctx, pl.mean.R, pl.mean.rcnt_max, pl.mean_words, pl.off_mean_table, st);
+    if (rc != FDA_OK) return rc;
+    ctx->mean_table_built = true;
+    if (pl.shared_table) ctx->table_built = true;
   }
   const int samples = (int)(d.d < kScaleSamples ? d.d : kScaleSamples);
   int slices = (d.K + 7) / 8;                 // about eight workers per thread
@@ -569,13 +604,13 @@ int fda_create(fda_ctx** ctx, const fda_desc* desc, void* workspace, size_t work
   Split narrow_max = pl.narrow, wide_max = pl.wide;
   MeanSplit mean_max = pl.mean;
   narrow_max.lds_bytes = wide_max.lds_bytes = mean_max.lds_bytes = lds;
-  rc = dispatch_any(desc->dtype, fda::kCellI32, narrow_max, nullptr, nullptr);
-  if (rc == FDA_OK) rc = dispatch_mean(desc->dtype, fda::kCellI64, mean_max, nullptr, nullptr);
+  rc = dispatch_any(desc->dtype, fda::kCellI32, narrow_max, pl.fb, nullptr, nullptr);
+  if (rc == FDA_OK) rc = dispatch_mean(desc->dtype, fda::kCellI64, mean_max, pl.fb, nullptr, nullptr);
   if (rc == FDA_OK && (desc->variants & FDA_VARIANT_SKETCH))
-    rc = dispatch_mean(desc->dtype, fda::kCellF64, mean_max, nullptr, nullptr);
+    rc = dispatch_mean(desc->dtype, fda::kCellF64, mean_max, pl.fb, nullptr, nullptr);
   if (rc == FDA_OK && (desc->variants & FDA_VARIANT_SKETCH)) {
-    rc = dispatch_any(desc->dtype, fda::kCellI64, wide_max, nullptr, nullptr);
-    if (rc == FDA_OK) rc = dispatch_any(desc->dtype, fda::kCellF64, wide_max, nullptr, nullptr);
+    rc = dispatch_any(desc->dtype, fda::kCellI64, wide_max, pl.fb, nullptr, nullptr);
+    if (rc == FDA_OK) rc = dispatch_any(desc->dtype, fda::kCellF64, wide_max, pl.fb, nullptr, nullptr);
     if (rc == FDA_OK &&
         hipFuncSetAttribute(reinterpret_cast<const void*>(fda::cell_count_kernel),
                             hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -685,27 +720,28 @@ int fda_local_state(fda_ctx* ctx, const void* w, const float* w_t0, const float*
     prm.scale = reinterpret_cast<fda::ScaleInfo*>(ctx->ws + pl.off_scale);
     prm.table = reinterpret_cast<const uint16_t*>(ctx->ws + pl.off_table);
     prm.dpad = pl.dpad;
+    prm.coef = ctx->coef;
     return prm;
   };
   const fda::StateParams prm32 = params_for(pl.narrow);
   const fda::StateParams prm64 = params_for(pl.wide);
 
   if (sk) {
-    rc = prepare_sketch(ctx, w, w_t0, prm32.scale, st);
+    rc = prepare_sketch(ctx, w, w_t0, prm32.scale, false, st);
     if (rc != FDA_OK) return rc;
   }
   int slot = -1;
   rc = prof_begin(ctx, st, &slot);
   if (rc != FDA_OK) return rc;
-  rc = dispatch_any(d.dtype, fda::kCellI32, pl.narrow, &prm32, st);
+  rc = dispatch_any(d.dtype, fda::kCellI32, pl.narrow, pl.fb, &prm32, st);
   if (rc != FDA_OK) return rc;
   rc = prof_end(ctx, st, slot);
   if (rc != FDA_OK) return rc;
   if (sk) {
     // these two return at once unless the pass before them could not represent the drifts
-    rc = dispatch_any(d.dtype, fda::kCellI64, pl.wide, &prm64, st);
+    rc = dispatch_any(d.dtype, fda::kCellI64, pl.wide, pl.fb, &prm64, st);
     if (rc != FDA_OK) return rc;
-    rc = dispatch_any(d.dtype, fda::kCellF64, pl.wide, &prm64, st);
+    rc = dispatch_any(d.dtype, fda::kCellF64, pl.wide, pl.fb, &prm64, st);
     if (rc != FDA_OK) return rc;
   }
 
@@ -745,23 +781,23 @@ int fda_mean_state(fda_ctx* ctx, const void* w, const float* w_t0, const float* 
   prm.part_np = reinterpret_cast<double*>(ctx->ws + pl.off_np);
   prm.part_sk = ctx->ws + pl.off_sk;
   prm.scale = reinterpret_cast<fda::ScaleInfo*>(ctx->ws + pl.off_scale) + 1;
-  prm.table = reinterpret_cast<const uint16_t*>(ctx->ws + pl.off_table);
+  prm.table = reinterpret_cast<const uint16_t*>(ctx->ws + pl.off_mean_table);
   prm.dpad = pl.dpad;
 
   if (sk) {
-    rc = prepare_sketch(ctx, w, w_t0, prm.scale, st);
+    rc = prepare_sketch(ctx, w, w_t0, prm.scale, true, st);
     if (rc != FDA_OK) return rc;
   }
   int slot = -1;
   rc = prof_begin(ctx, st, &slot);
   if (rc != FDA_OK) return rc;
-  rc = dispatch_mean(d.dtype, fda::kCellI64, ms, &prm, st);
+  rc = dispatch_mean(d.dtype, fda::kCellI64, ms, pl.fb, &prm, st);
   if (rc != FDA_OK) return rc;
   rc = prof_end(ctx, st, slot);
   if (rc != FDA_OK) return rc;
   if (sk) {
     // returns at once unless a drift was too large for the integers
-    rc = dispatch_mean(d.dtype, fda::kCellF64, ms, &prm, st);
+    rc = dispatch_mean(d.dtype, fda::kCellF64, ms, pl.fb, &prm, st);
     if (rc != FDA_OK) return rc;
   }
   const int blocks = (int)((pl.S + 1 + 31) / 32);

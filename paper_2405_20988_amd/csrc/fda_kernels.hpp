@@ -4,9 +4,12 @@
 // The hash of a coordinate (bucket and sign per sketch row) depends on the coefficients and on
 // j only -- not on the worker, not on the step.  Evaluating two cubics mod p per sketch row
 // costs more vector-ALU work per coordinate than the whole rest of the pass is allowed at the
-// HBM roofline, so it is evaluated once per context into a table in HBM, [row][dpad] 16-bit
-// words (bits 0..14 bucket, bit 15 set for sign -1), which the state pass streams next to the
-// slab (2*l extra bytes per coordinate).
+// HBM roofline, so it is evaluated once per context into a table in HBM which the state pass
+// streams next to the slab: one record per coordinate holding, for every sketch row of a row
+// group, a field of FB bits (bucket in the low FB-1 bits, top bit set for sign -1), fields packed
+// back to back and the record padded to whole 16-bit words -- 10 bytes per coordinate for a
+// 7 x 1000 sketch, 8 for 5 x 500 and 5 x 250 (FB = 11), 2 bytes per row for wider sketches
+// (FB = 16).  A lane's V = 4 coordinates are 4 consecutive records: a few wide loads.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -66,8 +69,9 @@ struct StateParams {
   double* part_np;        // [P][K][2]
   void* part_sk;          // [P][K][l*m] 8-byte words: int64 (integer cells) or double (fp64 cells)
   ScaleInfo* scale;
-  const uint16_t* table;  // [l][dpad] tabulated hash
+  const uint16_t* table;  // [R][dpad] records of the tabulated hash (32-bit-cell pass only)
   long long dpad;
+  HashCoef coef;          // the fallback passes evaluate the hash themselves
 };
 
 struct bf16_t { uint16_t bits; };
@@ -193,17 +197,79 @@ __device__ __host__ inline void group_range(int K, int G, int g, int* start, int
 
 constexpr double kRoundMagic = 6755399441055744.0;       // 1.5 * 2^52
 
+// ---- arithmetic modulo the Mersenne prime 2^31 - 1 (operands already reduced) --------
+__device__ __forceinline__ uint32_t addmod(uint32_t a, uint32_t b) {
+  uint32_t s = a + b;                        // < 2^32
+  return min(s, s - kPrime);                 // s - p wraps to a huge value when s < p
+}
+__device__ __forceinline__ uint32_t mulmod(uint32_t a, uint32_t b) {
+  uint64_t t = (uint64_t)a * b;              // < 2^62
+  uint32_t lo = (uint32_t)t & kPrime;
+  uint32_t hi = (uint32_t)(t >> 31);         // 2^31 = 1 (mod p)
+  uint32_t s = lo + hi;                      // <= 2p - 1
+  return min(s, s - kPrime);
+}
+// c[3] j^3 + c[2] j^2 + c[1] j + c[0] mod p
+__device__ __forceinline__ uint32_t poly3(const uint32_t* c, uint32_t j) {
+  uint32_t g = c[3];
+  g = addmod(mulmod(g, j), c[2]);
+  g = addmod(mulmod(g, j), c[1]);
+  g = addmod(mulmod(g, j), c[0]);
+  return g;
+}
+// bucket = floor(g_b(j) * m / 2^31) in bits 0..14, bit 15 set when g_s(j) is odd (sign -1)
+__device__ __forceinline__ uint32_t hash_entry(const HashCoef& hc, int row, uint32_t j, uint32_t m) {
+  const uint32_t gb = poly3(hc.c[row][0], j);
+  const uint32_t gs = poly3(hc.c[row][1], j);
+  return __umulhi(gb << 1, m) | ((gs & 1u) << 15);
+}
+
+// ---- the tabulated hash: geometry of a record and of a lane's share of a tile -----------
+constexpr int kDummyCells = 64;              // cells of the dummy region (power of two)
+// field width for a sketch of m columns: 11 bits while the bucket fits in 10, else 16
+__host__ __device__ constexpr int field_bits_for(int m) { return m <= 1024 ? 11 : 16; }
+template <int LR, int FB>
+struct RecGeom {
+  static constexpr int kWords = (LR * FB + 15) / 16;        // 16-bit words per coordinate record
+  static constexpr int kDwords = 2 * kWords;                // dwords of a lane's 4 consecutive records
+  static constexpr uint32_t kBucketMask = (1u << (FB - 1)) - 1u;
+};
+// N dwords from p (4-byte aligned at least), in the widest pieces
+template <int N, bool NT>
+__device__ __forceinline__ void load_dwords(const uint32_t* p, uint32_t (&out)[N]) {
+  constexpr int n4 = N / 4, n2 = (N % 4) / 2, n1 = N % 2;
+#pragma unroll
+  for (int q = 0; q < n4; ++q) {
+    const u32x4 t = load_vec_hint<u32x4, NT>(p + 4 * q);
+    out[4 * q] = t.x; out[4 * q + 1] = t.y; out[4 * q + 2] = t.z; out[4 * q + 3] = t.w;
+  }
+  if constexpr (n2 == 1) {
+    const u32x2 t = load_vec_hint<u32x2, NT>(p + 4 * n4);
+    out[4 * n4] = t.x; out[4 * n4 + 1] = t.y;
+  }
+  if constexpr (n1 == 1) out[N - 1] = load_vec_hint<uint32_t, NT>(p + N - 1);
+}
+// the FB-bit field of sketch-row slot i of the lane's coordinate v (both known after unrolling:
+// word index and shift fold to constants); bits above FB are garbage, callers mask
+template <int LR, int FB>
+__device__ __forceinline__ uint32_t rec_field(const uint32_t (&rec)[RecGeom<LR, FB>::kDwords], int v, int i) {
+  const int bit = v * 16 * RecGeom<LR, FB>::kWords + i * FB;
+  const int dw = bit >> 5, sh = bit & 31;
+  if (sh + FB <= 32) return rec[dw] >> sh;
+  return __builtin_amdgcn_alignbit(rec[dw + 1 < RecGeom<LR, FB>::kDwords ? dw + 1 : dw], rec[dw], sh);
+}
+
 // One lane's share of a tile, as loaded: V coordinates of w_t0, xi, of each worker's row and
-// of each sketch row's hash table.
+// the V hash records.
 constexpr int kStateV = 4;       // coordinates a lane owns per tile (fp32: 16 bytes, bf16: 8 bytes)
-template <typename T, int KC, int LR>
+template <typename T, int KC, int LR, int FB>
 struct TileRaw {
   static constexpr int V = kStateV;
   static constexpr int kWords = V * (int)sizeof(T) / 4;
   float w0[V];
   float x[V];
-  uint32_t w[KC][kWords];       // V elements of row k: 4 fp32 or 4 bf16
-  uint32_t tab[LR][V / 2];      // V 16-bit table entries per sketch row
+  uint32_t w[KC][kWords];                       // V elements of row k: 4 fp32 or 4 bf16
+  uint32_t rec[RecGeom<LR, FB>::kDwords];       // the V records of the tabulated hash
 };
 __device__ __forceinline__ float raw_elem(const uint32_t (&r)[4], int v) {      // fp32
   return __uint_as_float(r[v]);
@@ -244,14 +310,15 @@ __device__ __forceinline__ float raw_elem(const uint32_t (&r)[2], int v) {      
 //             ScaleInfo::overflow64 (noticed by the first pass, which sees every drift).
 //   kCellF64  fp64 cells (ds_add_f64), sketch only, runs only when overflow64 is set.
 // ----------------------------------------------------------------------------------------
-constexpr int kDummyCells = 64;              // cells of the dummy region (power of two)
-
-template <typename T, int KC, int LR, int CELL>
+template <typename T, int KC, int LR, int CELL, int FB>
 __global__ void __launch_bounds__(kStateThreads)
 state_kernel(const StateParams prm) {
   constexpr int V = kStateV;
   constexpr long long kTile = (long long)kStateThreads * V;
-  using Tile = TileRaw<T, KC, LR>;
+  // only the 32-bit-cell pass streams the table; the fallback passes evaluate the hash
+  constexpr bool kTabulated = CELL == kCellI32;
+  using Geom = RecGeom<LR, FB>;
+  using Tile = TileRaw<T, KC, LR, FB>;        // the fallback passes leave its records unloaded
   extern __shared__ __align__(16) unsigned char lds_raw[];
   constexpr int kCellBytes = (CELL == kCellI32) ? 4 : 8;
   if constexpr (CELL == kCellI64) {
@@ -304,21 +371,19 @@ state_kernel(const StateParams prm) {
   for (int k = 0; k < KC; ++k) { dn[k] = 0.0; dp[k] = 0.0; }
 
   // per worker slot: its slab row (spare slots repeat the last worker);
-  // per row slot: its table row, LDS base and bucket mask (spare slots: dummy region)
+  // per row slot: its LDS base (spare slots: the dummy region, whose table fields -- and, in the
+  // fallback passes, masked buckets -- stay below kDummyCells)
   const T* wrow[KC];
 #pragma unroll
   for (int k = 0; k < KC; ++k)
     wrow[k] = reinterpret_cast<const T*>(prm.w) +
               (long long)(kstart + (k < kcnt ? k : kcnt - 1)) * prm.row_stride;
-  const uint16_t* trow[LR];
-  uint32_t rowbase[LR], rowmask[LR];
+  uint32_t rowbase[LR];
 #pragma unroll
-  for (int i = 0; i < LR; ++i) {
-    const bool live = i < rcnt;
-    trow[i] = prm.table + (size_t)(rstart + (live ? i : 0)) * prm.dpad;
-    rowbase[i] = live ? (uint32_t)(i * prm.m) * stride_bytes : dummy_base;
-    rowmask[i] = live ? 0x7fffu : (uint32_t)(kDummyCells - 1);
-  }
+  for (int i = 0; i < LR; ++i) rowbase[i] = i < rcnt ? (uint32_t)(i * prm.m) * stride_bytes : dummy_base;
+  // this row group's records: [r][dpad] records of Geom::kWords 16-bit words
+  const uint32_t* const recs =
+      reinterpret_cast<const uint32_t*>(prm.table + (size_t)r * prm.dpad * Geom::kWords);
 
   const long long cbeg = (long long)p * prm.chunk;
   long long cend = cbeg + prm.chunk;
@@ -352,13 +417,8 @@ state_kernel(const StateParams prm) {
           t.w[k][0] = q.x; t.w[k][1] = q.y;
         }
       }
-      if constexpr (SK) {
-#pragma unroll
-        for (int i = 0; i < LR; ++i) {
-          const u32x2_a8 q = load_vec_hint<u32x2_a8, kNtShared>(trow[i] + j0);
-          t.tab[i][0] = q.x; t.tab[i][1] = q.y;
-        }
-      }
+      if constexpr (SK && kTabulated)
+        load_dwords<Geom::kDwords, kNtShared>(recs + (j0 >> 1) * Geom::kWords, t.rec);
     };
     // element by element, every access tested: ragged tails and slabs without dword alignment
     auto load_slow = [&](Tile& t, long long j0) {
@@ -385,17 +445,12 @@ state_kernel(const StateParams prm) {
           }
         }
       }
-      if constexpr (SK) {
-        // the table is padded to dpad (a multiple of 64 coordinates): always a whole vector
-#pragma unroll
-        for (int i = 0; i < LR; ++i) {
-          const uint2 q = *reinterpret_cast<const uint2*>(trow[i] + j0);
-          t.tab[i][0] = q.x; t.tab[i][1] = q.y;
-        }
-      }
+      // the table is padded to dpad (a multiple of 64 coordinates): always whole records
+      if constexpr (SK && kTabulated)
+        load_dwords<Geom::kDwords, false>(recs + (j0 >> 1) * Geom::kWords, t.rec);
     };
 
-    auto consume = [&](const Tile& t) {
+    auto consume = [&](const Tile& t, long long j0) {
       float sn[KC], sp[KC];
 #pragma unroll
       for (int k = 0; k < KC; ++k) { sn[k] = 0.0f; sp[k] = 0.0f; }
@@ -414,18 +469,21 @@ state_kernel(const StateParams prm) {
           }
         }
         if constexpr (SK && CELL == kCellI32) {
-          uint32_t q[KC];
+          uint32_t q[KC], nq[KC];
 #pragma unroll
-          for (int k = 0; k < KC; ++k) q[k] = (uint32_t)(int)rintf(u[k] * S32);
+          for (int k = 0; k < KC; ++k) {
+            q[k] = (uint32_t)(int)rintf(u[k] * S32);
+            nq[k] = 0u - q[k];
+          }
 #pragma unroll
           for (int i = 0; i < LR; ++i) {
-            const uint32_t h = (v & 1) ? (t.tab[i][v >> 1] >> 16) : (t.tab[i][v >> 1] & 0xffffu);
-            const uint32_t off = __umul24(h & rowmask[i], stride_bytes) + rowbase[i];
-            const uint32_t sgn = 0u - ((h >> 15) & 1u);                  // all ones for sign -1
+            const uint32_t h = rec_field<LR, FB>(t.rec, v, i);
+            const uint32_t off = __umul24(h & Geom::kBucketMask, stride_bytes) + rowbase[i];
+            const bool neg = (h & (1u << (FB - 1))) != 0u;                // sign -1
             uint32_t* cell = reinterpret_cast<uint32_t*>(lds_raw + off);
             uint32_t old[KC];
 #pragma unroll
-            for (int k = 0; k < KC; ++k) old[k] = atomicAdd(cell + k, (q[k] ^ sgn) - sgn);   // +q or -q
+            for (int k = 0; k < KC; ++k) old[k] = atomicAdd(cell + k, neg ? nq[k] : q[k]);
             // Every add is below 2^30 in magnitude (ScaleInfo::bound32), so a cell cannot wrap
             // in an add that found it inside [2^30, 3*2^30): if every value ever returned was
             // inside that band, no cell wrapped.  Only the smallest and the largest returned value
@@ -444,34 +502,35 @@ state_kernel(const StateParams prm) {
             have_pending = true;
           }
         }
-        if constexpr (SK && CELL == kCellI64) {
+        if constexpr (SK && CELL != kCellI32) {
+          // fallback passes: the hash is evaluated here (two cubics mod p per row and coordinate)
           unsigned long long q[KC], nq[KC];
+          if constexpr (CELL == kCellI64) {
 #pragma unroll
-          for (int k = 0; k < KC; ++k) {
-            const double y = fma((double)u[k], S64, kRoundMagic);           // round to integer
-            q[k] = (unsigned long long)(__double_as_longlong(y) - __double_as_longlong(kRoundMagic));
-            nq[k] = 0ull - q[k];
+            for (int k = 0; k < KC; ++k) {
+              const double y = fma((double)u[k], S64, kRoundMagic);           // round to integer
+              q[k] = (unsigned long long)(__double_as_longlong(y) - __double_as_longlong(kRoundMagic));
+              nq[k] = 0ull - q[k];
+            }
           }
+          const long long j = j0 + v;
+          const uint32_t key = j < dlim ? (uint32_t)j : 0u;                  // past the end the drift is zero
 #pragma unroll
           for (int i = 0; i < LR; ++i) {
-            const uint32_t h = (v & 1) ? (t.tab[i][v >> 1] >> 16) : (t.tab[i][v >> 1] & 0xffffu);
-            const uint32_t off = __umul24(h & rowmask[i], stride_bytes) + rowbase[i];
-            const unsigned long long sgn = 0ull - (unsigned long long)((h >> 15) & 1u);
-            unsigned long long* cell = reinterpret_cast<unsigned long long*>(lds_raw + off);
+            const bool live = i < rcnt;
+            const uint32_t h = hash_entry(prm.coef, rstart + (live ? i : 0), key, (uint32_t)prm.m);
+            const uint32_t bucket = live ? (h & 0x7fffu) : (h & (uint32_t)(kDummyCells - 1));
+            const uint32_t off = __umul24(bucket, stride_bytes) + rowbase[i];
+            const bool neg = (h & 0x8000u) != 0u;
+            if constexpr (CELL == kCellI64) {
+              unsigned long long* cell = reinterpret_cast<unsigned long long*>(lds_raw + off);
 #pragma unroll
-            for (int k = 0; k < KC; ++k) atomicAdd(cell + k, (nq[k] & sgn) | (q[k] & ~sgn));
-          }
-        }
-        if constexpr (SK && CELL == kCellF64) {
+              for (int k = 0; k < KC; ++k) atomicAdd(cell + k, neg ? nq[k] : q[k]);
+            } else {
+              double* cell = reinterpret_cast<double*>(lds_raw + off);
 #pragma unroll
-          for (int i = 0; i < LR; ++i) {
-            const uint32_t h = (v & 1) ? (t.tab[i][v >> 1] >> 16) : (t.tab[i][v >> 1] & 0xffffu);
-            const uint32_t off = __umul24(h & rowmask[i], stride_bytes) + rowbase[i];
-            const uint32_t sbit = (h & 0x8000u) << 16;                    // the float sign bit
-            double* cell = reinterpret_cast<double*>(lds_raw + off);
-#pragma unroll
-            for (int k = 0; k < KC; ++k)
-              atomicAdd(cell + k, (double)__uint_as_float(__float_as_uint(u[k]) ^ sbit));
+              for (int k = 0; k < KC; ++k) atomicAdd(cell + k, neg ? -(double)u[k] : (double)u[k]);
+            }
           }
         }
       }
@@ -500,18 +559,18 @@ state_kernel(const StateParams prm) {
       for (long long it = 1; it < nfast; ++it) {
         Tile nxt;
         load_fast(nxt, j0 + kTile);
-        consume(cur);
+        consume(cur, j0);
         cur = nxt;
         j0 += kTile;
       }
-      consume(cur);
+      consume(cur, j0);
       j0 += kTile;
     }
     // what is left: at most one ragged tile, or everything when vectors are not possible
     for (; j0 < cend; j0 += kTile) {
       Tile t;
       load_slow(t, j0);
-      consume(t);
+      consume(t, j0);
     }
   };
   if (scalars) {

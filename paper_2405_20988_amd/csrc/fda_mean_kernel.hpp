@@ -48,7 +48,7 @@ struct MeanParams {
   double* part_np;        // [P][3]: sum_k ||u_k||^2, sum_k <xi,u_k>, ||w_bar - w_t0||^2 of the partition
   void* part_sk;          // [P][l*m] 8-byte words: int64 (integer cells) or double (fp64 cells)
   ScaleInfo* scale;
-  const uint16_t* table;  // [l][dpad] tabulated hash
+  const uint16_t* table;  // [R][dpad] records of the tabulated hash, one field per row slot
   long long dpad;
 };
 
@@ -57,21 +57,22 @@ struct MeanBatch {
   static constexpr int kWords = kStateV * (int)sizeof(T) / 4;
   uint32_t w[KB][kWords];       // V elements of each of KB slab rows
 };
-template <int LR>
+template <int LR, int FB>
 struct MeanHead {
   float w0[kStateV];
   float x[kStateV];
-  uint32_t tab[LR][kStateV / 2];
+  uint32_t rec[RecGeom<LR, FB>::kDwords];      // the V records of the tabulated hash
 };
 
-template <typename T, int KB, int LR, int CELL>
+template <typename T, int KB, int LR, int CELL, int FB>
 __global__ void __launch_bounds__(kStateThreads)
 mean_state_kernel(const MeanParams prm) {
   static_assert(CELL == kCellI64 || CELL == kCellF64, "8-byte cells only");
   constexpr int V = kStateV;
   constexpr long long kTile = (long long)kStateThreads * V;
   using Batch = MeanBatch<T, KB>;
-  using Head = MeanHead<LR>;
+  using Geom = RecGeom<LR, FB>;
+  using Head = MeanHead<LR, FB>;
   extern __shared__ __align__(16) unsigned char lds_raw[];
   if constexpr (CELL == kCellF64) {
     if (prm.do_sk == 0 || prm.scale->flagm == 0) return;
@@ -106,15 +107,12 @@ mean_state_kernel(const MeanParams prm) {
   }
   __syncthreads();
 
-  const uint16_t* trow[LR];
-  uint32_t rowbase[LR], rowmask[LR];
+  // spare row slots: their table fields hold buckets below kDummyCells, sent to the dummy region
+  uint32_t rowbase[LR];
 #pragma unroll
-  for (int i = 0; i < LR; ++i) {
-    const bool live = i < rcnt;
-    trow[i] = prm.table + (size_t)(rstart + (live ? i : 0)) * prm.dpad;
-    rowbase[i] = live ? (uint32_t)(i * prm.m) * 8u : dummy_base;
-    rowmask[i] = live ? 0x7fffu : (uint32_t)(kDummyCells - 1);
-  }
+  for (int i = 0; i < LR; ++i) rowbase[i] = i < rcnt ? (uint32_t)(i * prm.m) * 8u : dummy_base;
+  const uint32_t* const recs =
+      reinterpret_cast<const uint32_t*>(prm.table + (size_t)r * prm.dpad * Geom::kWords);
 
   const long long cbeg = (long long)p * prm.chunk;
   long long cend = cbeg + prm.chunk;
@@ -182,14 +180,8 @@ mean_state_kernel(const MeanParams prm) {
       }
     };
     auto load_table = [&](Head& h, long long j0) {
-      if constexpr (SK) {
-        // the table is padded to dpad (a multiple of 64 coordinates): always a whole vector
-#pragma unroll
-        for (int i = 0; i < LR; ++i) {
-          const u32x2_a8 q = load_vec_hint<u32x2_a8, kNtShared>(trow[i] + j0);
-          h.tab[i][0] = q.x; h.tab[i][1] = q.y;
-        }
-      }
+      // the table is padded to dpad (a multiple of 64 coordinates): always whole records
+      if constexpr (SK) load_dwords<Geom::kDwords, kNtSlab>(recs + (j0 >> 1) * Geom::kWords, h.rec);
     };
     auto load_head_fast = [&](Head& h, long long j0) {
       load_f32_vec<V, kNtShared>(w0p + j0, h.w0);
@@ -263,16 +255,14 @@ mean_state_kernel(const MeanParams prm) {
         for (int v = 0; v < V; ++v) {
 #pragma unroll
           for (int i = 0; i < LR; ++i) {
-            const uint32_t hw = (v & 1) ? (h.tab[i][v >> 1] >> 16) : (h.tab[i][v >> 1] & 0xffffu);
-            const uint32_t off = ((hw & rowmask[i]) << 3) + rowbase[i];
+            const uint32_t hw = rec_field<LR, FB>(h.rec, v, i);
+            const uint32_t off = ((hw & Geom::kBucketMask) << 3) + rowbase[i];
+            const bool neg = (hw & (1u << (FB - 1))) != 0u;                // sign -1
             if constexpr (CELL == kCellI64) {
-              const unsigned long long sgn = 0ull - (unsigned long long)((hw >> 15) & 1u);
               const unsigned long long q = (unsigned long long)acc[v];
-              atomicAdd(reinterpret_cast<unsigned long long*>(lds_raw + off), (q ^ sgn) - sgn);
+              atomicAdd(reinterpret_cast<unsigned long long*>(lds_raw + off), neg ? 0ull - q : q);
             } else {
-              const unsigned long long sbit = (unsigned long long)(hw & 0x8000u) << 48;
-              atomicAdd(reinterpret_cast<double*>(lds_raw + off),
-                        __longlong_as_double(__double_as_longlong(us[v]) ^ (long long)sbit));
+              atomicAdd(reinterpret_cast<double*>(lds_raw + off), neg ? -us[v] : us[v]);
             }
           }
           acc[v] = 0; us[v] = 0.0;

@@ -11,14 +11,15 @@ constexpr int kMeanMaxLR = 8;                // sketch-row slots of one workgrou
 constexpr int kMeanBatchF32 = 4;             // slab rows per batch: 4 x 16 bytes per lane ...
 constexpr int kMeanBatchBF16 = 4;            // ... or 4 x 8 bytes
 
+// FB: bits per field of the tabulated hash (field_bits_for(m)): 11 or 16
 #define FDA_MEAN_LAUNCHER(t, c) \
-  hipError_t launch_mean_##t##_##c(int LR, const MeanParams* prm, size_t lds, hipStream_t st)
+  hipError_t launch_mean_##t##_##c(int LR, int FB, const MeanParams* prm, size_t lds, hipStream_t st)
 FDA_MEAN_LAUNCHER(f32, i64); FDA_MEAN_LAUNCHER(f32, f64);
 FDA_MEAN_LAUNCHER(bf16, i64); FDA_MEAN_LAUNCHER(bf16, f64);
 
-template <typename T, int KB, int LR, int CELL>
+template <typename T, int KB, int LR, int CELL, int FB>
 hipError_t launch_mean_kernel(const MeanParams* prm, size_t lds, hipStream_t st) {
-  auto kern = mean_state_kernel<T, KB, LR, CELL>;
+  auto kern = mean_state_kernel<T, KB, LR, CELL, FB>;
   if (prm == nullptr)
     return hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);

@@ -15,50 +15,36 @@
 
 namespace fda {
 
-// ---- arithmetic modulo the Mersenne prime 2^31 - 1 (operands already reduced) --------
-__device__ __forceinline__ uint32_t addmod(uint32_t a, uint32_t b) {
-  uint32_t s = a + b;                        // < 2^32
-  return min(s, s - kPrime);                 // s - p wraps to a huge value when s < p
-}
-__device__ __forceinline__ uint32_t mulmod(uint32_t a, uint32_t b) {
-  uint64_t t = (uint64_t)a * b;              // < 2^62
-  uint32_t lo = (uint32_t)t & kPrime;
-  uint32_t hi = (uint32_t)(t >> 31);         // 2^31 = 1 (mod p)
-  uint32_t s = lo + hi;                      // <= 2p - 1
-  return min(s, s - kPrime);
-}
-// c[3] j^3 + c[2] j^2 + c[1] j + c[0] mod p
-__device__ __forceinline__ uint32_t poly3(const uint32_t* c, uint32_t j) {
-  uint32_t g = c[3];
-  g = addmod(mulmod(g, j), c[2]);
-  g = addmod(mulmod(g, j), c[1]);
-  g = addmod(mulmod(g, j), c[0]);
-  return g;
-}
-
-// ---- the hash, tabulated once per context: [row][dpad] 16-bit words, bits 0..14 bucket,
-// bit 15 set for sign -1 (Section 3.1 sketch; hash family: two cubics mod 2^31 - 1 per row)
+// ---- the hash, tabulated once per context (Section 3.1 sketch; hash family: two cubics mod 2^31 - 1
+// per row).  Layout [row group r][coordinate j] records of `words` 16-bit words; a record packs,
+// lowest bits first, one field of `fb` bits per row slot of the group: bucket in the low fb-1 bits,
+// top bit set for sign -1.  Slots past the group's last row (and whole records past d) hold a bucket
+// below kDummyCells and sign +: the state kernels send those additions to a dummy region.
+// One thread writes the 4 records a lane of the state kernels loads together.
 __global__ void __launch_bounds__(kSmallThreads)
-hash_table_kernel(const HashCoef hc, int m, long long d, long long dpad,
-                  uint16_t* __restrict__ table) {
-  const int i = blockIdx.y;
-  const long long j8 = ((long long)blockIdx.x * blockDim.x + threadIdx.x) * 8;
-  if (j8 >= dpad) return;
-  uint32_t h[8];
-#pragma unroll
-  for (int q = 0; q < 8; ++q) {
-    const long long j = j8 + q;
-    h[q] = 0u;
-    if (j < d) {
-      const uint32_t gb = poly3(hc.c[i][0], (uint32_t)j);
-      const uint32_t gs = poly3(hc.c[i][1], (uint32_t)j);
-      h[q] = __umulhi(gb << 1, (uint32_t)m) | ((gs & 1u) << 15);   // floor(gb*m/2^31); odd -> -1
+hash_table_kernel(const HashCoef hc, int l, int R, int slots, int m, int fb, int words, long long d,
+                  long long dpad, uint16_t* __restrict__ table) {
+  const int r = blockIdx.y;
+  const long long j4 = ((long long)blockIdx.x * blockDim.x + threadIdx.x) * 4;
+  if (j4 >= dpad) return;
+  int rstart, rcnt;
+  group_range(l, R, r, &rstart, &rcnt);
+  uint16_t* out = table + ((size_t)r * dpad + j4) * words;
+  for (int q = 0; q < 4; ++q) {
+    const long long j = j4 + q;
+    unsigned long long bits[3] = {0ull, 0ull, 0ull};          // slots * fb <= 8 * 16 bits
+    for (int i = 0; i < slots; ++i) {
+      unsigned long long f = (unsigned long long)((uint32_t)(j + 17 * i) & (uint32_t)(kDummyCells - 1));
+      if (i < rcnt && j < d) {
+        const uint32_t h = hash_entry(hc, rstart + i, (uint32_t)j, (uint32_t)m);
+        f = (unsigned long long)(h & 0x7fffu) | ((unsigned long long)(h >> 15) << (fb - 1));
+      }
+      const int pos = i * fb, idx = pos >> 6, sh = pos & 63;
+      bits[idx] |= f << sh;
+      if (sh + fb > 64) bits[idx + 1] |= f >> (64 - sh);
     }
+    for (int t = 0; t < words; ++t) out[q * words + t] = (uint16_t)(bits[t >> 2] >> (16 * (t & 3)));
   }
-  uint4 o;
-  o.x = h[0] | (h[1] << 16); o.y = h[2] | (h[3] << 16);
-  o.z = h[4] | (h[5] << 16); o.w = h[6] | (h[7] << 16);
-  *reinterpret_cast<uint4*>(table + (size_t)i * dpad + j8) = o;
 }
 
 // ---- how many coordinates can meet in one cell of one workgroup ------------------------
@@ -77,10 +63,8 @@ cell_count_kernel(const HashCoef hc, int l, int m, long long d, long long chunk,
   const long long cbeg = (long long)p * chunk;
   long long cend = cbeg + chunk;
   if (cend > d) cend = d;
-  for (long long j = cbeg + threadIdx.x; j < cend; j += kStateThreads) {
-    const uint32_t gb = poly3(hc.c[i][0], (uint32_t)j);
-    atomicAdd(cnt + __umulhi(gb << 1, (uint32_t)m), 1u);
-  }
+  for (long long j = cbeg + threadIdx.x; j < cend; j += kStateThreads)
+    atomicAdd(cnt + (hash_entry(hc, i, (uint32_t)j, (uint32_t)m) & 0x7fffu), 1u);
   __syncthreads();
   unsigned int mx = 0u;
   for (int t = threadIdx.x; t < m; t += kStateThreads) mx = max(mx, cnt[t]);

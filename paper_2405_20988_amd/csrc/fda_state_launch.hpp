@@ -18,8 +18,9 @@ constexpr int kMaxSlots = 32;
 constexpr int kWideKCSet[] = {1, 2, 4};
 constexpr int kWideLRSet[] = {1, 2, 4, 8};
 
+// FB: bits per field of the tabulated hash (field_bits_for(m)): 11 or 16
 #define FDA_NARROW_LAUNCHER(t, kc) \
-  hipError_t launch_narrow_##t##_kc##kc(int LR, const StateParams* prm, size_t lds, hipStream_t st)
+  hipError_t launch_narrow_##t##_kc##kc(int LR, int FB, const StateParams* prm, size_t lds, hipStream_t st)
 #define FDA_WIDE_LAUNCHER(t, c) \
   hipError_t launch_wide_##t##_##c(int KC, int LR, const StateParams* prm, size_t lds, hipStream_t st)
 FDA_NARROW_LAUNCHER(f32, 1); FDA_NARROW_LAUNCHER(f32, 2); FDA_NARROW_LAUNCHER(f32, 3);
@@ -31,9 +32,9 @@ FDA_NARROW_LAUNCHER(bf16, 8);
 FDA_WIDE_LAUNCHER(f32, i64); FDA_WIDE_LAUNCHER(f32, f64);
 FDA_WIDE_LAUNCHER(bf16, i64); FDA_WIDE_LAUNCHER(bf16, f64);
 
-template <typename T, int KC, int LR, int CELL>
+template <typename T, int KC, int LR, int CELL, int FB>
 hipError_t launch_state_kernel(const StateParams* prm, size_t lds, hipStream_t st) {
-  auto kern = state_kernel<T, KC, LR, CELL>;
+  auto kern = state_kernel<T, KC, LR, CELL, FB>;
   if (prm == nullptr)
     return hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
