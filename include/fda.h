@@ -160,8 +160,13 @@ int fda_get_plan(const fda_ctx* ctx, fda_plan_info* out);
  * Pointers need the alignment of their element type only (2 bytes for a bf16 slab, 4 for everything
  * fp32; anything less is FDA_EINVAL): whole-vector loads are used for any d and any row_stride.
  * Sketch cells are accumulated as integers (a drift u enters as round(u * 2^e), 2^e chosen
- * per call so that the rounding is at most 2^-19 of the mean |u|), and everything across
- * workgroups is merged in a fixed order: the state is bit-identical from run to run.
+ * per call so that the rounding is at most 2^-18 of the mean |u|), and everything across
+ * workgroups is merged in a fixed order: with the integer cells (fda_last_state_path 0 or 1) the
+ * state is bit-identical from run to run; the fp64 cells of the last fallback (path 2, and path 1
+ * of fda_mean_state) add in the order the lanes arrive and are not.
+ * The pass works on drifts scaled by that 2^e, so a single drift 2^45 times the mean magnitude or
+ * more makes ||u_k||^2 overflow to infinity (reported as a non-finite estimate) where the plain
+ * fp32 square would overflow only at 2^64.
  * The first call of a context also tabulates the hash (2*l*d bytes of the workspace).
  */
 int fda_local_state(fda_ctx* ctx, const void* w, const float* w_t0, const float* xi,

@@ -299,8 +299,9 @@ __device__ __forceinline__ float raw_elem(const uint32_t (&r)[2], int v) {      
 // So the cells are integers and a drift u is added as round(u * 2^e), with 2^e chosen per call
 // from a sample of the drifts (scale_kernel).  Integer addition is exact: the result
 // does not depend on the order in which lanes and workgroups add, run-to-run bit-identical.
-//   kCellI32  32-bit cells, started at 2^31; every add is below 2^30 in magnitude and returns
-//             the old value, which must lie in [2^30, 3*2^30): then no add can have wrapped.
+//   kCellI32  32-bit cells holding sum + 2^30; every add is below 2^30 in magnitude and returns
+//             the old value, which must lie in [0, 2^31) -- top bit clear, i.e. the sum so far in
+//             [-2^30, 2^30): then no add can have wrapped.
 //             The mean sampled |u| maps to about 2^18.  Runs on every call and also produces
 //             the scalar components.  A value outside the band, or a drift at or above
 //             ScaleInfo::bound32, raises ScaleInfo::flag32.
@@ -310,6 +311,16 @@ __device__ __forceinline__ float raw_elem(const uint32_t (&r)[2], int v) {      
 //             ScaleInfo::overflow64 (noticed by the first pass, which sees every drift).
 //   kCellF64  fp64 cells (ds_add_f64), sketch only, runs only when overflow64 is set.
 // ----------------------------------------------------------------------------------------
+constexpr uint32_t kCellBias = 0x40000000u;   // a 32-bit cell holds its sum plus 2^30
+
+// floor(x + 0.5) as an integer in one instruction (|x| < 2^31): the fixed-point term of a scaled drift,
+// at most half a unit from it
+__device__ __forceinline__ int round_half_up(float x) {
+  int q;
+  asm("v_cvt_rpi_i32_f32 %0, %1" : "=v"(q) : "v"(x));
+  return q;
+}
+
 template <typename T, int KC, int LR, int CELL, int FB>
 __global__ void __launch_bounds__(kStateThreads)
 state_kernel(const StateParams prm) {
@@ -359,7 +370,7 @@ state_kernel(const StateParams prm) {
   const int tid = threadIdx.x;
   if constexpr (CELL == kCellI32) {
     uint32_t* c32 = reinterpret_cast<uint32_t*>(lds_raw);
-    for (int t = tid; t < lds_cells; t += kStateThreads) c32[t] = 0x80000000u;   // mid-range
+    for (int t = tid; t < lds_cells; t += kStateThreads) c32[t] = kCellBias;     // sum 0
   } else {
     unsigned long long* c64 = reinterpret_cast<unsigned long long*>(lds_raw);
     for (int t = tid; t < lds_cells; t += kStateThreads) c64[t] = 0ull;         // integer 0 and 0.0
@@ -395,7 +406,7 @@ state_kernel(const StateParams prm) {
 
   double S64 = 1.0;
   float S32 = 1.0f, amax = 0.0f;
-  uint32_t seen_lo = 0x80000000u, seen_hi = 0x80000000u;   // range of the 32-bit cell values this lane's adds returned
+  uint32_t seen_or = 0u;            // OR of every 32-bit cell value this lane's adds returned
   if (prm.do_sk) { S64 = prm.scale->S64; S32 = prm.scale->S32; }
 
   // SC: this workgroup also produces the scalar components; SK: it accumulates sketch rows.
@@ -458,10 +469,16 @@ state_kernel(const StateParams prm) {
       bool have_pending = false;
 #pragma unroll
       for (int v = 0; v < V; ++v) {
+        // The 32-bit-cell pass works on u * S32 throughout: S32 is a power of two, so
+        // fma(w, S32, -w_t0 * S32) is exactly (w - w_t0 as fp32 rounds it) * S32, the scalar
+        // sums come out multiplied by S32^2 and S32 (undone exactly at the end), and the
+        // fixed-point term is one conversion away.  (The fallback passes keep the plain drift.)
         float u[KC];
+        const float w0s = (CELL == kCellI32) ? t.w0[v] * S32 : t.w0[v];
 #pragma unroll
         for (int k = 0; k < KC; ++k) {
-          u[k] = raw_elem(t.w[k], v) - t.w0[v];
+          if constexpr (CELL == kCellI32) u[k] = fmaf(raw_elem(t.w[k], v), S32, -w0s);
+          else u[k] = raw_elem(t.w[k], v) - w0s;
           if constexpr (SC) {
             sn[k] = fmaf(u[k], u[k], sn[k]);
             sp[k] = fmaf(t.x[v], u[k], sp[k]);
@@ -472,7 +489,7 @@ state_kernel(const StateParams prm) {
           uint32_t q[KC], nq[KC];
 #pragma unroll
           for (int k = 0; k < KC; ++k) {
-            q[k] = (uint32_t)(int)rintf(u[k] * S32);
+            q[k] = (uint32_t)round_half_up(u[k]);
             nq[k] = 0u - q[k];
           }
 #pragma unroll
@@ -484,18 +501,16 @@ state_kernel(const StateParams prm) {
             uint32_t old[KC];
 #pragma unroll
             for (int k = 0; k < KC; ++k) old[k] = atomicAdd(cell + k, neg ? nq[k] : q[k]);
-            // Every add is below 2^30 in magnitude (ScaleInfo::bound32), so a cell cannot wrap
-            // in an add that found it inside [2^30, 3*2^30): if every value ever returned was
-            // inside that band, no cell wrapped.  Only the smallest and the largest returned value
-            // are kept (three-operand min / max: one instruction per add).  The values of the row
-            // before are examined only now, with this row's adds already on their way, so the
-            // LDS round trip hides behind the next batch.
+            // Every add is below 2^30 in magnitude (ScaleInfo::bound32) and a cell holds its sum
+            // plus 2^30, so a cell cannot wrap in an add that found it below 2^31 (sum so far in
+            // [-2^30, 2^30)): if the top bit of every value ever returned was clear, no cell
+            // wrapped.  The returned values are OR-ed together (a three-operand OR takes two of
+            // them: half an instruction per add).  The values of the row before are examined only
+            // now, with this row's adds already on their way, so the LDS round trip hides behind
+            // the next batch.
             if (have_pending) {
 #pragma unroll
-              for (int k = 0; k < KC; ++k) {
-                seen_lo = min(seen_lo, pend_old[k]);
-                seen_hi = max(seen_hi, pend_old[k]);
-              }
+              for (int k = 0; k < KC; ++k) seen_or |= pend_old[k];
             }
 #pragma unroll
             for (int k = 0; k < KC; ++k) pend_old[k] = old[k];
@@ -537,10 +552,7 @@ state_kernel(const StateParams prm) {
       if constexpr (SK && CELL == kCellI32) {
         if (have_pending) {
 #pragma unroll
-          for (int k = 0; k < KC; ++k) {
-            seen_lo = min(seen_lo, pend_old[k]);
-            seen_hi = max(seen_hi, pend_old[k]);
-          }
+          for (int k = 0; k < KC; ++k) seen_or |= pend_old[k];
         }
       }
       if constexpr (SC) {
@@ -585,12 +597,13 @@ state_kernel(const StateParams prm) {
       if (scalars) {
         // drifts the integer cells cannot hold (any drift at all when the sample saw none)
         const float b32 = prm.scale->bound32, b64 = prm.scale->bound64;
+        amax = amax * (1.0f / S32);              // back to the drift's own unit (exact: a power of two)
         const bool bad32 = b32 > 0.0f ? !(amax < b32) : (amax > 0.0f);
         const bool bad64 = b64 > 0.0f ? !(amax < b64) : (amax > 0.0f);
         if (bad32 || bad64) prm.scale->flag32 = 1;
         if (bad64) prm.scale->overflow64 = 1;
       }
-      if (seen_lo < 0x40000000u || seen_hi >= 0xC0000000u) prm.scale->flag32 = 1;
+      if ((seen_or & 0x80000000u) != 0u) prm.scale->flag32 = 1;
     }
   }
 
@@ -611,7 +624,9 @@ state_kernel(const StateParams prm) {
     double s = 0.0;
     for (int wv = 0; wv < kWaves; ++wv) s += red[(wv * KC + k) * 2 + q];
     if (q == 1 && !lin) s = 0.0;               // no LinearFDA: the projection slot stays zero
-    prm.part_np[((size_t)p * prm.K + kstart + k) * 2 + q] = s;
+    // the sums were formed on drifts scaled by S32 (a power of two: exact to undo)
+    const double inv = 1.0 / (double)S32;
+    prm.part_np[((size_t)p * prm.K + kstart + k) * 2 + q] = s * (q == 0 ? inv * inv : inv);
   }
   // ---- flush the LDS sketch to this workgroup's slice of the partial buffer -----------
   if (sketch) {
@@ -621,7 +636,7 @@ state_kernel(const StateParams prm) {
       const int k = t / cells, c = t - k * cells;
       unsigned long long val;
       if constexpr (CELL == kCellI32)
-        val = (unsigned long long)(long long)(int)(reinterpret_cast<const uint32_t*>(lds_raw)[(size_t)c * prm.stride + k] - 0x80000000u);
+        val = (unsigned long long)(long long)(int)(reinterpret_cast<const uint32_t*>(lds_raw)[(size_t)c * prm.stride + k] - kCellBias);
       else
         val = reinterpret_cast<const unsigned long long*>(lds_raw)[(size_t)c * prm.stride + k];
       out[((size_t)p * prm.K + kstart + k) * allcells + (size_t)rstart * prm.m + c] = val;
