@@ -96,7 +96,11 @@ typedef struct fda_estimate {
   int32_t near_tie_linear;  /* 1 iff |h_linear - theta| <= tie_tol * max(mean_sqnorm,|theta|) */
   int32_t near_tie_sketch;  /* same for h_sketch                                            */
   int32_t nonfinite;        /* 1 iff a requested estimate is NaN or infinite                */
-  int32_t reserved;
+  int32_t state_path;       /* which kind of sketch cell the context's last state pass ended up
+                               using, read on the device when the estimate ran (no stream wait):
+                               after fda_local_state 0 / 1 / 2 as fda_last_state_path reports,
+                               after fda_mean_state 0 / 1 as fda_last_mean_state_path reports;
+                               -1 without a sketch and from fda_estimate_variance_static          */
 } fda_estimate;
 
 /* How the state pass is laid out on the chip; filled by fda_plan (for inspection and for

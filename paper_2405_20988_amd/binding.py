@@ -39,10 +39,10 @@ class FdaEstimate(C.Structure):
                 ("h_linear", C.c_double), ("h_sketch", C.c_double),
                 ("sync_linear", C.c_int32), ("sync_sketch", C.c_int32),
                 ("near_tie_linear", C.c_int32), ("near_tie_sketch", C.c_int32),
-                ("nonfinite", C.c_int32), ("reserved", C.c_int32)]
+                ("nonfinite", C.c_int32), ("state_path", C.c_int32)]
 
     def as_dict(self) -> dict:
-        return {name: getattr(self, name) for name, _ in self._fields_ if name != "reserved"}
+        return {name: getattr(self, name) for name, _ in self._fields_}
 
 
 class FdaPlanInfo(C.Structure):

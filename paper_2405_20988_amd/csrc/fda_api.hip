@@ -394,6 +394,12 @@ int clear_tickets_once(fda_ctx* c, hipStream_t st) {
   hipLaunchKernelGGL(fda::clear_u32_kernel, dim3(1), dim3(64), 0, st,
                      reinterpret_cast<unsigned int*>(c->ws + c->plan.off_ticket), 2);
   FDA_HIP(hipGetLastError());
+  // ... and so are the two scale records, whose flags an estimate may report before any state pass ran
+  static_assert(2 * sizeof(fda::ScaleInfo) <= 64 * 4, "clear_u32_kernel clears at most 64 words");
+  hipLaunchKernelGGL(fda::clear_u32_kernel, dim3(1), dim3(64), 0, st,
+                     reinterpret_cast<unsigned int*>(c->ws + c->plan.off_scale),
+                     (int)(2 * sizeof(fda::ScaleInfo) / 4));
+  FDA_HIP(hipGetLastError());
   c->tickets_cleared = true;
   return FDA_OK;
 }
@@ -808,7 +814,7 @@ int fda_mean_state(fda_ctx* ctx, const void* w, const float* w_t0, const float* 
   return FDA_OK;
 }
 
-static int estimate_rows(fda_ctx* ctx, const float* state, int rows, double theta, double tie_tol,
+static int estimate_rows(fda_ctx* ctx, const float* state, int rows, int mean_mode, double theta, double tie_tol,
                          fda_estimate* out_dev, fda_estimate* out_host, void* stream) {
   if (ctx == nullptr || state == nullptr || out_dev == nullptr)
     return fail(FDA_EINVAL, "NULL argument");
@@ -823,10 +829,13 @@ static int estimate_rows(fda_ctx* ctx, const float* state, int rows, double thet
   const int eblocks = sk ? d.l * bpr : 1;
   int rc = clear_tickets_once(ctx, st);
   if (rc != FDA_OK) return rc;
+  const fda::ScaleInfo* scale =
+      reinterpret_cast<const fda::ScaleInfo*>(ctx->ws + ctx->plan.off_scale) + (mean_mode ? 1 : 0);
   hipLaunchKernelGGL(fda::estimate_kernel, dim3(eblocks), dim3(fda::kSmallThreads), 0, st, state, rows,
                      sk ? d.l : 0, sk ? d.m : 1, d.variants, d.eps, theta, tie_tol,
                      reinterpret_cast<double*>(ctx->ws + ctx->plan.off_est),
-                     reinterpret_cast<unsigned int*>(ctx->ws + ctx->plan.off_ticket) + 1, out_dev);
+                     reinterpret_cast<unsigned int*>(ctx->ws + ctx->plan.off_ticket) + 1, scale, mean_mode,
+                     out_dev);
   FDA_HIP(hipGetLastError());
   if (out_host != nullptr) {
     FDA_HIP(hipMemcpyAsync(out_host, out_dev, sizeof(fda_estimate), hipMemcpyDeviceToHost, st));
@@ -837,12 +846,12 @@ static int estimate_rows(fda_ctx* ctx, const float* state, int rows, double thet
 
 int fda_estimate_variance(fda_ctx* ctx, const float* state, double theta, double tie_tol,
                           fda_estimate* out_dev, fda_estimate* out_host, void* stream) {
-  return estimate_rows(ctx, state, ctx ? ctx->desc.K : 0, theta, tie_tol, out_dev, out_host, stream);
+  return estimate_rows(ctx, state, ctx ? ctx->desc.K : 0, 0, theta, tie_tol, out_dev, out_host, stream);
 }
 
 int fda_estimate_variance_mean(fda_ctx* ctx, const float* mean_state, double theta, double tie_tol,
                                fda_estimate* out_dev, fda_estimate* out_host, void* stream) {
-  return estimate_rows(ctx, mean_state, 1, theta, tie_tol, out_dev, out_host, stream);
+  return estimate_rows(ctx, mean_state, 1, 1, theta, tie_tol, out_dev, out_host, stream);
 }
 
 int fda_estimate_variance_static(const float* state, int32_t K, int32_t l, int32_t m, int32_t variants,
@@ -877,7 +886,8 @@ int fda_estimate_variance_static(const float* state, int32_t K, int32_t l, int32
   FDA_HIP(hipGetLastError());
   hipLaunchKernelGGL(fda::estimate_kernel, dim3(eblocks), dim3(fda::kSmallThreads), 0, st, state, K,
                      sk ? l : 0, sk ? m : 1, variants, eps, theta, tie_tol,
-                     reinterpret_cast<double*>(base), ticket, out_dev);
+                     reinterpret_cast<double*>(base), ticket, static_cast<const fda::ScaleInfo*>(nullptr), 0,
+                     out_dev);
   FDA_HIP(hipGetLastError());
   return FDA_OK;
 }

@@ -213,7 +213,7 @@ mean_state_kernel(const MeanParams prm) {
             amax = fmaxf(amax, fabsf(u));
             um[v] += u;
           }
-          if constexpr (SK && CELL == kCellI64) acc[v] += (long long)(int)rintf(u * Sm);
+          if constexpr (SK && CELL == kCellI64) acc[v] += (long long)round_half_up(u * Sm);
           if constexpr (SK && CELL == kCellF64) us[v] += (double)u;
         }
       }

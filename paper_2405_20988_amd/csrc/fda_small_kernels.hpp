@@ -313,7 +313,7 @@ constexpr int kEstCols = kSmallThreads;      // cells per workgroup
 __global__ void __launch_bounds__(kSmallThreads)
 estimate_kernel(const float* __restrict__ state, int K, int l, int m, int variants, double eps,
                 double theta, double tie_tol, double* __restrict__ part, unsigned int* __restrict__ ticket,
-                fda_estimate* __restrict__ out) {
+                const ScaleInfo* __restrict__ scale, int mean_mode, fda_estimate* __restrict__ out) {
   __shared__ double scratch[kSmallThreads / 64];
   __shared__ int last;
   const int cells = (variants & FDA_VARIANT_SKETCH) ? l * m : 0;
@@ -356,7 +356,11 @@ estimate_kernel(const float* __restrict__ state, int K, int l, int m, int varian
   e.mean_sqnorm = vpart[0] / (double)K;
   e.mean_proj = 0.0; e.m2 = 0.0; e.h_linear = 0.0; e.h_sketch = 0.0;
   e.sync_linear = 0; e.sync_sketch = 0; e.near_tie_linear = 0; e.near_tie_sketch = 0;
-  e.nonfinite = 0; e.reserved = 0;
+  e.nonfinite = 0;
+  // which kind of sketch cell the last state pass used (scale: its record, or NULL)
+  e.state_path = -1;
+  if (cells && scale != nullptr)
+    e.state_path = mean_mode ? (scale->flagm ? 1 : 0) : (scale->overflow64 ? 2 : (scale->flag32 ? 1 : 0));
   const double band = tie_tol * fmax(e.mean_sqnorm, fabs(theta));
   if (variants & FDA_VARIANT_LINEAR) {
     e.mean_proj = vpart[1] / (double)K;

@@ -168,6 +168,7 @@ def test_mean_state_equals_average_of_local_states():
         nb, pb, skb = mon.mean_numpy()
         e2 = mon.estimate_variance_mean(1e-9)
         assert mon.last_state_path() == 0 and mon.last_mean_state_path() == 0
+        assert mon.estimate_variance_mean(1e30).state_path == 0
         assert nb == pytest.approx(n.astype(np.float64).mean(), rel=1e-6)
         w32 = wl.w.float() if wl.dtype == "bf16" else wl.w
         p_abs = float(((w32 - wl.w_t0).abs() * wl.xi.abs()).sum(dim=1).double().mean())

@@ -526,6 +526,7 @@ def test_drifts_outside_the_sampled_range(dtype):
         # (with a bf16 slab the rounding residue narrows the range: which of the two wider kinds
         # takes over there depends on what the sample of the scale happens to see)
         assert mon.last_state_path() >= 1
+        assert mon.estimate_variance(1e30).state_path == mon.last_state_path()
         if dtype == "f32" and kind == "spikes":
             assert mon.last_state_path() == 2
         mon.close()
@@ -544,6 +545,7 @@ def test_sketch_cell_paths():
     mon = monitor_for(wl)
     mon.local_state(wl.w, wl.w_t0, wl.xi)
     assert mon.last_state_path() == 0
+    assert mon.estimate_variance(1e30).state_path == 0          # the same, reported without a stream wait
     check_state(mon, oracle_state(wl))
     mon.close()
     # (b) two drifts per worker 8000 times the mean, every coordinate sampled
@@ -558,6 +560,7 @@ def test_sketch_cell_paths():
     mon = F.FdaMonitor(K, d, "f32", 3, l, m, 0.06, coef, device=DEV)
     mon.local_state(u, w_t0, xi)
     assert mon.last_state_path() == 1
+    assert mon.estimate_variance(1e30).state_path == 1
     check_state(mon, O.local_state(u.cpu().numpy(), "f32", w_t0.cpu().numpy(), xi.cpu().numpy(), coef, m))
     mon.close()
     # (c) every coordinate in one bucket with one sign and equal positive drifts: the cell of a
