@@ -223,7 +223,8 @@ int fda_estimate_variance_mean(fda_ctx* ctx, const float* mean_state, double the
 /*
  * fda_estimate_variance for callers that cannot allocate and hold no context: code under HIP graph
  * capture, tight serving loops, harnesses that forbid hipMalloc.  Same kernel and same result as
- * fda_estimate_variance (out_dev is written bit for bit the same), but the per-workgroup partial sums
+ * fda_estimate_variance (out_dev is written bit for bit the same, except state_path = -1: there is
+ * no context whose last state pass could be reported), but the per-workgroup partial sums
  * and the finished-workgroup counter live in a static device array of the library (17 KiB per GPU,
  * held until the process ends) instead of a context's workspace.  Calls no hipMalloc / hipFree and no
  * allocating library routine, creates no events, never waits; enqueues a one-workgroup fill kernel
