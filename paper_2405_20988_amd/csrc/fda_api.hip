@@ -248,7 +248,7 @@ int make_plan(const fda_desc* d, int cus, int64_t lds_cu, Plan* pl) {
   pl->off_est = round_up(pl->off_dnorm + 8, kAlign);
   pl->off_ticket = round_up(pl->off_est + (2 + (int64_t)FDA_MAX_SKETCH_ROWS * kMaxEstBlocksPerRow) * 8, kAlign);
   pl->off_table = round_up(pl->off_ticket + 8, kAlign);
-  pl->dpad = round_up(d->d, 64);
+  pl->dpad = round_up(d->d, fda::kRecBlockCoords);      // the table comes in whole blocks
   // the tabulated hash: per row group one record per coordinate with a field per row slot
   pl->fb = fda::field_bits_for(sk ? d->m : 1);
   pl->words = (pl->narrow.LR * pl->fb + 15) / 16;

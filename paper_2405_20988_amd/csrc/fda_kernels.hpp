@@ -234,20 +234,27 @@ struct RecGeom {
   static constexpr int kDwords = 2 * kWords;                // dwords of a lane's 4 consecutive records
   static constexpr uint32_t kBucketMask = (1u << (FB - 1)) - 1u;
 };
-// N dwords from p (4-byte aligned at least), in the widest pieces
+// The table is stored in blocks of 256 coordinates: the share of one wave of one tile (64 lanes x 4
+// consecutive coordinates).  A lane's 4 records are N = RecGeom::kDwords dwords, which it loads in the
+// widest pieces: N / 4 of 16 bytes, then one of 8, then one of 4.  Inside a block the dwords are laid
+// out piece by piece, lane after lane within a piece, so every load instruction of the wave reads one
+// dense run of 64 x 16 (8, 4) bytes.  (Records laid one after the other would make each instruction
+// touch every line of the block for a part of its bytes.)
+constexpr int kRecBlockCoords = 256;
+// the N dwords of `lane` from the block starting at blk (16-byte aligned)
 template <int N, bool NT>
-__device__ __forceinline__ void load_dwords(const uint32_t* p, uint32_t (&out)[N]) {
+__device__ __forceinline__ void load_rec_block(const uint32_t* blk, int lane, uint32_t (&out)[N]) {
   constexpr int n4 = N / 4, n2 = (N % 4) / 2, n1 = N % 2;
 #pragma unroll
   for (int q = 0; q < n4; ++q) {
-    const u32x4 t = load_vec_hint<u32x4, NT>(p + 4 * q);
+    const u32x4 t = load_vec_hint<u32x4, NT>(blk + (q * 64 + lane) * 4);
     out[4 * q] = t.x; out[4 * q + 1] = t.y; out[4 * q + 2] = t.z; out[4 * q + 3] = t.w;
   }
   if constexpr (n2 == 1) {
-    const u32x2 t = load_vec_hint<u32x2, NT>(p + 4 * n4);
+    const u32x2 t = load_vec_hint<u32x2, NT>(blk + n4 * 256 + lane * 2);
     out[4 * n4] = t.x; out[4 * n4 + 1] = t.y;
   }
-  if constexpr (n1 == 1) out[N - 1] = load_vec_hint<uint32_t, NT>(p + N - 1);
+  if constexpr (n1 == 1) out[N - 1] = load_vec_hint<uint32_t, NT>(blk + n4 * 256 + n2 * 128 + lane);
 }
 // the FB-bit field of sketch-row slot i of the lane's coordinate v (both known after unrolling:
 // word index and shift fold to constants); bits above FB are garbage, callers mask
@@ -429,7 +436,7 @@ state_kernel(const StateParams prm) {
         }
       }
       if constexpr (SK && kTabulated)
-        load_dwords<Geom::kDwords, kNtShared>(recs + (j0 >> 1) * Geom::kWords, t.rec);
+        load_rec_block<Geom::kDwords, kNtShared>(recs + (j0 >> 8) * (64 * Geom::kDwords), (int)(j0 >> 2) & 63, t.rec);
     };
     // element by element, every access tested: ragged tails and slabs without dword alignment
     auto load_slow = [&](Tile& t, long long j0) {
@@ -456,9 +463,9 @@ state_kernel(const StateParams prm) {
           }
         }
       }
-      // the table is padded to dpad (a multiple of 64 coordinates): always whole records
+      // the table is padded to dpad (whole blocks of 256 coordinates): always whole records
       if constexpr (SK && kTabulated)
-        load_dwords<Geom::kDwords, false>(recs + (j0 >> 1) * Geom::kWords, t.rec);
+        load_rec_block<Geom::kDwords, false>(recs + (j0 >> 8) * (64 * Geom::kDwords), (int)(j0 >> 2) & 63, t.rec);
     };
 
     auto consume = [&](const Tile& t, long long j0) {

@@ -180,8 +180,9 @@ mean_state_kernel(const MeanParams prm) {
       }
     };
     auto load_table = [&](Head& h, long long j0) {
-      // the table is padded to dpad (a multiple of 64 coordinates): always whole records
-      if constexpr (SK) load_dwords<Geom::kDwords, kNtSlab>(recs + (j0 >> 1) * Geom::kWords, h.rec);
+      // the table is padded to dpad (whole blocks of 256 coordinates): always whole records
+      if constexpr (SK)
+        load_rec_block<Geom::kDwords, kNtSlab>(recs + (j0 >> 8) * (64 * Geom::kDwords), (int)(j0 >> 2) & 63, h.rec);
     };
     auto load_head_fast = [&](Head& h, long long j0) {
       load_f32_vec<V, kNtShared>(w0p + j0, h.w0);

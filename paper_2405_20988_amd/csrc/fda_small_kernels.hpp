@@ -16,11 +16,13 @@
 namespace fda {
 
 // ---- the hash, tabulated once per context (Section 3.1 sketch; hash family: two cubics mod 2^31 - 1
-// per row).  Layout [row group r][coordinate j] records of `words` 16-bit words; a record packs,
+// per row).  Per row group r and coordinate j one record of `words` 16-bit words; a record packs,
 // lowest bits first, one field of `fb` bits per row slot of the group: bucket in the low fb-1 bits,
 // top bit set for sign -1.  Slots past the group's last row (and whole records past d) hold a bucket
 // below kDummyCells and sign +: the state kernels send those additions to a dummy region.
-// One thread writes the 4 records a lane of the state kernels loads together.
+// Layout [row group][block of 256 coordinates][dwords in load order]: the 2 * words dwords of the 4
+// records that a lane of the state kernels loads together are placed where load_rec_block() reads
+// them.  One thread writes one lane's share.
 __global__ void __launch_bounds__(kSmallThreads)
 hash_table_kernel(const HashCoef hc, int l, int R, int slots, int m, int fb, int words, long long d,
                   long long dpad, uint16_t* __restrict__ table) {
@@ -29,7 +31,8 @@ hash_table_kernel(const HashCoef hc, int l, int R, int slots, int m, int fb, int
   if (j4 >= dpad) return;
   int rstart, rcnt;
   group_range(l, R, r, &rstart, &rcnt);
-  uint16_t* out = table + ((size_t)r * dpad + j4) * words;
+  uint32_t dw[16];                                             // 4 records of at most 8 words
+  for (int t = 0; t < 16; ++t) dw[t] = 0u;
   for (int q = 0; q < 4; ++q) {
     const long long j = j4 + q;
     unsigned long long bits[3] = {0ull, 0ull, 0ull};          // slots * fb <= 8 * 16 bits
@@ -43,7 +46,22 @@ hash_table_kernel(const HashCoef hc, int l, int R, int slots, int m, int fb, int
       bits[idx] |= f << sh;
       if (sh + fb > 64) bits[idx + 1] |= f >> (64 - sh);
     }
-    for (int t = 0; t < words; ++t) out[q * words + t] = (uint16_t)(bits[t >> 2] >> (16 * (t & 3)));
+    for (int t = 0; t < words; ++t) {
+      const uint32_t w16 = (uint32_t)(bits[t >> 2] >> (16 * (t & 3))) & 0xffffu;
+      const int w = q * words + t;                             // 16-bit word of the lane's share
+      dw[w >> 1] |= w16 << (16 * (w & 1));
+    }
+  }
+  const int N = 2 * words, n4 = N / 4, n2 = (N % 4) / 2;
+  const int lane = (int)(j4 >> 2) & 63;
+  uint32_t* blk = reinterpret_cast<uint32_t*>(table) +
+                  ((size_t)r * (size_t)(dpad / kRecBlockCoords) + (size_t)(j4 / kRecBlockCoords)) * (size_t)(64 * N);
+  for (int t = 0; t < N; ++t) {
+    int off;
+    if (t < 4 * n4) off = ((t >> 2) * 64 + lane) * 4 + (t & 3);
+    else if (t < 4 * n4 + 2 * n2) off = n4 * 256 + lane * 2 + (t - 4 * n4);
+    else off = n4 * 256 + n2 * 128 + lane;
+    blk[off] = dw[t];
   }
 }
 

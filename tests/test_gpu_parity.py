@@ -564,13 +564,13 @@ def test_sketch_cell_paths():
     check_state(mon, O.local_state(u.cpu().numpy(), "f32", w_t0.cpu().numpy(), xi.cpu().numpy(), coef, m))
     mon.close()
     # (c) every coordinate in one bucket with one sign and equal positive drifts: the cell of a
-    # workgroup collects 12288 terms of about 2^17.5 units and leaves [2^30, 3*2^30)
-    d, m = 256 * 12_288, 4
+    # workgroup collects at least 12288 terms of about 2^17.5 units and leaves [2^30, 3*2^30)
+    d, m = 512 * 12_288, 4
     coef = np.array([[[1 << 30, 0, 0, 0], [0, 0, 0, 0]]], np.uint32)      # bucket 2, sign +1
     w_t0 = torch.zeros(d, device=DEV)
     w = torch.full((1, d), 0.5, device=DEV)
     mon = F.FdaMonitor(1, d, "f32", 2, 1, m, 0.06, coef, device=DEV)
-    assert mon.plan["chunk"] == 12_288, mon.plan
+    assert mon.plan["chunk"] >= 12_288, mon.plan
     mon.local_state(w, w_t0)
     assert mon.last_state_path() == 1
     n, _, sk = mon.state_numpy()
