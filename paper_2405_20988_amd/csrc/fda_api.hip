@@ -145,8 +145,10 @@ int make_split(const fda_desc* d, int cus, int64_t lds_cu, int cell_bytes, Split
           if (c >= rc) { LR = c; break; }
       }
       if (LR == 0) continue;
-      if (cells && ((int64_t)rc * d->m + fda::kDummyCells) * stride * cell_bytes + kLdsReserve > lds_cu)
-        continue;
+      const int64_t need = !cells ? 0
+                           : narrow ? (int64_t)fda::cells32_words(rc, d->m, KC) * 4
+                                    : ((int64_t)rc * d->m + fda::kDummyCells) * stride * cell_bytes;
+      if (need + kLdsReserve > lds_cu) continue;
       const double slots = (double)G * R * KC;           // element slots per coordinate
       const double cost = slots * kElementCost + slots * LR * kAtomicCost +
                           (double)G * R * LR * kDecodeCost +
@@ -165,8 +167,9 @@ int make_split(const fda_desc* d, int cus, int64_t lds_cu, int cell_bytes, Split
   sp->KC = bestKC;
   sp->LR = bestLR;
   sp->stride = (sp->KC == 1) ? 1 : (sp->KC | 1);
-  const int64_t sk_bytes =
-      cells ? ((int64_t)sp->rcnt_max * d->m + fda::kDummyCells) * sp->stride * cell_bytes : 0;
+  const int64_t sk_bytes = !cells ? 0
+                           : narrow ? (int64_t)fda::cells32_words(sp->rcnt_max, d->m, sp->KC) * 4
+                                    : ((int64_t)sp->rcnt_max * d->m + fda::kDummyCells) * sp->stride * cell_bytes;
   sp->lds_bytes = round_up(sk_bytes, 16) + kLdsReserve;
   // one workgroup per CU: the kernels hold more registers than two resident workgroups would allow
   const int occ = 1;

@@ -564,18 +564,52 @@ def test_sketch_cell_paths():
     check_state(mon, O.local_state(u.cpu().numpy(), "f32", w_t0.cpu().numpy(), xi.cpu().numpy(), coef, m))
     mon.close()
     # (c) every coordinate in one bucket with one sign and equal positive drifts: the cell of a
-    # workgroup collects at least 12288 terms of about 2^17.5 units and leaves [2^30, 3*2^30)
-    d, m = 512 * 12_288, 4
+    # workgroup collects 12288 terms of about 2^17.5 units and leaves [2^30, 3*2^30)
+    d, m = 256 * 12_288, 4
     coef = np.array([[[1 << 30, 0, 0, 0], [0, 0, 0, 0]]], np.uint32)      # bucket 2, sign +1
     w_t0 = torch.zeros(d, device=DEV)
     w = torch.full((1, d), 0.5, device=DEV)
     mon = F.FdaMonitor(1, d, "f32", 2, 1, m, 0.06, coef, device=DEV)
-    assert mon.plan["chunk"] >= 12_288, mon.plan
+    assert mon.plan["chunk"] == 12_288, mon.plan      # beyond 16384 terms a cell the call would not try 32-bit cells
     mon.local_state(w, w_t0)
     assert mon.last_state_path() == 1
     n, _, sk = mon.state_numpy()
     assert sk[0, 0].tolist() == [0.0, 0.0, 0.5 * d, 0.0]
     assert n[0] == 0.25 * d
+    mon.close()
+    # (d) the same with two workers, whose cells of a bucket are the two halves of one 8-byte word that
+    # takes both additions at once: either half leaving its band, upwards or downwards (the low half
+    # then borrows from the high one), must send the call to the 64-bit cells
+    tiny = 2.0 ** -12
+    for drifts in ((0.5, tiny), (-0.5, tiny), (tiny, 0.5), (tiny, -0.5), (-0.5, -0.5)):
+        w = torch.empty((2, d), device=DEV)
+        w[0].fill_(drifts[0])
+        w[1].fill_(drifts[1])
+        mon = F.FdaMonitor(2, d, "f32", 2, 1, m, 0.06, coef, device=DEV)
+        assert mon.plan["workers_per_group"] == 2 and mon.plan["chunk"] == 12_288, mon.plan
+        mon.local_state(w, w_t0)
+        assert mon.last_state_path() == 1, drifts
+        n, _, sk = mon.state_numpy()
+        for k in range(2):
+            assert sk[k, 0].tolist() == [0.0, 0.0, drifts[k] * d, 0.0], (drifts, k)
+            assert n[k] == drifts[k] ** 2 * d
+        mon.close()
+    # ... and while both halves stay inside their bands they are exact and independent, whatever the
+    # signs of the terms: drifts of alternating sign (the low half is added to and subtracted from all
+    # the time), opposite in the two workers, a few coordinates changed by hand
+    alt = torch.where(torch.arange(d, device=DEV) % 2 == 0, 2.0 ** -6, -(2.0 ** -6))
+    w = torch.stack([alt, -alt]).contiguous()
+    w[0, 5] = 2.0 ** -6
+    w[1, 8] = -3 * 2.0 ** -6
+    w[1, 77] = 5 * 2.0 ** -6
+    mon = F.FdaMonitor(2, d, "f32", 2, 1, m, 0.06, coef, device=DEV)
+    mon.local_state(w, w_t0)
+    assert mon.last_state_path() == 0
+    n, _, sk = mon.state_numpy()
+    want = w.double().sum(dim=1).cpu().numpy()
+    assert want.tolist() == [2.0 ** -5, -2.0 ** -5 + 2.0 ** -4]          # +2/64 and -2/64 + 4/64
+    for k in range(2):
+        assert sk[k, 0].tolist() == [0.0, 0.0, want[k], 0.0], k
     mon.close()
 
 
