@@ -544,8 +544,10 @@ state_kernel(const StateParams prm) {
           for (int i = 0; i < LR; ++i) {
             const uint32_t h = rec_field<LR, FB>(t.rec, v, i);
             const uint32_t bucket = h & Geom::kBucketMask;
-            uint32_t off = __umul24(bucket, stride_bytes) + rowbase[i];
-            if constexpr (kSkewed) off += bucket & ~7u;                   // 8 bytes after every 8 buckets
+            // skewed: 8 more bytes after every 8 buckets, bucket * stride + (bucket & ~7) -- the same as
+            // bucket * (stride + 1) with its low three bits cleared (stride and row bases: multiples of 8)
+            const uint32_t off = kSkewed ? ((__umul24(bucket, stride_bytes + 1u) + rowbase[i]) & ~7u)
+                                         : __umul24(bucket, stride_bytes) + rowbase[i];
             const bool neg = (h & (1u << (FB - 1))) != 0u;                // sign -1
             uint32_t old[KC];
             if constexpr (kPaired) {
