@@ -123,6 +123,8 @@ typedef struct fda_plan_info {
   int32_t mean_workgroups_per_cu;/* resident workgroups per CU the launch is sized for       */
   int64_t mean_chunk;            /* coordinates per partition                                */
   int64_t mean_lds_bytes;        /* LDS per workgroup                                        */
+  int32_t sign_split_rows;  /* 1: the state pass keeps terms of sign -1 in LDS rows of their own */
+  int32_t worker_slots;     /* worker slots of the state kernel that runs (>= workers_per_group)  */
 } fda_plan_info;
 
 const char* fda_strerror(int code);

@@ -53,7 +53,8 @@ class FdaPlanInfo(C.Structure):
                 ("state_floats", C.c_int64),
                 ("mean_row_groups", C.c_int32), ("mean_rows_per_group", C.c_int32),
                 ("mean_partitions", C.c_int32), ("mean_workgroups_per_cu", C.c_int32),
-                ("mean_chunk", C.c_int64), ("mean_lds_bytes", C.c_int64)]
+                ("mean_chunk", C.c_int64), ("mean_lds_bytes", C.c_int64),
+                ("sign_split_rows", C.c_int32), ("worker_slots", C.c_int32)]
 
     def as_dict(self) -> dict:
         return {name: getattr(self, name) for name, _ in self._fields_}

@@ -17,7 +17,7 @@ LIB_PATH = os.path.join(LIB_DIR, "libfda.so")
 EXAMPLE_SRC = os.path.join(CSRC, "fda_c_example.c")
 EXAMPLE_PATH = os.path.join(LIB_DIR, "fda_c_example")
 UNITS = (["fda_api", "fda_calibration"] +
-         ["fda_state_narrow_%s_kc%d" % (t, k) for t in ("f32", "bf16") for k in (1, 2, 3, 4, 5, 6, 8)] +
+         ["fda_state_narrow_%s_kc%d" % (t, k) for t in ("f32", "bf16") for k in (1, 2, 4, 6, 8)] +
          ["fda_state_wide_%s_%s" % (t, c) for t in ("f32", "bf16") for c in ("i64", "f64")] +
          ["fda_mean_%s_%s" % (t, c) for t in ("f32", "bf16") for c in ("i64", "f64")])
 SOURCES = [os.path.join(CSRC, u + ".hip") for u in UNITS]

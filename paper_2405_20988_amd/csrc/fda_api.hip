@@ -45,10 +45,15 @@ int fail(int code, const char* fmt, ...) {
 
 constexpr int64_t kLdsReserve = 1536;      // reduction scratch (8 waves x 8 worker slots x 2 doubles) + slack
 constexpr int kMaxRounds = 4;              // at most this many rounds of resident workgroups per launch
-constexpr double kElementCost = 10.0;      // rough cost of loading / differencing / converting one slab element
-constexpr double kAtomicCost = 3.0;        // select the signed value, issue the LDS atomic
-constexpr double kDecodeCost = 5.0;        // unpack one table entry into an LDS address and a sign
-constexpr double kSharedByteCost = 0.5;    // per byte of w_t0 / xi / table re-read by another workgroup
+// the planner's cost model, in vector-ALU instructions per coordinate
+constexpr double kElementCost = 6.5;       // load / unpack / drift / fixed point / scalar sums of one slab element
+constexpr double kNegateCost = 2.0;        // ... its negated term, when the rows are not sign-split
+constexpr double kDecodeCost = 2.5;        // one table field into an LDS address
+constexpr double kSignCost = 3.0;          // ... and into a sign and a bucket, when the rows are not sign-split
+constexpr double kSelectCost = 1.0;        // choosing the term or its negative for one 32-bit cell
+constexpr double kAtomicCost = 7.5;        // one 32-bit LDS addition and the OR of what it returned
+constexpr double kPairAddCost = 13.0;      // one 64-bit LDS addition (two cells) and the OR of what it returned
+constexpr double kSharedByteCost = 0.25;   // per byte of w_t0 / xi / table read by one more workgroup
 constexpr int kMaxEstBlocksPerRow = 128;   // 32768 / 256: workgroups of estimate_kernel per sketch row
 constexpr int kScaleSamples = 16384;       // sampled coordinates per worker for the scale
 constexpr int kScaleBlocks = kScaleSamples * fda::kScaleMaxSlices / fda::kSmallThreads;   // its workgroups, at most
@@ -62,6 +67,7 @@ int64_t round_up(int64_t x, int64_t a) { return (x + a - 1) / a * a; }
 // How one state pass is spread over the chip for a given sketch-cell size.
 struct Split {
   int G, R, kcnt_max, rcnt_max, KC, LR, P, stride;
+  int split;        // 32-bit cells: sign-split LDS rows (2 m buckets per row)
   int64_t chunk, lds_bytes;
 };
 // How one mean-state pass is spread over the chip.
@@ -121,40 +127,57 @@ int make_split(const fda_desc* d, int cus, int64_t lds_cu, int cell_bytes, Split
   // Pick the split with the least estimated vector-ALU work per coordinate.
   const int l = sk ? d->l : 1;
   double best = -1.0;
-  int bestG = 0, bestR = 0, bestKC = 0, bestLR = 0;
+  int bestG = 0, bestR = 0, bestKC = 0, bestLR = 0, bestSplit = 0;
   const bool narrow = cell_bytes == 4;
   for (int G = 1; G <= d->K; ++G) {
     const int kc = (d->K + G - 1) / G;
-    int KC = 0;
-    if (narrow) {
-      for (int c : fda::kKCSet)
-        if (c >= kc) { KC = c; break; }
-    } else {
-      for (int c : fda::kWideKCSet)
-        if (c >= kc) { KC = c; break; }
-    }
-    if (KC == 0) continue;
-    const int stride = (KC == 1) ? 1 : (KC | 1);
-    for (int R = 1; R <= l; ++R) {
-      const int rc = (l + R - 1) / R;
-      int LR = 0;                                        // row slots of the kernel that would run
+    {
+      int KC = 0;                                            // the smallest kernel that holds kc workers
       if (narrow) {
-        if (rc <= fda::kMaxLR && KC * rc <= fda::kMaxSlots) LR = rc;
+        for (int c : fda::kKCSet)
+          if (c >= kc) { KC = c; break; }
       } else {
-        for (int c : fda::kWideLRSet)
-          if (c >= rc) { LR = c; break; }
+        for (int c : fda::kWideKCSet)
+          if (c >= kc) { KC = c; break; }
       }
-      if (LR == 0) continue;
-      const int64_t need = !cells ? 0
-                           : narrow ? (int64_t)fda::cells32_words(rc, d->m, KC) * 4
-                                    : ((int64_t)rc * d->m + fda::kDummyCells) * stride * cell_bytes;
-      if (need + kLdsReserve > lds_cu) continue;
-      const double slots = (double)G * R * KC;           // element slots per coordinate
-      const double cost = slots * kElementCost + slots * LR * kAtomicCost +
-                          (double)G * R * LR * kDecodeCost +
-                          (double)G * R * (8 + 2 * LR) * kSharedByteCost + 1e-3 * G * R;
-      if (best < 0.0 || cost < best) { best = cost; bestG = G; bestR = R; bestKC = KC; bestLR = LR; }
-      break;   // a larger R only costs more for this G
+      if (KC == 0) continue;
+      const int stride = (KC == 1) ? 1 : (KC | 1);
+      // sign-split rows (32-bit cells, even slot counts): no negated terms, no select per addition, twice the LDS
+      // (without a sketch either kind of kernel does the same)
+      for (int split = (narrow && KC % 2 == 0) ? 1 : 0; split >= 0; --split) {
+        if (narrow && !fda::narrow_kernel_exists(KC, split != 0)) continue;
+        for (int R = 1; R <= l; ++R) {
+          const int rc = (l + R - 1) / R;
+          int LR = 0;                                        // row slots of the kernel that would run
+          if (narrow) {
+            if (rc <= fda::kMaxLR && KC * rc <= fda::kMaxSlots) LR = rc;
+          } else {
+            for (int c : fda::kWideLRSet)
+              if (c >= rc) { LR = c; break; }
+          }
+          if (LR == 0) continue;
+          const int64_t need = !cells ? 0
+                               : narrow ? (int64_t)fda::cells32_words(rc, split ? 2 * d->m : d->m, KC) * 4
+                                        : ((int64_t)rc * d->m + fda::kDummyCells) * stride * cell_bytes;
+          if (need + kLdsReserve > lds_cu) continue;
+          // Estimated cost per coordinate, in vector-ALU instructions (an LDS addition counted as what it
+          // keeps the compute unit from issuing): per element slot the load / drift / fixed-point work
+          // (with the negated terms unless the rows are sign-split), per row slot the table field, per
+          // addition the select (unless split), the overflow OR and the LDS instruction itself.
+          const double wg = (double)G * R;
+          const double pairs = (KC % 2 == 0 && narrow) ? KC / 2 : KC;           // LDS instructions per row slot
+          const double per_add = (KC % 2 == 0 && narrow) ? (split ? kPairAddCost : kPairAddCost + 2.0 * kSelectCost)
+                                                         : kAtomicCost + kSelectCost;
+          const double cost = wg * KC * (split ? kElementCost : kElementCost + kNegateCost) +
+                              wg * LR * (split ? kDecodeCost : kDecodeCost + kSignCost) +
+                              wg * LR * pairs * per_add +
+                              wg * (8 + 2 * LR) * kSharedByteCost + 1e-3 * wg;
+          if (best < 0.0 || cost < best) {
+            best = cost; bestG = G; bestR = R; bestKC = KC; bestLR = LR; bestSplit = split;
+          }
+          break;   // a larger R only costs more for this G
+        }
+      }
     }
   }
   if (bestG == 0)
@@ -162,13 +185,14 @@ int make_split(const fda_desc* d, int cus, int64_t lds_cu, int cell_bytes, Split
                 (long long)lds_cu);
   sp->G = bestG;
   sp->R = bestR;
+  sp->split = bestSplit;
   sp->kcnt_max = (d->K + bestG - 1) / bestG;
   sp->rcnt_max = (l + bestR - 1) / bestR;
   sp->KC = bestKC;
   sp->LR = bestLR;
   sp->stride = (sp->KC == 1) ? 1 : (sp->KC | 1);
   const int64_t sk_bytes = !cells ? 0
-                           : narrow ? (int64_t)fda::cells32_words(sp->rcnt_max, d->m, sp->KC) * 4
+                           : narrow ? (int64_t)fda::cells32_words(sp->rcnt_max, sp->split ? 2 * d->m : d->m, sp->KC) * 4
                                     : ((int64_t)sp->rcnt_max * d->m + fda::kDummyCells) * sp->stride * cell_bytes;
   sp->lds_bytes = round_up(sk_bytes, 16) + kLdsReserve;
   // one workgroup per CU: the kernels hold more registers than two resident workgroups would allow
@@ -282,6 +306,8 @@ void export_plan(const Plan& pl, fda_plan_info* out) {
   out->mean_workgroups_per_cu = pl.mean.occ;
   out->mean_chunk = pl.mean.chunk;
   out->mean_lds_bytes = pl.mean.lds_bytes;
+  out->sign_split_rows = pl.narrow.split;
+  out->worker_slots = pl.narrow.KC;
 }
 
 int device_shape(int* cus, int64_t* lds) {
@@ -307,13 +333,11 @@ int dispatch_any(int dtype, int cell, const Split& sp, int FB, const fda::StateP
   const size_t lds = (size_t)sp.lds_bytes;
   hipError_t e = hipErrorInvalidValue;
   if (cell == fda::kCellI32) {
-#define FDA_CASE(t, kc) case kc: e = fda::launch_narrow_##t##_kc##kc(LR, FB, prm, lds, st); break
+#define FDA_CASE(t, kc) case kc: e = fda::launch_narrow_##t##_kc##kc(LR, FB, sp.split, prm, lds, st); break
     if (dtype == FDA_F32) {
-      switch (KC) { FDA_CASE(f32, 1); FDA_CASE(f32, 2); FDA_CASE(f32, 3); FDA_CASE(f32, 4);
-                    FDA_CASE(f32, 5); FDA_CASE(f32, 6); FDA_CASE(f32, 8); }
+      switch (KC) { FDA_CASE(f32, 1); FDA_CASE(f32, 2); FDA_CASE(f32, 4); FDA_CASE(f32, 6); FDA_CASE(f32, 8); }
     } else {
-      switch (KC) { FDA_CASE(bf16, 1); FDA_CASE(bf16, 2); FDA_CASE(bf16, 3); FDA_CASE(bf16, 4);
-                    FDA_CASE(bf16, 5); FDA_CASE(bf16, 6); FDA_CASE(bf16, 8); }
+      switch (KC) { FDA_CASE(bf16, 1); FDA_CASE(bf16, 2); FDA_CASE(bf16, 4); FDA_CASE(bf16, 6); FDA_CASE(bf16, 8); }
     }
 #undef FDA_CASE
   } else if (dtype == FDA_F32) {

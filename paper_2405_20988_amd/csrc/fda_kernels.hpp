@@ -226,14 +226,15 @@ __device__ __forceinline__ uint32_t hash_entry(const HashCoef& hc, int row, uint
 
 // ---- the tabulated hash: geometry of a record and of a lane's share of a tile -----------
 constexpr int kDummyCells = 64;              // cells of the dummy region (power of two)
-// field width for a sketch of m columns: 11 bits while the bucket fits in 10, else 16
+// field width for a sketch of m columns (a field is below 2 m): 11 bits while m <= 1024, else 16
 __host__ __device__ constexpr int field_bits_for(int m) { return m <= 1024 ? 11 : 16; }
 template <int LR, int FB>
 struct RecGeom {
   static constexpr int kWords = (LR * FB + 15) / 16;        // 16-bit words per coordinate record
   static constexpr int kDwords = 2 * kWords;                // dwords of a lane's 4 consecutive records
-  static constexpr uint32_t kBucketMask = (1u << (FB - 1)) - 1u;
+  static constexpr uint32_t kFieldMask = (1u << FB) - 1u;
 };
+// A field of the table is s = bucket + m * (1 when the sign is -1), below 2 m.
 // The table is stored in blocks of 256 coordinates: the share of one wave of one tile (64 lanes x 4
 // consecutive coordinates).  A lane's 4 records are N = RecGeom::kDwords dwords, which it loads in the
 // widest pieces: N / 4 of 16 bytes, then one of 8, then one of 4.  Inside a block the dwords are laid
@@ -343,6 +344,9 @@ __host__ __device__ constexpr uint32_t cells32_row_words(int m, int KC) {       
 __host__ __device__ constexpr uint32_t cells32_words(int rows, int m, int KC) {    // rows plus the dummy region
   return (uint32_t)rows * cells32_row_words(m, KC) + cells32_row_words(kDummyCells, KC);
 }
+// Sign-split rows (SPLIT): a row has 2 m buckets, the table field s itself is the bucket index -- terms
+// of sign -1 are ADDED to bucket m + b, and the flush takes (bucket b) - (bucket m + b).  The pass then
+// needs neither the negated terms nor a select per addition; it needs twice the LDS.
 
 // floor(x + 0.5) as an integer in one instruction (|x| < 2^31): the fixed-point term of a scaled drift,
 // at most half a unit from it
@@ -352,9 +356,10 @@ __device__ __forceinline__ int round_half_up(float x) {
   return q;
 }
 
-template <typename T, int KC, int LR, int CELL, int FB>
+template <typename T, int KC, int LR, int CELL, int FB, bool SPLIT = false>
 __global__ void __launch_bounds__(kStateThreads)
 state_kernel(const StateParams prm) {
+  static_assert(!SPLIT || CELL == kCellI32, "sign-split rows: 32-bit cells only");
   constexpr int V = kStateV;
   constexpr long long kTile = (long long)kStateThreads * V;
   // only the 32-bit-cell pass streams the table; the fallback passes evaluate the hash
@@ -397,10 +402,11 @@ state_kernel(const StateParams prm) {
   constexpr bool kSkewed = CELL == kCellI32 && cells32_skewed(KC);
   const uint32_t stride_bytes = CELL == kCellI32 ? 4u * KC : (uint32_t)prm.stride * kCellBytes;
   const int cells = rcnt * prm.m;                      // cells this workgroup owns
-  const uint32_t row_words32 = cells32_row_words(prm.m, KC);
+  const int mrow = SPLIT ? 2 * prm.m : prm.m;          // buckets of one LDS row
+  const uint32_t row_words32 = cells32_row_words(mrow, KC);
   const uint32_t dummy_base = CELL == kCellI32 ? (uint32_t)rcnt * row_words32 * 4u : (uint32_t)cells * stride_bytes;
   const int lds_cells = !sketch ? 0
-                        : CELL == kCellI32 ? (int)cells32_words(rcnt, prm.m, KC) : (cells + kDummyCells) * prm.stride;
+                        : CELL == kCellI32 ? (int)cells32_words(rcnt, mrow, KC) : (cells + kDummyCells) * prm.stride;
   double* red = reinterpret_cast<double*>(lds_raw + (((size_t)lds_cells * kCellBytes + 15) & ~(size_t)15));
 
   const int tid = threadIdx.x;
@@ -529,7 +535,7 @@ state_kernel(const StateParams prm) {
 #pragma unroll
           for (int k = 0; k < KC; ++k) {
             q[k] = (uint32_t)round_half_up(u[k]);
-            nq[k] = 0u - q[k];
+            nq[k] = SPLIT ? 0u : 0u - q[k];
           }
           // paired slots: the high half of q_lo + 2^32 * q_hi is q_hi minus one when q_lo is negative
           uint32_t qh[KC / 2 + 1], nqh[KC / 2 + 1];
@@ -537,18 +543,19 @@ state_kernel(const StateParams prm) {
 #pragma unroll
             for (int k = 0; k < KC; k += 2) {
               qh[k / 2] = q[k + 1] + (uint32_t)((int)q[k] >> 31);
-              nqh[k / 2] = nq[k + 1] + (uint32_t)((int)nq[k] >> 31);
+              nqh[k / 2] = SPLIT ? 0u : nq[k + 1] + (uint32_t)((int)nq[k] >> 31);
             }
           }
 #pragma unroll
           for (int i = 0; i < LR; ++i) {
-            const uint32_t h = rec_field<LR, FB>(t.rec, v, i);
-            const uint32_t bucket = h & Geom::kBucketMask;
+            const uint32_t s = rec_field<LR, FB>(t.rec, v, i) & Geom::kFieldMask;
+            // sign-split rows add the term itself to bucket s; otherwise s >= m means sign -1, bucket s - m
+            const bool neg = !SPLIT && s >= (uint32_t)prm.m;
+            const uint32_t bucket = neg ? s - (uint32_t)prm.m : s;
             // skewed: 8 more bytes after every 8 buckets, bucket * stride + (bucket & ~7) -- the same as
             // bucket * (stride + 1) with its low three bits cleared (stride and row bases: multiples of 8)
             const uint32_t off = kSkewed ? ((__umul24(bucket, stride_bytes + 1u) + rowbase[i]) & ~7u)
                                          : __umul24(bucket, stride_bytes) + rowbase[i];
-            const bool neg = (h & (1u << (FB - 1))) != 0u;                // sign -1
             uint32_t old[KC];
             if constexpr (kPaired) {
               unsigned long long* cell = reinterpret_cast<unsigned long long*>(lds_raw + off);
@@ -701,10 +708,16 @@ state_kernel(const StateParams prm) {
       unsigned long long val;
       if constexpr (CELL == kCellI32) {
         const int i = c / prm.m, bkt = c - i * prm.m;
-        const uint32_t word = reinterpret_cast<const uint32_t*>(
-            lds_raw)[(size_t)i * row_words32 + cells32_bucket_word((uint32_t)bkt, KC) + k];
+        const uint32_t* row = reinterpret_cast<const uint32_t*>(lds_raw) + (size_t)i * row_words32 + k;
+        const uint32_t word = row[cells32_bucket_word((uint32_t)bkt, KC)];
         left_band = left_band || (word & 0x80000000u) != 0u;      // the last additions are examined here
-        val = (unsigned long long)(long long)(int)(word - kCellBias);
+        long long sum = (long long)(int)(word - kCellBias);
+        if constexpr (SPLIT) {
+          const uint32_t minus = row[cells32_bucket_word((uint32_t)(bkt + prm.m), KC)];
+          left_band = left_band || (minus & 0x80000000u) != 0u;
+          sum -= (long long)(int)(minus - kCellBias);
+        }
+        val = (unsigned long long)sum;
       } else {
         val = reinterpret_cast<const unsigned long long*>(lds_raw)[(size_t)c * prm.stride + k];
       }

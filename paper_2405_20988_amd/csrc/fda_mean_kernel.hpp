@@ -257,8 +257,9 @@ mean_state_kernel(const MeanParams prm) {
 #pragma unroll
           for (int i = 0; i < LR; ++i) {
             const uint32_t hw = rec_field<LR, FB>(h.rec, v, i);
-            const uint32_t off = ((hw & Geom::kBucketMask) << 3) + rowbase[i];
-            const bool neg = (hw & (1u << (FB - 1))) != 0u;                // sign -1
+            const uint32_t sb = hw & Geom::kFieldMask;                     // bucket + m * (sign is -1)
+            const bool neg = sb >= (uint32_t)prm.m;
+            const uint32_t off = ((neg ? sb - (uint32_t)prm.m : sb) << 3) + rowbase[i];
             if constexpr (CELL == kCellI64) {
               const unsigned long long q = (unsigned long long)acc[v];
               atomicAdd(reinterpret_cast<unsigned long long*>(lds_raw + off), neg ? 0ull - q : q);

@@ -17,9 +17,10 @@ namespace fda {
 
 // ---- the hash, tabulated once per context (Section 3.1 sketch; hash family: two cubics mod 2^31 - 1
 // per row).  Per row group r and coordinate j one record of `words` 16-bit words; a record packs,
-// lowest bits first, one field of `fb` bits per row slot of the group: bucket in the low fb-1 bits,
-// top bit set for sign -1.  Slots past the group's last row (and whole records past d) hold a bucket
-// below kDummyCells and sign +: the state kernels send those additions to a dummy region.
+// lowest bits first, one field of `fb` bits per row slot of the group: bucket + m for sign -1, bucket
+// for sign +1 (below 2 m, which fits: field_bits_for).  Slots past the group's last row (and whole
+// records past d) hold a value below kDummyCells: the state kernels send those additions to a dummy
+// region (whatever bucket and sign they decode from it, the bucket stays below kDummyCells).
 // Layout [row group][block of 256 coordinates][dwords in load order]: the 2 * words dwords of the 4
 // records that a lane of the state kernels loads together are placed where load_rec_block() reads
 // them.  One thread writes one lane's share.
@@ -40,7 +41,7 @@ hash_table_kernel(const HashCoef hc, int l, int R, int slots, int m, int fb, int
       unsigned long long f = (unsigned long long)((uint32_t)(j + 17 * i) & (uint32_t)(kDummyCells - 1));
       if (i < rcnt && j < d) {
         const uint32_t h = hash_entry(hc, rstart + i, (uint32_t)j, (uint32_t)m);
-        f = (unsigned long long)(h & 0x7fffu) | ((unsigned long long)(h >> 15) << (fb - 1));
+        f = (unsigned long long)((h & 0x7fffu) + (h >> 15) * (uint32_t)m);      // bucket + m * (sign is -1)
       }
       const int pos = i * fb, idx = pos >> 6, sh = pos & 63;
       bits[idx] |= f << sh;

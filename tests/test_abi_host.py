@@ -35,7 +35,7 @@ def test_struct_layouts_match_header():
     assert C.sizeof(F.FdaEstimate) == 64
     assert F.FdaEstimate.sync_linear.offset == 40 and F.FdaEstimate.sync_sketch.offset == 44
     assert C.sizeof(F.FdaDesc) == 56
-    assert C.sizeof(F.FdaPlanInfo) == 88
+    assert C.sizeof(F.FdaPlanInfo) == 96
 
 
 def test_strerror():
@@ -93,8 +93,9 @@ def test_plan_of_the_five_configs(name):
     assert p.partitions % 8 == 0 and p.partitions >= 8
     assert p.lds_bytes <= 163840
     assert p.partitions * p.chunk >= c["d"]
-    tile = p.threads * (4 if dt == F.FDA_F32 else 8)
+    tile = p.threads * 4                       # a lane owns 4 coordinates of a tile, whatever the slab type
     assert p.chunk % tile == 0
+    assert p.worker_slots >= p.workers_per_group and p.sign_split_rows in (0, 1)
     # the partial buffers fit in the workspace
     need = p.partitions * c["K"] * (16 + 8 * c["l"] * c["m"])
     assert p.workspace_bytes >= need

@@ -93,7 +93,14 @@ STATE_CASES = [
     ("cfg1", 30_001, {"l": 1, "m": 1}),
     ("cfg2", 20_000, {"K": 3, "l": 1, "m": 19_000}),   # one worker per group: sketch fills LDS
     ("cfg1", 5_000, {"K": 300, "l": 3, "m": 64}),      # many workers: 38 worker groups
+    # which kind of LDS rows the 32-bit-cell pass uses (expected plan: worker slots, sign-split rows)
+    ("cfg2", 30_011, {"K": 2, "l": 3, "m": 6_000}),     # two workers in one 8-byte word, LDS too small to split the signs
+    ("cfg2", 30_011, {"K": 4, "l": 2, "m": 4_500}),     # two groups of two rather than four slots: split rows fit
+    ("cfg2", 30_011, {"K": 5, "l": 6, "m": 64}),        # 6 slots x 6 rows are not built: groups of 2, 2, 1 workers
+    ("cfg2", 30_011, {"K": 5, "l": 5, "m": 64}),        # five workers in six slots: a spare high half
+    ("cfg5", 40_009, {"K": 8, "l": 4, "m": 300}),       # bf16, eight slots
 ]
+EXPECTED_ROWS = {(2, 3, 6_000): (2, 0), (4, 2, 4_500): (2, 1), (5, 6, 64): (2, 1), (5, 5, 64): (6, 1), (8, 4, 300): (8, 1)}
 
 
 @pytest.mark.parametrize("name,d,over", STATE_CASES)
@@ -102,6 +109,9 @@ def test_state_and_estimate_parity(name, d, over):
     wl = S.make(name, device=DEV, seed=1, d=d, **over)
     mon = monitor_for(wl)
     say(f"       plan {mon.plan}")
+    key = (wl.K, wl.l, wl.m)
+    if key in EXPECTED_ROWS and "K" in over:
+        assert (mon.plan["worker_slots"], mon.plan["sign_split_rows"]) == EXPECTED_ROWS[key], mon.plan
     mon.local_state(wl.w, wl.w_t0, wl.xi)
     torch.cuda.synchronize()
     ref = oracle_state(wl)

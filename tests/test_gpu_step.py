@@ -156,12 +156,15 @@ def test_contexts_with_different_sketch_sizes_coexist():
     first and then small: the later one must not shrink what the earlier one may launch with."""
     say("[case] a large-sketch context stays usable after a small-sketch one is created")
     from oracle import fda_oracle as O
-    big = S.make("cfg5", device=DEV, seed=14, d=100_003)           # 7 x 1000: 140 KB of LDS
+    big = S.make("cfg5", device=DEV, seed=14, d=100_003)           # 7 x 1000: 112 KB of LDS
     mon_big = monitor_for(big)
-    small = S.make("cfg5", device=DEV, seed=15, d=50_001, K=4, l=7, m=8)   # same kernels (4 workers x 7
-    assert mon_big.plan["workers_per_group"] == 4                           # rows per workgroup), ~1 KB of LDS
-    mon_small = monitor_for(small)
-    assert (mon_small.plan["workers_per_group"], mon_small.plan["rows_per_group"]) == (4, 7)
+    small = S.make("cfg5", device=DEV, seed=15, d=50_001, K=2, l=7, m=8)   # same kernels (2 worker slots x 7
+
+    def kernel_of(mon):
+        return mon.plan["worker_slots"], mon.plan["rows_per_group"], mon.plan["sign_split_rows"]
+    assert kernel_of(mon_big) == (2, 7, 1) and mon_big.plan["lds_bytes"] > 100_000    # rows per workgroup, split
+    mon_small = monitor_for(small)                                                       # rows), ~2 KB of LDS
+    assert kernel_of(mon_small) == kernel_of(mon_big) and mon_small.plan["lds_bytes"] < 10_000
     for mon, wl in ((mon_small, small), (mon_big, big), (mon_small, small)):
         mon.local_state(wl.w, wl.w_t0, wl.xi)
         mon.mean_state(wl.w, wl.w_t0, wl.xi)
