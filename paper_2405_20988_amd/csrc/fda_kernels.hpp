@@ -506,10 +506,26 @@ state_kernel(const StateParams prm) {
         load_rec_block<Geom::kDwords, false>(recs + (j0 >> 8) * (64 * Geom::kDwords), (int)(j0 >> 2) & 63, t.rec);
     };
 
-    auto consume = [&](const Tile& t, long long j0) {
-      float sn[KC], sp[KC];
+    // fp32 partial sums of the scalar components: kept over kScalarTiles tiles (that many times V
+    // terms each), then added to the fp64 sums -- the fp64 conversions and additions are the most
+    // expensive instructions of the loop, and 16 fp32 terms stay well inside the tolerance
+    constexpr int kScalarTiles = 4;
+    float sn[KC], sp[KC];
 #pragma unroll
-      for (int k = 0; k < KC; ++k) { sn[k] = 0.0f; sp[k] = 0.0f; }
+    for (int k = 0; k < KC; ++k) { sn[k] = 0.0f; sp[k] = 0.0f; }
+    int held = 0;                             // tiles whose scalar partials are still in sn / sp
+    auto widen = [&]() {
+      if constexpr (SC) {
+#pragma unroll
+        for (int k = 0; k < KC; ++k) {
+          dn[k] += (double)sn[k]; dp[k] += (double)sp[k];
+          sn[k] = 0.0f; sp[k] = 0.0f;
+        }
+      }
+      held = 0;
+    };
+
+    auto consume = [&](const Tile& t, long long j0) {
       uint32_t pend_old[KC];                  // 32-bit cells: the last batch not yet examined
       bool have_pending = false;
 #pragma unroll
@@ -626,8 +642,7 @@ state_kernel(const StateParams prm) {
         }
       }
       if constexpr (SC) {
-#pragma unroll
-        for (int k = 0; k < KC; ++k) { dn[k] += (double)sn[k]; dp[k] += (double)sp[k]; }
+        if (++held == kScalarTiles) widen();
       }
     };
 
@@ -654,6 +669,7 @@ state_kernel(const StateParams prm) {
       load_slow(t, j0);
       consume(t, j0);
     }
+    widen();
   };
   if (scalars) {
     if (sketch) run(std::true_type{}, std::true_type{});
