@@ -45,6 +45,7 @@ int fail(int code, const char* fmt, ...) {
 
 constexpr int64_t kLdsReserve = 1536;      // reduction scratch (8 waves x 8 worker slots x 2 doubles) + slack
 constexpr int kMaxRounds = 4;              // at most this many rounds of resident workgroups per launch
+constexpr double kWorkgroupOverheadTiles = 6.0;   // what a state workgroup costs besides its tiles, in tiles
 // the planner's cost model, in vector-ALU instructions per coordinate
 constexpr double kElementCost = 6.5;       // load / unpack / drift / fixed point / scalar sums of one slab element
 constexpr double kNegateCost = 2.0;        // ... its negated term, when the rows are not sign-split
@@ -198,20 +199,22 @@ int make_split(const fda_desc* d, int cus, int64_t lds_cu, int cell_bytes, Split
   // one workgroup per CU: the kernels hold more registers than two resident workgroups would allow
   const int occ = 1;
   const int64_t tile = (int64_t)fda::kStateThreads * vec;
-  // Partitions: all workgroups do the same amount of work, so the launch should fill the
-  // resident slots a whole number of times.  Try 1..4 rounds and keep the best-filled one.
+  // Partitions: all workgroups do the same amount of work, so the launch should fill the resident
+  // slots a whole number of times; and a workgroup costs its set-up, reductions and flush on top of
+  // its tiles (measured: about six tiles' worth).  Try 1..4 rounds of resident workgroups and keep
+  // the cheapest: rounds x (tiles per workgroup + overhead).
   const int64_t slots = (int64_t)cus * occ, gr = (int64_t)bestG * bestR;
+  const int64_t tiles = (d->d + tile - 1) / tile;
   int64_t P = 8;
-  double best_fill = -1.0;
+  double best_time = -1.0;
   for (int rounds = 1; rounds <= kMaxRounds; ++rounds) {
     int64_t cand = slots * rounds / gr / 8 * 8;
     if (cand < 8) cand = 8;
+    if (cand > round_up(tiles, 8)) cand = round_up(tiles, 8);
     const int64_t wgs = cand * gr;
-    const double fill = (double)wgs / (double)((wgs + slots - 1) / slots * slots);
-    if (fill > best_fill + 0.02) { best_fill = fill; P = cand; }
+    const double est = (double)((wgs + slots - 1) / slots) * ((double)((tiles + cand - 1) / cand) + kWorkgroupOverheadTiles);
+    if (best_time < 0.0 || est < best_time * 0.98) { best_time = est; P = cand; }
   }
-  const int64_t tiles = (d->d + tile - 1) / tile;
-  if (P > round_up(tiles, 8)) P = round_up(tiles, 8);
   sp->P = (int)P;
   sp->chunk = round_up((d->d + P - 1) / P, tile);
   return FDA_OK;

@@ -719,25 +719,31 @@ state_kernel(const StateParams prm) {
     const int allcells = prm.l * prm.m;
     unsigned long long* out = reinterpret_cast<unsigned long long*>(prm.part_sk);
     bool left_band = false;
-    for (int t = tid; t < kcnt * cells; t += kStateThreads) {
-      const int k = t / cells, c = t - k * cells;
-      unsigned long long val;
-      if constexpr (CELL == kCellI32) {
-        const int i = c / prm.m, bkt = c - i * prm.m;
-        const uint32_t* row = reinterpret_cast<const uint32_t*>(lds_raw) + (size_t)i * row_words32 + k;
-        const uint32_t word = row[cells32_bucket_word((uint32_t)bkt, KC)];
-        left_band = left_band || (word & 0x80000000u) != 0u;      // the last additions are examined here
-        long long sum = (long long)(int)(word - kCellBias);
-        if constexpr (SPLIT) {
-          const uint32_t minus = row[cells32_bucket_word((uint32_t)(bkt + prm.m), KC)];
-          left_band = left_band || (minus & 0x80000000u) != 0u;
-          sum -= (long long)(int)(minus - kCellBias);
+    if constexpr (CELL == kCellI32) {
+      // a wave takes one (row, worker) at a time, its lanes the buckets: no divisions per cell
+      const uint32_t* words = reinterpret_cast<const uint32_t*>(lds_raw);
+      for (int combo = wave; combo < rcnt * kcnt; combo += kWaves) {
+        const int i = combo / kcnt, k = combo - i * kcnt;
+        const uint32_t* row = words + (size_t)i * row_words32 + k;
+        unsigned long long* dst = out + ((size_t)p * prm.K + kstart + k) * allcells + (size_t)(rstart + i) * prm.m;
+        for (int bkt = lane; bkt < prm.m; bkt += 64) {
+          const uint32_t word = row[cells32_bucket_word((uint32_t)bkt, KC)];
+          left_band = left_band || (word & 0x80000000u) != 0u;      // the last additions are examined here
+          long long sum = (long long)(int)(word - kCellBias);
+          if constexpr (SPLIT) {
+            const uint32_t minus = row[cells32_bucket_word((uint32_t)(bkt + prm.m), KC)];
+            left_band = left_band || (minus & 0x80000000u) != 0u;
+            sum -= (long long)(int)(minus - kCellBias);
+          }
+          dst[bkt] = (unsigned long long)sum;
         }
-        val = (unsigned long long)sum;
-      } else {
-        val = reinterpret_cast<const unsigned long long*>(lds_raw)[(size_t)c * prm.stride + k];
       }
-      out[((size_t)p * prm.K + kstart + k) * allcells + (size_t)rstart * prm.m + c] = val;
+    } else {
+      for (int t = tid; t < kcnt * cells; t += kStateThreads) {
+        const int k = t / cells, c = t - k * cells;
+        out[((size_t)p * prm.K + kstart + k) * allcells + (size_t)rstart * prm.m + c] =
+            reinterpret_cast<const unsigned long long*>(lds_raw)[(size_t)c * prm.stride + k];
+      }
     }
     if constexpr (CELL == kCellI32) {
       if (left_band) prm.scale->flag32 = 1;
