@@ -288,18 +288,23 @@ def main():
                 "traffic": traffic, "traffic_source": traffic_source, "algorithmic_bytes": abytes,
                 "kernel_ms": round(kern_ms_avg, 4), "launches": launches}
     if args.variants & 2:
-        # what actually bounds this kernel: one LDS atomic add per (worker, sketch row, coordinate).
-        # The ceiling is measured here, by the library's calibration kernel: returning 32-bit LDS
-        # atomic adds on random cells, per lane, clock (the device's reported rate) and compute unit.
+        # what actually bounds this kernel: one LDS cell update per (worker, sketch row, coordinate).
+        # With an even number of worker slots one returning 64-bit LDS addition updates the cells of
+        # two workers; otherwise a returning 32-bit addition updates one.  The ceiling is measured
+        # here, by the library's calibration kernel: such additions on random cells, per lane, clock
+        # (the device's reported rate) and compute unit, times the cells an addition updates.
         props = torch.cuda.get_device_properties(0)
         sink = torch.zeros(4, dtype=torch.int32, device=dev)
-        ceiling, ghz = F.fda_calib_lds_atomics(F.LDS_OPS["u32_rtn"], F.LDS_PATTERNS["random"], 2000,
-                                               sink.data_ptr(), torch.cuda.current_stream().cuda_stream)
-        adds = float(wl.l) * K * d
-        roofline["lds_atomic_adds_per_clk_per_cu"] = round(
-            adds / (kern_ms_avg * 1e-3) / props.multi_processor_count / (ghz * 1e9), 2)
-        roofline["lds_atomic_ceiling_per_clk_per_cu"] = round(ceiling, 2)
-        roofline["lds_ceiling_source"] = "fda_calib_lds_atomics(u32_rtn, random), measured in this run"
+        paired = mon.plan["worker_slots"] % 2 == 0
+        op = "u64_rtn" if paired else "u32_rtn"
+        rate, ghz = F.fda_calib_lds_atomics(F.LDS_OPS[op], F.LDS_PATTERNS["random"], 2000,
+                                            sink.data_ptr(), torch.cuda.current_stream().cuda_stream)
+        updates = float(wl.l) * K * d
+        roofline["lds_cell_updates_per_clk_per_cu"] = round(
+            updates / (kern_ms_avg * 1e-3) / props.multi_processor_count / (ghz * 1e9), 2)
+        roofline["lds_cell_update_ceiling_per_clk_per_cu"] = round(rate * (2 if paired else 1), 2)
+        roofline["lds_ceiling_source"] = (f"fda_calib_lds_atomics({op}, random) x {2 if paired else 1} cells per "
+                                          "addition, measured in this run")
         roofline["clock_ghz"] = ghz
 
     # The same step with the average state computed directly (fda_mean_state: sketch of the mean

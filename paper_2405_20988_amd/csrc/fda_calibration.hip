@@ -78,7 +78,7 @@ calib_copy_kernel(const u32x4* __restrict__ src, u32x4* __restrict__ dst, long l
 // Every lane holds eight cell indices, fixed for the whole launch, and re-issues one atomic addition to
 // each of them per iteration: almost no vector-ALU work, so the rate is the LDS's own.
 //   OP       0: 32-bit integer add that returns the old value   1: 32-bit integer add, no return
-//            2: 64-bit integer add   3: fp64 add   4: fp32 add
+//            2: 64-bit integer add   3: fp64 add   4: fp32 add   5: 64-bit integer add that returns the old value
 //   PATTERN  0: every lane an independent random cell
 //            1: lane t the cell t (no two lanes of an instruction on one bank)
 //            2/3/4/5: groups of 4/8/16/32 lanes share a random group of consecutive cells, lane q of
@@ -91,7 +91,7 @@ calib_lds_kernel(int iters, uint32_t* __restrict__ sink) {
   const int tid = threadIdx.x, lane = tid & 63;
   for (int t = tid; t < kLdsWords; t += kLdsThreads) words[t] = 0u;
   __syncthreads();
-  constexpr int kWordsPerCell = (OP == 2 || OP == 3) ? 2 : 1;
+  constexpr int kWordsPerCell = (OP == 2 || OP == 3 || OP == 5) ? 2 : 1;
   constexpr int kCells = kLdsWords / kWordsPerCell;
   uint32_t idx[8];
   uint32_t s = (uint32_t)tid * 2654435761u + blockIdx.x * 97u + 12345u;
@@ -110,6 +110,7 @@ calib_lds_kernel(int iters, uint32_t* __restrict__ sink) {
     }
   }
   uint32_t seen = 0u;
+  unsigned long long seen64 = 0ull;
   for (int it = 0; it < iters; ++it) {
 #pragma unroll
     for (int q = 0; q < 8; ++q) {
@@ -118,10 +119,11 @@ calib_lds_kernel(int iters, uint32_t* __restrict__ sink) {
       if constexpr (OP == 2) atomicAdd(reinterpret_cast<unsigned long long*>(raw) + idx[q], 3ull);
       if constexpr (OP == 3) atomicAdd(reinterpret_cast<double*>(raw) + idx[q], 1.0);
       if constexpr (OP == 4) atomicAdd(reinterpret_cast<float*>(raw) + idx[q], 1.0f);
+      if constexpr (OP == 5) seen64 |= atomicAdd(reinterpret_cast<unsigned long long*>(raw) + idx[q], 3ull);
     }
   }
   __syncthreads();
-  uint32_t acc = seen & 1u;
+  uint32_t acc = (seen & 1u) + (uint32_t)(seen64 >> 63);
   for (int t = tid; t < kLdsWords; t += kLdsThreads) acc += words[t];
   if (acc == 0x9e3779b9u) *sink = acc;                 // keeps the additions alive
 }
@@ -150,6 +152,7 @@ hipError_t launch_lds_any(int op, int pattern, int blocks, int iters, uint32_t* 
     case 2: return launch_lds<2>(pattern, blocks, iters, sink, st, setup);
     case 3: return launch_lds<3>(pattern, blocks, iters, sink, st, setup);
     case 4: return launch_lds<4>(pattern, blocks, iters, sink, st, setup);
+    case 5: return launch_lds<5>(pattern, blocks, iters, sink, st, setup);
   }
   return hipErrorInvalidValue;
 }
@@ -203,7 +206,7 @@ int fda_calib_stream(int mode, const void* src, void* dst, size_t bytes, int rep
 
 int fda_calib_lds_atomics(int op, int pattern, int iters, void* sink_dev, void* stream,
                           double* lane_ops_per_clock_per_cu, double* clock_ghz) {
-  if (lane_ops_per_clock_per_cu == nullptr || sink_dev == nullptr || iters < 1 || op < 0 || op > 4 ||
+  if (lane_ops_per_clock_per_cu == nullptr || sink_dev == nullptr || iters < 1 || op < 0 || op > 5 ||
       pattern < 0 || pattern > 5)
     return FDA_EINVAL;
   hipStream_t st = static_cast<hipStream_t>(stream);
