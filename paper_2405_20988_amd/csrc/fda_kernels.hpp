@@ -267,6 +267,26 @@ __device__ __forceinline__ uint32_t rec_field(const uint32_t (&rec)[RecGeom<LR, 
   return __builtin_amdgcn_alignbit(rec[dw + 1 < RecGeom<LR, FB>::kDwords ? dw + 1 : dw], rec[dw], sh);
 }
 
+// the same field, exactly (nothing above its FB bits): one bit-field extract where the field lies inside a
+// dword (when it ends at bit 32 the shift alone), a funnel shift and an extract where it straddles two.
+// (Written as the instruction: from the plain expression the compiler makes a shift and a mask and then
+// cannot fold the scaling of the field into the address computation.)
+template <int WIDTH>
+__device__ __forceinline__ uint32_t bit_field(uint32_t x, uint32_t off) {     // off: the same in every lane
+  uint32_t r;
+  asm("v_bfe_u32 %0, %1, %2, %3" : "=v"(r) : "v"(x), "s"(off), "n"(WIDTH));
+  __builtin_assume(r < (1u << WIDTH));
+  return r;
+}
+template <int LR, int FB>
+__device__ __forceinline__ uint32_t rec_field_exact(const uint32_t (&rec)[RecGeom<LR, FB>::kDwords], int v, int i) {
+  const int bit = v * 16 * RecGeom<LR, FB>::kWords + i * FB;
+  const int dw = bit >> 5, sh = bit & 31;
+  if (sh + FB == 32) return rec[dw] >> sh;
+  if (sh + FB < 32) return bit_field<FB>(rec[dw], (uint32_t)sh);
+  return bit_field<FB>(__builtin_amdgcn_alignbit(rec[dw + 1 < RecGeom<LR, FB>::kDwords ? dw + 1 : dw], rec[dw], sh), 0u);
+}
+
 // One lane's share of a tile, as loaded: V coordinates of w_t0, xi, of each worker's row and
 // the V hash records.
 constexpr int kStateV = 4;       // coordinates a lane owns per tile (fp32: 16 bytes, bf16: 8 bytes)
@@ -564,7 +584,7 @@ state_kernel(const StateParams prm) {
           }
 #pragma unroll
           for (int i = 0; i < LR; ++i) {
-            const uint32_t s = rec_field<LR, FB>(t.rec, v, i) & Geom::kFieldMask;
+            const uint32_t s = rec_field_exact<LR, FB>(t.rec, v, i);
             // sign-split rows add the term itself to bucket s; otherwise s >= m means sign -1, bucket s - m
             const bool neg = !SPLIT && s >= (uint32_t)prm.m;
             const uint32_t bucket = neg ? s - (uint32_t)prm.m : s;

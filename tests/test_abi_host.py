@@ -96,6 +96,9 @@ def test_plan_of_the_five_configs(name):
     tile = p.threads * 4                       # a lane owns 4 coordinates of a tile, whatever the slab type
     assert p.chunk % tile == 0
     assert p.worker_slots >= p.workers_per_group and p.sign_split_rows in (0, 1)
+    # all five have LDS to spare for sign-split rows (an even number of worker slots, paired additions)
+    assert p.sign_split_rows == 1 and p.worker_slots % 2 == 0
+    assert p.worker_groups * p.row_groups * p.partitions <= 4 * 256
     # the partial buffers fit in the workspace
     need = p.partitions * c["K"] * (16 + 8 * c["l"] * c["m"])
     assert p.workspace_bytes >= need
@@ -108,6 +111,31 @@ def test_plan_of_the_five_configs(name):
     # sketch bytes the paper quotes for 5 x 250: l * m * 4 = 5 kB (Section 3.3)
     if (c["l"], c["m"]) == (5, 250):
         assert (p.state_floats - 2) * 4 == 5000
+
+
+def test_plan_chooses_the_rows_the_lds_allows():
+    """Sign-split rows need 2 m buckets per row: where even a single row of them does not fit, or more
+    worker groups would cost more than the selects they save, the rows stay plain."""
+    coef = S.hash_coefficients(0, 16)
+
+    def plan(K, l, m, d=10**6, dt=F.FDA_F32):
+        desc, keep = make_desc(K, d, dt, 3, l, m, 0.06, coef[:l])
+        return F.fda_plan(desc, 256, 163840)
+    p = plan(2, 3, 6_000)                  # 3 x 6000 x 2 slots: 144 KB plain, split would need 288
+    assert (p.worker_groups, p.worker_slots, p.row_groups, p.sign_split_rows) == (1, 2, 1, 0)
+    p = plan(4, 2, 4_500)                  # two groups of two slots with split rows instead of one of four
+    assert (p.worker_groups, p.worker_slots, p.sign_split_rows) == (2, 2, 1)
+    p = plan(1, 5, 250)                    # a single worker: one slot, 32-bit additions, plain rows
+    assert (p.worker_slots, p.sign_split_rows) == (1, 0)
+    p = plan(3, 5, 250)                    # three workers take a kernel of four slots (one spare)
+    assert (p.worker_groups, p.worker_slots, p.sign_split_rows) == (1, 4, 1)
+    p = plan(3, 1, 19_000)                 # one slot per workgroup: the row fills the LDS
+    assert (p.worker_groups, p.worker_slots, p.sign_split_rows) == (3, 1, 0)
+    p = plan(8, 7, 1000, 350_000_000, F.FDA_BF16)       # cfg5: four groups of two, one round of 256 workgroups
+    assert (p.worker_groups, p.worker_slots, p.partitions, p.sign_split_rows) == (4, 2, 64, 1)
+    p = plan(30, 5, 250, 7_000_000)                       # cfg3: one round of 240 workgroups, not three of 760
+    assert (p.worker_groups, p.worker_slots, p.partitions) == (5, 6, 48)
+    assert p.lds_bytes <= 163840
 
 
 def test_plan_of_the_mean_state_pass_splits_rows_only_when_it_must():
