@@ -208,9 +208,9 @@ int make_split(const fda_desc* d, int cus, int64_t lds_cu, int cell_bytes, Split
   int64_t P = 8;
   double best_time = -1.0;
   for (int rounds = 1; rounds <= kMaxRounds; ++rounds) {
-    int64_t cand = slots * rounds / gr / 8 * 8;
-    if (cand < 8) cand = 8;
-    if (cand > round_up(tiles, 8)) cand = round_up(tiles, 8);
+    int64_t cand = slots * rounds / gr;                 // (whole groups of 8 partitions share an XCD each)
+    if (cand < 1) cand = 1;
+    if (cand > tiles) cand = tiles;
     const int64_t wgs = cand * gr;
     const double est = (double)((wgs + slots - 1) / slots) * ((double)((tiles + cand - 1) / cand) + kWorkgroupOverheadTiles);
     if (best_time < 0.0 || est < best_time * 0.98) { best_time = est; P = cand; }

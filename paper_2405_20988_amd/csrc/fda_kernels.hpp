@@ -61,7 +61,7 @@ struct StateParams {
   int m;
   int G;                  // worker groups
   int R;                  // sketch-row groups (workgroups of one worker group share the data)
-  int P;                  // coordinate partitions, multiple of 8
+  int P;                  // coordinate partitions
   int stride;             // 8-byte-cell passes: LDS cells per bucket (>= worker slots of the group, odd)
   int do_lin;
   int do_sk;
@@ -398,11 +398,21 @@ state_kernel(const StateParams prm) {
   // XCD-aware placement: consecutive workgroup ids go round-robin over the 8 XCDs, so the
   // G*R workgroups that read the same coordinates (and share w_t0 / xi / slab rows / table
   // rows) get ids that land on one XCD and its L2.
+  // (Partitions beyond the last multiple of 8 take the ids that are left, in order: their workgroups are
+  // spread over the XCDs and fill the CUs that whole groups of 8 partitions would leave idle.)
   const int b = blockIdx.x;
-  const int xcd = b & 7, slot = b >> 3;
   const int GR = prm.G * prm.R;
-  const int gr = slot % GR;
-  const int p = (slot / GR) * 8 + xcd;
+  const int aligned = (prm.P & ~7) * GR;               // workgroups of the XCD-aligned partitions
+  int gr, p;
+  if (b < aligned) {
+    const int xcd = b & 7, slot = b >> 3;
+    gr = slot % GR;
+    p = (slot / GR) * 8 + xcd;
+  } else {
+    const int e = b - aligned;
+    gr = e % GR;
+    p = (prm.P & ~7) + e / GR;
+  }
   const int g = gr / prm.R, r = gr - g * prm.R;
   int kstart, kcnt, rstart = 0, rcnt = 0;
   group_range(prm.K, prm.G, g, &kstart, &kcnt);

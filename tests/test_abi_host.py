@@ -90,7 +90,7 @@ def test_plan_of_the_five_configs(name):
     assert p.state_floats == 2 + c["l"] * c["m"]
     assert p.worker_groups * p.workers_per_group >= c["K"]
     assert p.workers_per_group <= 8
-    assert p.partitions % 8 == 0 and p.partitions >= 8
+    assert p.partitions >= 1
     assert p.lds_bytes <= 163840
     assert p.partitions * p.chunk >= c["d"]
     tile = p.threads * 4                       # a lane owns 4 coordinates of a tile, whatever the slab type
@@ -133,8 +133,8 @@ def test_plan_chooses_the_rows_the_lds_allows():
     assert (p.worker_groups, p.worker_slots, p.sign_split_rows) == (3, 1, 0)
     p = plan(8, 7, 1000, 350_000_000, F.FDA_BF16)       # cfg5: four groups of two, one round of 256 workgroups
     assert (p.worker_groups, p.worker_slots, p.partitions, p.sign_split_rows) == (4, 2, 64, 1)
-    p = plan(30, 5, 250, 7_000_000)                       # cfg3: one round of 240 workgroups, not three of 760
-    assert (p.worker_groups, p.worker_slots, p.partitions) == (5, 6, 48)
+    p = plan(30, 5, 250, 7_000_000)                       # cfg3: one round of 255 workgroups, not three of 760
+    assert (p.worker_groups, p.worker_slots, p.partitions) == (5, 6, 51)
     assert p.lds_bytes <= 163840
 
 
