@@ -45,6 +45,7 @@ int fail(int code, const char* fmt, ...) {
 
 constexpr int64_t kLdsReserve = 1536;      // reduction scratch (8 waves x 8 worker slots x 2 doubles) + slack
 constexpr int kMaxRounds = 4;              // at most this many rounds of resident workgroups per launch
+constexpr int64_t kMaxTermsPlanned = 12000;    // terms per 32-bit cell and workgroup the planner allows for
 constexpr double kWorkgroupOverheadTiles = 6.0;   // what a state workgroup costs besides its tiles, in tiles
 // the planner's cost model, in vector-ALU instructions per coordinate
 constexpr double kElementCost = 6.5;       // load / unpack / drift / fixed point / scalar sums of one slab element
@@ -214,6 +215,13 @@ int make_split(const fda_desc* d, int cus, int64_t lds_cu, int cell_bytes, Split
     const int64_t wgs = cand * gr;
     const double est = (double)((wgs + slots - 1) / slots) * ((double)((tiles + cand - 1) / cand) + kWorkgroupOverheadTiles);
     if (best_time < 0.0 || est < best_time * 0.98) { best_time = est; P = cand; }
+  }
+  // 32-bit cells take up to 16384 terms (scale_kernel sends fuller ones to the 64-bit pass): with m (or,
+  // sign-split, 2 m) cells per row a chunk should put about 12000 into a cell at most
+  if (narrow && cells) {
+    const int64_t per_row = (int64_t)d->m * (bestSplit ? 2 : 1);
+    const int64_t pmin = (d->d + per_row * kMaxTermsPlanned - 1) / (per_row * kMaxTermsPlanned);
+    if (P < pmin) P = pmin < tiles ? pmin : tiles;
   }
   sp->P = (int)P;
   sp->chunk = round_up((d->d + P - 1) / P, tile);
@@ -496,11 +504,11 @@ int prepare_sketch(fda_ctx* ctx, const void* w, const float* w_t0, fda::ScaleInf
     hipLaunchKernelGGL(fda::clear_u32_kernel, dim3(1), dim3(64), 0, st, nmax, 2);
     FDA_HIP(hipGetLastError());
     hipLaunchKernelGGL(fda::cell_count_kernel, dim3(pl.narrow.P * d.l), dim3(fda::kStateThreads),
-                       (size_t)d.m * 4, st, ctx->coef, d.l, d.m, (long long)d.d,
-                       (long long)pl.narrow.chunk, nmax);
+                       (size_t)d.m * 4 * (pl.narrow.split ? 2 : 1), st, ctx->coef, d.l, d.m, pl.narrow.split,
+                       (long long)d.d, (long long)pl.narrow.chunk, nmax);
     FDA_HIP(hipGetLastError());
     hipLaunchKernelGGL(fda::cell_count_kernel, dim3(pl.wide.P * d.l), dim3(fda::kStateThreads),
-                       (size_t)d.m * 4, st, ctx->coef, d.l, d.m, (long long)d.d,
+                       (size_t)d.m * 4, st, ctx->coef, d.l, d.m, 0, (long long)d.d,
                        (long long)pl.wide.chunk, nmax + 1);
     FDA_HIP(hipGetLastError());
     ctx->counted = true;

@@ -71,22 +71,26 @@ hash_table_kernel(const HashCoef hc, int l, int R, int slots, int m, int fb, int
 // exact maximum, over workgroups, rows and buckets, of the number of coordinates of the
 // workgroup's chunk that fall into the bucket.  It bounds the number of terms of any LDS cell.
 __global__ void __launch_bounds__(kStateThreads)
-cell_count_kernel(const HashCoef hc, int l, int m, long long d, long long chunk,
+cell_count_kernel(const HashCoef hc, int l, int m, int split, long long d, long long chunk,
                   unsigned int* __restrict__ nmax) {   // nmax: the entry to raise
+  // split: the pass keeps the two signs of a bucket in cells of their own (sign-split rows)
   extern __shared__ __align__(16) unsigned char lds_raw[];
   unsigned int* cnt = reinterpret_cast<unsigned int*>(lds_raw);
   __shared__ unsigned int shmax[kStateThreads / 64];
   const int p = blockIdx.x / l, i = blockIdx.x - p * l;
-  for (int t = threadIdx.x; t < m; t += kStateThreads) cnt[t] = 0u;
+  const int ncell = split ? 2 * m : m;
+  for (int t = threadIdx.x; t < ncell; t += kStateThreads) cnt[t] = 0u;
   __syncthreads();
   const long long cbeg = (long long)p * chunk;
   long long cend = cbeg + chunk;
   if (cend > d) cend = d;
-  for (long long j = cbeg + threadIdx.x; j < cend; j += kStateThreads)
-    atomicAdd(cnt + (hash_entry(hc, i, (uint32_t)j, (uint32_t)m) & 0x7fffu), 1u);
+  for (long long j = cbeg + threadIdx.x; j < cend; j += kStateThreads) {
+    const uint32_t h = hash_entry(hc, i, (uint32_t)j, (uint32_t)m);
+    atomicAdd(cnt + (h & 0x7fffu) + ((split && (h >> 15)) ? m : 0), 1u);
+  }
   __syncthreads();
   unsigned int mx = 0u;
-  for (int t = threadIdx.x; t < m; t += kStateThreads) mx = max(mx, cnt[t]);
+  for (int t = threadIdx.x; t < ncell; t += kStateThreads) mx = max(mx, cnt[t]);
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) mx = max(mx, (unsigned int)__shfl_down((int)mx, o, 64));
   if ((threadIdx.x & 63) == 0) shmax[threadIdx.x >> 6] = mx;

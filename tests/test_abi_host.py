@@ -136,6 +136,13 @@ def test_plan_chooses_the_rows_the_lds_allows():
     p = plan(30, 5, 250, 7_000_000)                       # cfg3: one round of 255 workgroups, not three of 760
     assert (p.worker_groups, p.worker_slots, p.partitions) == (5, 6, 51)
     assert p.lds_bytes <= 163840
+    # a 32-bit cell takes 16384 terms at most: narrow sketches get more partitions than one round of
+    # workgroups needs, so that a cell of a workgroup expects about 12000 terms at most
+    for K, l, m, d in ((8, 9, 250, 350_000_000), (2, 2, 8, 300_000_000), (1, 1, 1, 40_000_000)):
+        p = plan(K, l, m, d, F.FDA_BF16)
+        cells_per_row = m * (2 if p.sign_split_rows else 1)
+        assert p.chunk <= cells_per_row * 12_000 + p.threads * 4, (K, l, m, p.as_dict())
+        assert p.partitions * p.chunk >= d
 
 
 def test_plan_of_the_mean_state_pass_splits_rows_only_when_it_must():
