@@ -99,6 +99,7 @@ STATE_CASES = [
     ("cfg2", 30_011, {"K": 5, "l": 6, "m": 64}),        # 6 slots x 6 rows are not built: groups of 2, 2, 1 workers
     ("cfg2", 30_011, {"K": 5, "l": 5, "m": 64}),        # five workers in six slots: a spare high half
     ("cfg5", 40_009, {"K": 8, "l": 4, "m": 300}),       # bf16, eight slots
+    ("cfg2", 20_011, {"K": 2, "l": 1, "m": 20_000}),    # about the widest sketch the LDS takes: 16-bit table fields up to 2 m - 1
 ]
 EXPECTED_ROWS = {(2, 3, 6_000): (2, 0), (4, 2, 4_500): (2, 1), (5, 6, 64): (2, 1), (5, 5, 64): (6, 1), (8, 4, 300): (8, 1)}
 
