@@ -46,6 +46,7 @@ int fail(int code, const char* fmt, ...) {
 constexpr int64_t kLdsReserve = 1536;      // reduction scratch (8 waves x 8 worker slots x 2 doubles) + slack
 constexpr int kMaxRounds = 4;              // at most this many rounds of resident workgroups per launch
 constexpr int64_t kMaxTermsPlanned = 12000;    // terms per 32-bit cell and workgroup the planner allows for
+constexpr int64_t kMaxTermsPlannedSplit = 3500;   // ... per cell of a sign-split row
 constexpr double kWorkgroupOverheadTiles = 6.0;   // what a state workgroup costs besides its tiles, in tiles
 // the planner's cost model, in vector-ALU instructions per coordinate
 constexpr double kElementCost = 6.5;       // load / unpack / drift / fixed point / scalar sums of one slab element
@@ -202,26 +203,35 @@ int make_split(const fda_desc* d, int cus, int64_t lds_cu, int cell_bytes, Split
   const int64_t tile = (int64_t)fda::kStateThreads * vec;
   // Partitions: all workgroups do the same amount of work, so the launch should fill the resident
   // slots a whole number of times; and a workgroup costs its set-up, reductions and flush on top of
-  // its tiles (measured: about six tiles' worth).  Try 1..4 rounds of resident workgroups and keep
-  // the cheapest: rounds x (tiles per workgroup + overhead).
+  // its tiles (measured: about six tiles' worth).  Among the first few feasible numbers of rounds of
+  // resident workgroups keep the cheapest: rounds x (tiles per workgroup + overhead).
+  // Feasible: 32-bit cells take up to 16384 terms (scale_kernel sends fuller ones to the 64-bit pass), so
+  // a chunk should put about 12000 into a cell at most.  The cells of sign-split rows take the terms of one
+  // hash sign each, which do not cancel when the drifts themselves lean one way: they are kept at about
+  // 3500 expected terms (a term of mean magnitude is 2^18..2^19 units: the band of 2^30 then holds unless
+  // more than about half of a cell's mass leans one way -- such a call finishes on the 64-bit cells).
   const int64_t slots = (int64_t)cus * occ, gr = (int64_t)bestG * bestR;
   const int64_t tiles = (d->d + tile - 1) / tile;
-  int64_t P = 8;
+  int64_t pmin = 1;
+  if (narrow && cells) {
+    const int64_t per_row = (int64_t)d->m * (bestSplit ? 2 : 1);
+    const int64_t terms = bestSplit ? kMaxTermsPlannedSplit : kMaxTermsPlanned;
+    pmin = (d->d + per_row * terms - 1) / (per_row * terms);
+    if (pmin > tiles) pmin = tiles;
+  }
+  int64_t P = 0;
   double best_time = -1.0;
-  for (int rounds = 1; rounds <= kMaxRounds; ++rounds) {
+  int tried = 0;
+  for (int64_t rounds = 1; tried < kMaxRounds; ++rounds) {
     int64_t cand = slots * rounds / gr;                 // (whole groups of 8 partitions share an XCD each)
     if (cand < 1) cand = 1;
     if (cand > tiles) cand = tiles;
+    if (cand < pmin) continue;                          // more rounds are needed: cand grows with them
+    ++tried;
     const int64_t wgs = cand * gr;
     const double est = (double)((wgs + slots - 1) / slots) * ((double)((tiles + cand - 1) / cand) + kWorkgroupOverheadTiles);
     if (best_time < 0.0 || est < best_time * 0.98) { best_time = est; P = cand; }
-  }
-  // 32-bit cells take up to 16384 terms (scale_kernel sends fuller ones to the 64-bit pass): with m (or,
-  // sign-split, 2 m) cells per row a chunk should put about 12000 into a cell at most
-  if (narrow && cells) {
-    const int64_t per_row = (int64_t)d->m * (bestSplit ? 2 : 1);
-    const int64_t pmin = (d->d + per_row * kMaxTermsPlanned - 1) / (per_row * kMaxTermsPlanned);
-    if (P < pmin) P = pmin < tiles ? pmin : tiles;
+    if (cand == tiles) break;                           // one tile per workgroup: nothing finer
   }
   sp->P = (int)P;
   sp->chunk = round_up((d->d + P - 1) / P, tile);

@@ -141,7 +141,8 @@ def test_plan_chooses_the_rows_the_lds_allows():
     for K, l, m, d in ((8, 9, 250, 350_000_000), (2, 2, 8, 300_000_000), (1, 1, 1, 40_000_000)):
         p = plan(K, l, m, d, F.FDA_BF16)
         cells_per_row = m * (2 if p.sign_split_rows else 1)
-        assert p.chunk <= cells_per_row * 12_000 + p.threads * 4, (K, l, m, p.as_dict())
+        terms = 3_500 if p.sign_split_rows else 12_000      # cells of one hash sign do not cancel a common lean
+        assert p.chunk <= cells_per_row * terms + p.threads * 4, (K, l, m, p.as_dict())
         assert p.partitions * p.chunk >= d
 
 

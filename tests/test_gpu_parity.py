@@ -129,6 +129,35 @@ def test_state_and_estimate_parity(name, d, over):
     mon.close()
 
 
+def test_drifts_that_lean_one_way():
+    """Sign-split rows keep the terms of one hash sign in a cell, so drifts that lean one way do not cancel
+    there.  The planner keeps such cells at about 3500 expected terms at most; with a sketch so narrow that
+    every workgroup's cells are about that full, drifts with a third of their mass leaning one way must
+    finish on the 32-bit cells, and drifts that are all positive must match the oracle whichever cells
+    they end on."""
+    say("[case] leaning drifts, sketch 3 x 2")
+    import paper_2405_20988_amd as F
+    K, d, l, m = 2, 3_584_007, 3, 2
+    g = torch.Generator(device=DEV)
+    g.manual_seed(77)
+    coef = S.hash_coefficients(5, l)
+    w_t0 = torch.randn(d, generator=g, device=DEV) * 0.05
+    xi = torch.randn(d, generator=g, device=DEV) / d ** 0.5
+    mon = F.FdaMonitor(K, d, "f32", 3, l, m, 0.06, coef, device=DEV)
+    say(f"       plan {mon.plan}")
+    assert mon.plan["sign_split_rows"] == 1
+    assert 2 * m * 1_500 <= mon.plan["chunk"] <= 2 * m * 3_500 + 2048      # the cells do get about that full
+    noise = torch.randn((K, d), generator=g, device=DEV)
+    for what, drift in (("a third leaning", (noise + 0.3) * 1e-3), ("all positive", noise.abs() * 1e-3)):
+        w = (w_t0 + drift).contiguous()
+        mon.local_state(w, w_t0, xi)
+        path = mon.last_state_path()
+        say(f"       {what}: sketch cells of kind {path}")
+        assert path == 0 if what == "a third leaning" else path in (0, 1)
+        check_state(mon, O.local_state(w.cpu().numpy(), "f32", w_t0.cpu().numpy(), xi.cpu().numpy(), coef, m))
+    mon.close()
+
+
 @pytest.mark.parametrize("variants", [1, 2])
 def test_single_variant(variants):
     say(f"[case] single variant {variants}")
