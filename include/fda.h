@@ -173,7 +173,8 @@ int fda_get_plan(const fda_ctx* ctx, fda_plan_info* out);
  * The pass works on drifts scaled by that 2^e, so a single drift 2^45 times the mean magnitude or
  * more makes ||u_k||^2 overflow to infinity (reported as a non-finite estimate) where the plain
  * fp32 square would overflow only at 2^64.
- * The first call of a context also tabulates the hash (2*l*d bytes of the workspace).
+ * The first call of a context also tabulates the hash into the workspace (one record per coordinate:
+ * 11 bits per sketch row, 16 for m > 1024, rounded up to whole 16-bit words; 10 bytes for l = 7).
  */
 int fda_local_state(fda_ctx* ctx, const void* w, const float* w_t0, const float* xi,
                     float* state, void* stream);
