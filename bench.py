@@ -2,7 +2,7 @@
 """Benchmark of the FDA local-state + variance-check path on one MI355X.
 
 A step is one pass of Algorithm 1 lines 6-9 over a synthetic [K, d] slab that is already
-resident in HBM: fda_local_state, fda_estimate_variance, then fda_sync and fda_update_xi
+resident in HBM: fda_local_state, fda_estimate_variance, then fda_sync_xi (fda_sync and fda_update_xi)
 predicated on the device-side decision (no host round trip inside a step).  The threshold
 is set above the estimate, so in the timed steps the decision is "no synchronization" --
 the case the method is built for -- and the metric is the cost of the state + check.  The
@@ -250,9 +250,10 @@ def main():
     def step():
         mon.local_state(wl.w, wl.w_t0, xi)
         mon.estimate_variance(theta, want_host=False)
-        mon.sync(wl.w, wl.w_t0, w_prev, pred=pred)
         if args.variants & 1:
-            mon.update_xi(wl.w_t0, w_prev, wl.xi, pred=pred)
+            mon.sync_xi(wl.w, wl.w_t0, w_prev, wl.xi, pred=pred)
+        else:
+            mon.sync(wl.w, wl.w_t0, w_prev, pred=pred)
 
     for _ in range(args.warmup):
         step()
@@ -315,9 +316,10 @@ def main():
         if not args.wbar:
             mon.mean_state(wl.w, wl.w_t0, xi)
             mon.estimate_variance_mean(theta, want_host=False)
-            mon.sync(wl.w, wl.w_t0, w_prev, pred=pred)
             if args.variants & 1:
-                mon.update_xi(wl.w_t0, w_prev, wl.xi, pred=pred)
+                mon.sync_xi(wl.w, wl.w_t0, w_prev, wl.xi, pred=pred)
+            else:
+                mon.sync(wl.w, wl.w_t0, w_prev, pred=pred)
         else:
             mon.mean_state(wl.w, wl.w_t0, xi, w_bar=w_bar)
             mon.estimate_variance_mean(theta, want_host=False)
@@ -343,7 +345,7 @@ def main():
     mean_info = {"what": "same step with fda_mean_state (average state by linearity of the sketch, no "
                          "per-worker states" + ("; also emits the average model" if args.wbar else "") +
                          ") + fda_estimate_variance_mean + predicated " +
-                         ("fda_sync_from_mean" if args.wbar else "fda_sync/fda_update_xi"),
+                         ("fda_sync_from_mean" if args.wbar else "fda_sync_xi"),
                  "ms_per_step": round(mean_ms, 4), "value": K * d / (mean_ms * 1e-3),
                  "unit": "worker-params/s", "kernel": "mean_state_kernel", "kernel_ms": round(mk, 4),
                  "achieved": round(abytes / (mk * 1e-3) / 1e9, 1), "peak": HBM_PEAK_GBS,
@@ -374,6 +376,17 @@ def main():
     ev1.record()
     torch.cuda.synchronize()
     xi_ms = ev0.elapsed_time(ev1) / reps
+    # both in one call, the norm taken inside the synchronization pass
+    # (w_t0 is moved before each call, outside the timed part: after a synchronization the mean equals
+    # w_t0, and a zero change would spare the scaling pass its reads)
+    pairs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
+    for e0, e1 in pairs:
+        wl.w_t0.add_(1e-3)
+        e0.record()
+        mon.sync_xi(wl.w, wl.w_t0, w_prev, wl.xi, pred=None)
+        e1.record()
+    torch.cuda.synchronize()
+    sync_xi_ms = sum(e0.elapsed_time(e1) for e0, e1 in pairs) / reps
     # the write-only synchronization from the average model fda_mean_state emitted (xi included)
     mon.mean_state(wl.w, wl.w_t0, xi, w_bar=w_bar)
     torch.cuda.synchronize()
@@ -391,8 +404,8 @@ def main():
     amortized = None
     if period is not None:
         amortized = {"sync_every_steps": period,
-                     "ms_per_step_incl_syncs": round(ms_per_step + (sync_ms + xi_ms) / period, 4),
-                     "mean_state_mode_ms_per_step_incl_syncs": round(mean_ms + (sync_ms + xi_ms) / period, 4)}
+                     "ms_per_step_incl_syncs": round(ms_per_step + sync_xi_ms / period, 4),
+                     "mean_state_mode_ms_per_step_incl_syncs": round(mean_ms + sync_xi_ms / period, 4)}
     # what this chip sustains for a plain copy with 16-byte accesses (read N, write N), the reference the
     # synchronization kernels' mix of reads and writes is compared with: measured here
     cal_n = min(K * d * esz, 2 << 30) // 16 * 16
@@ -411,7 +424,9 @@ def main():
                  "sync_from_mean_algorithmic_bytes": fused_bytes,
                  "sync_ms": round(sync_ms, 4), "sync_GBps": round(sync_bytes / sync_ms / 1e6, 1),
                  "sync_algorithmic_bytes": sync_bytes, "update_xi_ms": round(xi_ms, 4),
-                 "update_xi_GBps": round(20 * d / xi_ms / 1e6, 1)}
+                 "update_xi_GBps": round(20 * d / xi_ms / 1e6, 1),
+                 "sync_xi_ms": round(sync_xi_ms, 4), "sync_xi_algorithmic_bytes": sync_bytes + 12 * d,
+                 "sync_xi_GBps": round((sync_bytes + 12 * d) / sync_xi_ms / 1e6, 1)}
 
     out = {
         "metric": "worker-params/s (K*d per step) for local-state+variance check",
@@ -427,7 +442,7 @@ def main():
         "config": {"workload": workload, "K": K, "d": d, "slab_dtype": wl.dtype,
                    "sketch": f"{wl.l}x{wl.m}", "variants": args.variants,
                    "slab_bytes": K * d * esz, "plan": mon.plan,
-                   "step": "fda_local_state + fda_estimate_variance + predicated fda_sync/fda_update_xi "
+                   "step": "fda_local_state + fda_estimate_variance + predicated fda_sync_xi "
                            "(decision: no sync)"},
         "roofline": roofline,
         "mean_state_mode": mean_info,

@@ -258,6 +258,18 @@ int fda_sync(fda_ctx* ctx, void* w, float* w_t0, float* w_prev, const int32_t* p
              void* stream);
 
 /*
+ * Algorithm 1, line 9 followed by Section 3.2: fda_sync, then xi <- (w_t0 - w_prev) / ||w_t0 - w_prev||_2
+ * for the new w_t0 and the old one (now in w_prev) -- what fda_sync followed by fda_update_xi computes,
+ * except that the synchronization pass, which holds both models of every coordinate anyway, leaves
+ * the squared norm of their difference, so that the refresh of xi is one pass over the two vectors
+ * instead of two.  (The norm is the same sum of the same fp32 terms, added up in another fixed order:
+ * xi agrees with fda_update_xi's to the last bit or two.)
+ *   w, w_t0, pred_dev as in fda_sync;  w_prev and xi: DEVICE [d] fp32, both required
+ */
+int fda_sync_xi(fda_ctx* ctx, void* w, float* w_t0, float* w_prev, float* xi, const int32_t* pred_dev,
+                void* stream);
+
+/*
  * Algorithm 1, line 9 and Section 3.2 in one write-only pass, for a caller whose last
  * fda_mean_state of this context produced `w_bar` from the slab as it still is:
  *   w        DEVICE slab, rewritten: every row <- w_bar (bf16 slabs: round-to-nearest-even)
@@ -286,9 +298,9 @@ int fda_update_xi(fda_ctx* ctx, const float* w_t0, const float* w_prev, float* x
  * predicated on the device-side decision of the variant `decide_by` -- the synchronization and
  * the refresh of xi.  Exactly the calls above, in order:
  *   flags == 0:                    fda_local_state(state[K][S]), fda_estimate_variance,
- *                                  fda_sync, fda_update_xi
+ *                                  fda_sync_xi (fda_sync when xi == NULL)
  *   flags & FDA_STEP_MEAN_STATE:   fda_mean_state(state[S]), fda_estimate_variance_mean, then
- *                                  fda_sync + fda_update_xi, or, with w_bar != NULL (which
+ *                                  fda_sync_xi, or, with w_bar != NULL (which
  *                                  fda_mean_state then fills), fda_sync_from_mean
  *   decide_by   FDA_VARIANT_LINEAR or FDA_VARIANT_SKETCH (must be one of the context's variants)
  *   xi          read by the state pass (if LINEAR) and rewritten when the step synchronizes; with

@@ -103,6 +103,7 @@ def load_library():
                              C.POINTER(FdaEstimate), vp]
     lib.fda_sync.argtypes = [vp, vp, vp, vp, i32p, vp]
     lib.fda_update_xi.argtypes = [vp, vp, vp, vp, i32p, vp]
+    lib.fda_sync_xi.argtypes = [vp, vp, vp, vp, vp, i32p, vp]
     lib.fda_last_state_path.argtypes = [vp, C.POINTER(C.c_int32), vp]
     lib.fda_profile_enable.argtypes = [vp, C.c_int]
     lib.fda_profile_read.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(C.c_int64), C.c_int]
@@ -114,7 +115,7 @@ def load_library():
     for name in ("fda_estimate_variance_static", "fda_calib_stream", "fda_calib_lds_atomics", "fda_step", "fda_sync_from_mean", "fda_mean_state", "fda_estimate_variance_mean", "fda_last_mean_state_path",
                  "fda_last_state_path", "fda_profile_enable", "fda_profile_read", "fda_plan", "fda_workspace_bytes", "fda_create", "fda_destroy",
                  "fda_state_floats", "fda_get_plan", "fda_local_state",
-                 "fda_estimate_variance", "fda_sync", "fda_update_xi"):
+                 "fda_estimate_variance", "fda_sync", "fda_sync_xi", "fda_update_xi"):
         getattr(lib, name).restype = C.c_int
     _lib = lib
     return lib
@@ -227,6 +228,11 @@ def fda_estimate_variance_mean(ctx: int, mean_state: int, theta: float, tie_tol:
 def fda_sync(ctx: int, w: int, w_t0: int, w_prev: int | None, pred_dev: int | None = None,
              stream: int = 0) -> None:
     _check(load_library().fda_sync(ctx, w, w_t0, w_prev, pred_dev, stream), "fda_sync")
+
+
+def fda_sync_xi(ctx: int, w: int, w_t0: int, w_prev: int, xi: int, pred_dev: int | None = None,
+                stream: int = 0) -> None:
+    _check(load_library().fda_sync_xi(ctx, w, w_t0, w_prev, xi, pred_dev, stream), "fda_sync_xi")
 
 
 def fda_update_xi(ctx: int, w_t0: int, w_prev: int, xi: int, pred_dev: int | None = None,

@@ -61,6 +61,7 @@ constexpr int kMaxEstBlocksPerRow = 128;   // 32768 / 256: workgroups of estimat
 constexpr int kScaleSamples = 16384;       // sampled coordinates per worker for the scale
 constexpr int kScaleBlocks = kScaleSamples * fda::kScaleMaxSlices / fda::kSmallThreads;   // its workgroups, at most
 constexpr int kXiBlocks = 4096;
+constexpr int kSyncNormSlices = 64;   // the synchronization kernel's partial norms are condensed to this many
 constexpr long long kSyncVectorsPerBlock = 4 * fda::kSmallThreads;   // four trips per workgroup
 constexpr long long kStreamBytes = 512ll << 20;   // slabs beyond this are synchronized with streaming hints
 constexpr int64_t kAlign = 256;
@@ -88,7 +89,7 @@ struct Plan {
   int mean_words;   // ... and of the mean-state pass's table
   bool shared_table;  // both passes split the rows alike and stream one table
   int64_t cells, S, dpad;
-  int64_t off_np, off_sk, off_xi, off_scale, off_smax, off_ssum, off_nmax, off_dnorm, off_est, off_ticket, off_table,
+  int64_t off_np, off_sk, off_xi, off_syncnorm, off_scale, off_smax, off_ssum, off_nmax, off_dnorm, off_est, off_ticket, off_table,
       off_mean_table, ws_bytes;
 };
 
@@ -291,7 +292,10 @@ int make_plan(const fda_desc* d, int cus, int64_t lds_cu, Plan* pl) {
   pl->off_np = 0;
   pl->off_sk = round_up(pl->off_np + np_bytes, kAlign);
   pl->off_xi = round_up(pl->off_sk + sk_bytes, kAlign);
-  pl->off_scale = round_up(pl->off_xi + kXiBlocks * 8, kAlign);
+  // one partial norm per workgroup of the synchronization kernel, and their sum
+  const int64_t sync_blocks = ((d->d + fda::kSyncV - 1) / fda::kSyncV + kSyncVectorsPerBlock - 1) / kSyncVectorsPerBlock;
+  pl->off_syncnorm = round_up(pl->off_xi + kXiBlocks * 8, kAlign);
+  pl->off_scale = round_up(pl->off_syncnorm + (sync_blocks + kSyncNormSlices) * 8, kAlign);
   pl->off_smax = round_up(pl->off_scale + 2 * (int64_t)sizeof(fda::ScaleInfo), kAlign);
   pl->off_ssum = round_up(pl->off_smax + kScaleBlocks * 4, kAlign);
   pl->off_nmax = round_up(pl->off_ssum + kScaleBlocks * 8, kAlign);
@@ -943,8 +947,25 @@ int fda_estimate_variance_static(const float* state, int32_t K, int32_t l, int32
   return FDA_OK;
 }
 
+namespace {
+int sync_impl(fda_ctx* ctx, void* w, float* w_t0, float* w_prev, float* xi, const int32_t* pred_dev,
+              void* stream);
+}
 int fda_sync(fda_ctx* ctx, void* w, float* w_t0, float* w_prev, const int32_t* pred_dev,
              void* stream) {
+  return sync_impl(ctx, w, w_t0, w_prev, nullptr, pred_dev, stream);
+}
+int fda_sync_xi(fda_ctx* ctx, void* w, float* w_t0, float* w_prev, float* xi, const int32_t* pred_dev,
+                void* stream) {
+  if (w_prev == nullptr || xi == nullptr) return fail(FDA_EINVAL, "NULL argument");
+  if (reinterpret_cast<uintptr_t>(xi) % 4 != 0) return fail(FDA_EINVAL, "pointer not aligned to its element type");
+  return sync_impl(ctx, w, w_t0, w_prev, xi, pred_dev, stream);
+}
+namespace {
+// xi != NULL: the synchronization kernel also leaves the squared norm of the model change, and xi is
+// written by the scaling pass of fda_update_xi alone
+int sync_impl(fda_ctx* ctx, void* w, float* w_t0, float* w_prev, float* xi, const int32_t* pred_dev,
+              void* stream) {
   if (ctx == nullptr || w == nullptr || w_t0 == nullptr) return fail(FDA_EINVAL, "NULL argument");
   int rcd = check_device(ctx);
   if (rcd != FDA_OK) return rcd;
@@ -960,15 +981,32 @@ int fda_sync(fda_ctx* ctx, void* w, float* w_t0, float* w_prev, const int32_t* p
   const long long blocks = (nvec + kSyncVectorsPerBlock - 1) / kSyncVectorsPerBlock;
   const bool hinted = (long long)d.K * d.d * (d.dtype == FDA_F32 ? 4 : 2) > kStreamBytes;
   const dim3 grid((unsigned)blocks), block(fda::kSmallThreads);
+  double* norm_part = xi != nullptr ? reinterpret_cast<double*>(ctx->ws + ctx->plan.off_syncnorm) : nullptr;
 #define FDA_SYNC_LAUNCH(T, S)                                                                          \
   hipLaunchKernelGGL((fda::sync_kernel<T, S>), grid, block, 0, st, static_cast<T*>(w), w_t0, w_prev,   \
-                     pred_dev, d.K, (long long)d.d, (long long)d.row_stride, vec_ok)
+                     pred_dev, d.K, (long long)d.d, (long long)d.row_stride, vec_ok, norm_part)
   if (d.dtype == FDA_F32) { if (hinted) FDA_SYNC_LAUNCH(float, true); else FDA_SYNC_LAUNCH(float, false); }
   else { if (hinted) FDA_SYNC_LAUNCH(fda::bf16_t, true); else FDA_SYNC_LAUNCH(fda::bf16_t, false); }
 #undef FDA_SYNC_LAUNCH
   FDA_HIP(hipGetLastError());
+  if (xi != nullptr) {
+    // the partial norms -> a few (fixed order), then the scaling pass: xi = (w_t0 - w_prev) / norm
+    double* total = norm_part + blocks;
+    hipLaunchKernelGGL(fda::sum_partials_kernel, dim3(kSyncNormSlices), dim3(fda::kSmallThreads), 0, st,
+                       norm_part, blocks, pred_dev, total);
+    FDA_HIP(hipGetLastError());
+    const long long items = vec_ok ? (d.d + 3) / 4 : d.d;
+    long long sblocks = (items + fda::kSmallThreads - 1) / fda::kSmallThreads;
+    const long long cap = (long long)ctx->cus * 16;
+    if (sblocks > cap) sblocks = cap;
+    if (sblocks < 1) sblocks = 1;
+    hipLaunchKernelGGL(fda::xi_scale_kernel, dim3((unsigned)sblocks), dim3(fda::kSmallThreads), 0, st,
+                       w_t0, w_prev, xi, pred_dev, (long long)d.d, vec_ok, total, kSyncNormSlices);
+    FDA_HIP(hipGetLastError());
+  }
   return FDA_OK;
 }
+}  // namespace
 
 int fda_sync_from_mean(fda_ctx* ctx, void* w, float* w_t0, float* w_prev, float* xi,
                        const float* w_bar, const int32_t* pred_dev, void* stream) {
@@ -1059,8 +1097,8 @@ int fda_step(fda_ctx* ctx, void* w, float* w_t0, float* w_prev, float* xi, float
   if (w_bar != nullptr) {
     rc = fda_sync_from_mean(ctx, w, w_t0, w_prev, xi, w_bar, pred, stream);
   } else {
-    rc = fda_sync(ctx, w, w_t0, w_prev, pred, stream);
-    if (rc == FDA_OK && xi != nullptr) rc = fda_update_xi(ctx, w_t0, w_prev, xi, pred, stream);
+    rc = xi != nullptr ? fda_sync_xi(ctx, w, w_t0, w_prev, xi, pred, stream)
+                       : fda_sync(ctx, w, w_t0, w_prev, pred, stream);
   }
   if (rc != FDA_OK) return rc;
   if (out_host != nullptr) {

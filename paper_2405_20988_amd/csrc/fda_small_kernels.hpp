@@ -7,7 +7,8 @@
 //   merge_kernel     fixed-order fp64 sum of the per-workgroup partials -> state[K][S]
 //   merge_mean_kernel  the same for the partials of mean_state_kernel -> mean_state[S]
 //   estimate_kernel  Algorithm 1 lines 7-8: mean state, M2, H (Thm 1, Thm 2), decision
-//   sync_kernel      Algorithm 1 line 9: fused mean over workers + broadcast to all rows
+//   sync_kernel      Algorithm 1 line 9: fused mean over workers + broadcast to all rows (+ the squared
+//                    norm of the model change, for the refresh of xi)
 //   sync_from_mean_kernel  the same from an average model that is already there, with xi
 //   xi_norm_kernel / xi_scale_kernel   Section 3.2: the normalized model difference
 #pragma once
@@ -504,9 +505,14 @@ __device__ __forceinline__ SyncRange sync_range(long long nvec) {
 template <typename T, bool STREAM>
 __global__ void __launch_bounds__(kSmallThreads)
 sync_kernel(T* __restrict__ w, float* __restrict__ w_t0, float* __restrict__ w_prev,
-            const int32_t* __restrict__ pred, int K, long long d, long long row_stride, int vec_ok) {
+            const int32_t* __restrict__ pred, int K, long long d, long long row_stride, int vec_ok,
+            double* __restrict__ norm_part) {
+  // norm_part != NULL: entry [workgroup] receives the workgroup's share of ||new w_t0 - old w_t0||^2
+  // (fp32 squares of four coordinates, then fp64), which saves the refresh of xi its pass over both vectors
   constexpr int V = kSyncV;
+  __shared__ double scratch[kSmallThreads / 64];
   if (pred != nullptr && *pred == 0) return;
+  double nacc = 0.0;
   const float kf = (float)K;
   const SyncRange rg = sync_range((d + V - 1) / V);
   for (long long vi = rg.beg + threadIdx.x; vi < rg.end; vi += rg.step) {
@@ -524,10 +530,14 @@ sync_kernel(T* __restrict__ w, float* __restrict__ w_t0, float* __restrict__ w_p
       }
 #pragma unroll
       for (int v = 0; v < V; ++v) acc[v] = acc[v] / kf;
-      if (w_prev != nullptr) {
+      if (w_prev != nullptr || norm_part != nullptr) {
         float old[V];
         load_f32_vec<V, STREAM>(w_t0 + j0, old);
-        store_f32x4<STREAM>(w_prev + j0, old);
+        if (w_prev != nullptr) store_f32x4<STREAM>(w_prev + j0, old);
+        if (norm_part != nullptr) {
+          const float dx = acc[0] - old[0], dy = acc[1] - old[1], dz = acc[2] - old[2], dw = acc[3] - old[3];
+          nacc += (double)fmaf(dx, dx, fmaf(dy, dy, fmaf(dz, dz, dw * dw)));
+        }
       }
       store_f32x4<STREAM>(w_t0 + j0, acc);
       const RowVec4 row = pack_row4(acc, static_cast<const T*>(nullptr));
@@ -540,12 +550,32 @@ sync_kernel(T* __restrict__ w, float* __restrict__ w_t0, float* __restrict__ w_p
         float a = 0.0f;
         for (int k = 0; k < K; ++k) a += Slab<T>::load_one(w + (long long)k * row_stride + j);
         a = a / kf;
-        if (w_prev != nullptr) w_prev[j] = w_t0[j];
+        const float o = w_t0[j];
+        if (w_prev != nullptr) w_prev[j] = o;
+        if (norm_part != nullptr) nacc += (double)((a - o) * (a - o));
         w_t0[j] = a;
         for (int k = 0; k < K; ++k) Slab<T>::store_one(w + (long long)k * row_stride + j, a);
       }
     }
   }
+  if (norm_part != nullptr) {
+    const double s = block_sum(nacc, scratch);
+    if (threadIdx.x == 0) norm_part[blockIdx.x] = s;
+  }
+}
+// n partial sums -> gridDim.x sums of contiguous slices, out[workgroup], each in a fixed order
+__global__ void __launch_bounds__(kSmallThreads)
+sum_partials_kernel(const double* __restrict__ part, long long n, const int32_t* __restrict__ pred,
+                    double* __restrict__ out) {
+  __shared__ double scratch[kSmallThreads / 64];
+  if (pred != nullptr && *pred == 0) return;
+  const long long per = (n + gridDim.x - 1) / gridDim.x;
+  const long long beg = (long long)blockIdx.x * per;
+  const long long end = beg + per < n ? beg + per : n;
+  double acc = 0.0;
+  for (long long t = beg + threadIdx.x; t < end; t += kSmallThreads) acc += part[t];
+  const double s = block_sum(acc, scratch);
+  if (threadIdx.x == 0) out[blockIdx.x] = s;
 }
 
 // Algorithm 1 line 9 when the average model is already there (w_bar from mean_state_kernel):

@@ -82,6 +82,11 @@ class FdaMonitor:
         B.fda_sync(self.ctx, w.data_ptr(), w_t0.data_ptr(),
                    None if w_prev is None else w_prev.data_ptr(), self.pred_ptr(pred), self._stream())
 
+    def sync_xi(self, w, w_t0, w_prev, xi, pred=None):
+        """sync followed by update_xi, with the norm taken inside the synchronization pass."""
+        B.fda_sync_xi(self.ctx, w.data_ptr(), w_t0.data_ptr(), w_prev.data_ptr(), xi.data_ptr(),
+                      self.pred_ptr(pred), self._stream())
+
     def update_xi(self, w_t0, w_prev, xi, pred=None):
         B.fda_update_xi(self.ctx, w_t0.data_ptr(), w_prev.data_ptr(), xi.data_ptr(),
                         self.pred_ptr(pred), self._stream())

@@ -23,7 +23,7 @@ def declared_functions():
 def test_library_exports_every_declared_symbol():
     lib = F.load_library()
     names = declared_functions()
-    assert {"fda_local_state", "fda_estimate_variance", "fda_sync", "fda_update_xi"} <= set(names)
+    assert {"fda_local_state", "fda_estimate_variance", "fda_sync", "fda_sync_xi", "fda_update_xi"} <= set(names)
     for n in names:
         assert hasattr(lib, n), n
     # the binding offers the same names

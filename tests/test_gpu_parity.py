@@ -336,6 +336,45 @@ def test_sync_and_xi_parity(name, d, over):
     mon.close()
 
 
+@pytest.mark.parametrize("name,d,over", [("cfg4", 250_003, {}), ("cfg5", 400_005, {}), ("cfg3", 1_300_001, {}),
+                                         ("cfg1", None, {}), ("cfg2", 9, {"K": 2})])
+def test_sync_xi_equals_sync_then_update_xi(name, d, over):
+    """The synchronization that also takes the norm (Algorithm 1 line 9 with Section 3.2): rows, w_t0 and
+    w_prev to the bit, xi to the rounding of a norm added up in another order; nothing moves under a
+    zero predicate; a second synchronization right after the first gives the zero vector."""
+    say(f"[case] sync_xi vs sync + update_xi {name} d={d} {over}")
+    wl = S.make(name, device=DEV, seed=15, d=d, **over)
+    mon = monitor_for(wl)
+    a = [wl.w.clone(), wl.w_t0.clone(), torch.full_like(wl.w_t0, 7.0), torch.full_like(wl.w_t0, 5.0)]
+    b = [t.clone() for t in a]
+    mon.local_state(wl.w, wl.w_t0, wl.xi)
+    mon.estimate_variance(1e30)
+    mon.sync_xi(*b, pred="sketch")
+    torch.cuda.synchronize()
+    for x, y in zip(a, b):
+        assert torch.equal(x.view(torch.uint8), y.view(torch.uint8))
+    mon.estimate_variance(0.0)
+    mon.sync(a[0], a[1], a[2], pred="sketch")
+    mon.update_xi(a[1], a[2], a[3], pred="sketch")
+    mon.sync_xi(*b, pred="sketch")
+    torch.cuda.synchronize()
+    for x, y in zip(a[:3], b[:3]):
+        assert torch.equal(x.view(torch.uint8), y.view(torch.uint8))
+    xa, xb = a[3].cpu().numpy().astype(np.float64), b[3].cpu().numpy().astype(np.float64)
+    assert np.abs(xa - xb).max() <= 4e-7 * np.abs(xa).max()
+    want_xi = O.update_xi(b[1].cpu().numpy(), b[2].cpu().numpy())
+    assert np.abs(xb - want_xi).max() <= RTOL * np.abs(want_xi).max()
+    assert float(xb @ xb) == pytest.approx(1.0, rel=1e-5)
+    K = wl.w.shape[0]
+    if wl.dtype == "f32" and K & (K - 1) == 0:
+        # the rows are the model already: their mean (exact for such K) is the model again, and xi of no
+        # change is the zero vector
+        mon.sync_xi(*b, pred=None)
+        torch.cuda.synchronize()
+        assert torch.equal(b[1], b[2]) and not b[3].any()
+    mon.close()
+
+
 def test_xi_zero_difference_gives_zero_vector():
     say("[case] xi of a zero difference")
     import paper_2405_20988_amd as F

@@ -54,8 +54,7 @@ def separate_calls(mon, b, theta, decide_by, mode):
     if mode == "mean_wbar":
         mon.sync_from_mean(b.w, b.w_t0, b.w_bar, w_prev=b.w_prev, xi=b.xi, pred=decide_by)
     else:
-        mon.sync(b.w, b.w_t0, b.w_prev, pred=decide_by)
-        mon.update_xi(b.w_t0, b.w_prev, b.xi, pred=decide_by)
+        mon.sync_xi(b.w, b.w_t0, b.w_prev, b.xi, pred=decide_by)
 
 
 def one_step(mon, b, theta, decide_by, mode):
