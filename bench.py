@@ -142,7 +142,7 @@ def run_calibration(args):
                 iters = 200 if op == "f32" else 2000
                 r, ghz = F.fda_calib_lds_atomics(opi, pi, iters, sink.data_ptr(), st)
                 rates[f"{op}/{pat}"] = round(r, 2)
-        out["lds_atomic_adds_per_lane_per_clk_per_cu"] = rates
+        out["lds_atomic_adds_per_lane_per_clk_per_cu"] = rates      # read8 / read16: plain reads
         out["clock_ghz"] = ghz
         out["compute_units"] = torch.cuda.get_device_properties(0).multi_processor_count
     if args.stream_calibration:

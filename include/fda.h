@@ -354,7 +354,8 @@ int fda_profile_read(fda_ctx* ctx, double* state_kernel_ms, int64_t* launches, i
  * fda_calib_lds_atomics: one workgroup of 512 threads per compute unit adds into 144 KiB of LDS cells,
  * `iters` times eight atomic additions per lane to cell addresses fixed at the start.
  *   op       0: 32-bit integer add returning the old value, 1: 32-bit integer add, 2: 64-bit integer
- *            add, 3: fp64 add, 4: fp32 add, 5: 64-bit integer add returning the old value
+ *            add, 3: fp64 add, 4: fp32 add, 5: 64-bit integer add returning the old value, 6 / 7: no
+ *            addition, a plain read of 8 / 16 bytes (the cell moves by a fixed step per iteration)
  *   pattern  0: every lane its own random cell, 1: lane t on cell t (no conflicts), 2/3/4/5: groups of
  *            4/8/16/32 lanes on consecutive cells of a random group
  *   sink_dev DEVICE, 4 bytes (practically never written)

@@ -281,7 +281,7 @@ def fda_last_mean_state_path(ctx: int, stream: int = 0) -> int:
 
 
 CALIB_READ, CALIB_WRITE, CALIB_COPY, CALIB_NONTEMPORAL = 0, 1, 2, 4
-LDS_OPS = {"u32_rtn": 0, "u32": 1, "u64": 2, "f64": 3, "f32": 4, "u64_rtn": 5}
+LDS_OPS = {"u32_rtn": 0, "u32": 1, "u64": 2, "f64": 3, "f32": 4, "u64_rtn": 5, "read8": 6, "read16": 7}
 LDS_PATTERNS = {"random": 0, "consecutive": 1, "groups4": 2, "groups8": 3, "groups16": 4, "groups32": 5}
 
 

@@ -79,6 +79,8 @@ calib_copy_kernel(const u32x4* __restrict__ src, u32x4* __restrict__ dst, long l
 // each of them per iteration: almost no vector-ALU work, so the rate is the LDS's own.
 //   OP       0: 32-bit integer add that returns the old value   1: 32-bit integer add, no return
 //            2: 64-bit integer add   3: fp64 add   4: fp32 add   5: 64-bit integer add that returns the old value
+//            6 / 7: no addition at all, a plain read of 8 / 16 bytes (what a gather from LDS would cost; the
+//               cell moves by a fixed step per iteration so that the reads stay in the loop)
 //   PATTERN  0: every lane an independent random cell
 //            1: lane t the cell t (no two lanes of an instruction on one bank)
 //            2/3/4/5: groups of 4/8/16/32 lanes share a random group of consecutive cells, lane q of
@@ -91,7 +93,7 @@ calib_lds_kernel(int iters, uint32_t* __restrict__ sink) {
   const int tid = threadIdx.x, lane = tid & 63;
   for (int t = tid; t < kLdsWords; t += kLdsThreads) words[t] = 0u;
   __syncthreads();
-  constexpr int kWordsPerCell = (OP == 2 || OP == 3 || OP == 5) ? 2 : 1;
+  constexpr int kWordsPerCell = OP == 7 ? 4 : (OP == 2 || OP == 3 || OP == 5 || OP == 6) ? 2 : 1;
   constexpr int kCells = kLdsWords / kWordsPerCell;
   uint32_t idx[8];
   uint32_t s = (uint32_t)tid * 2654435761u + blockIdx.x * 97u + 12345u;
@@ -120,6 +122,17 @@ calib_lds_kernel(int iters, uint32_t* __restrict__ sink) {
       if constexpr (OP == 3) atomicAdd(reinterpret_cast<double*>(raw) + idx[q], 1.0);
       if constexpr (OP == 4) atomicAdd(reinterpret_cast<float*>(raw) + idx[q], 1.0f);
       if constexpr (OP == 5) seen64 |= atomicAdd(reinterpret_cast<unsigned long long*>(raw) + idx[q], 3ull);
+      if constexpr (OP == 6 || OP == 7) {
+        idx[q] += 1021u;                                   // below kCells: one conditional subtraction wraps
+        idx[q] = idx[q] >= (uint32_t)kCells ? idx[q] - (uint32_t)kCells : idx[q];
+        if constexpr (OP == 6) {
+          seen64 += reinterpret_cast<const unsigned long long*>(raw)[idx[q]];
+        } else {
+          const u32x4 v = reinterpret_cast<const u32x4*>(raw)[idx[q]];
+          seen += v.x ^ v.y;
+          seen64 += v.z ^ v.w;
+        }
+      }
     }
   }
   __syncthreads();
@@ -153,6 +166,8 @@ hipError_t launch_lds_any(int op, int pattern, int blocks, int iters, uint32_t* 
     case 3: return launch_lds<3>(pattern, blocks, iters, sink, st, setup);
     case 4: return launch_lds<4>(pattern, blocks, iters, sink, st, setup);
     case 5: return launch_lds<5>(pattern, blocks, iters, sink, st, setup);
+    case 6: return launch_lds<6>(pattern, blocks, iters, sink, st, setup);
+    case 7: return launch_lds<7>(pattern, blocks, iters, sink, st, setup);
   }
   return hipErrorInvalidValue;
 }
@@ -206,7 +221,7 @@ int fda_calib_stream(int mode, const void* src, void* dst, size_t bytes, int rep
 
 int fda_calib_lds_atomics(int op, int pattern, int iters, void* sink_dev, void* stream,
                           double* lane_ops_per_clock_per_cu, double* clock_ghz) {
-  if (lane_ops_per_clock_per_cu == nullptr || sink_dev == nullptr || iters < 1 || op < 0 || op > 5 ||
+  if (lane_ops_per_clock_per_cu == nullptr || sink_dev == nullptr || iters < 1 || op < 0 || op > 7 ||
       pattern < 0 || pattern > 5)
     return FDA_EINVAL;
   hipStream_t st = static_cast<hipStream_t>(stream);
