@@ -174,6 +174,9 @@ def main():
     ap.add_argument("--l", type=int, default=None, help="override the sketch rows (sketch-size sweeps)")
     ap.add_argument("--m", type=int, default=None, help="override the sketch width (sketch-size sweeps)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--plain-table", action="store_true",
+                    help="FDA_DESC_PLAIN_TABLE: every sketch row in its own slot of the tabulated hash "
+                         "(the state pass without the placement against LDS collisions, for comparison)")
     ap.add_argument("--wbar", action="store_true",
                     help="mean-state mode: also emit the average model from the state pass and "
                          "synchronize with fda_sync_from_mean instead of fda_sync + fda_update_xi "
@@ -236,7 +239,8 @@ def main():
     wl = S.make(args.config, device=dev, seed=0, d=args.d, **over)
     K, d = wl.K, wl.d
     esz = 4 if wl.dtype == "f32" else 2
-    mon = F.FdaMonitor(K, d, wl.dtype, args.variants, wl.l, wl.m, wl.eps, wl.hash_coef, device=dev)
+    mon = F.FdaMonitor(K, d, wl.dtype, args.variants, wl.l, wl.m, wl.eps, wl.hash_coef, device=dev,
+                       flags=F.FDA_DESC_PLAIN_TABLE if args.plain_table else 0)
     w_prev = wl.w_t0.clone()
     xi = wl.xi if args.variants & 1 else None
     pred = "sketch" if args.variants & 2 else "linear"

@@ -70,6 +70,11 @@ typedef struct fda_ctx fda_ctx;   /* opaque */
  * +1 if g(j) is even and -1 otherwise.  The values are copied by fda_create.  May be NULL
  * when FDA_VARIANT_SKETCH is not requested.
  */
+/* fda_desc.flags: keep every sketch row in its own slot of the tabulated hash (no placement against
+ * LDS collisions, see fda_plan_info.placed_row_group): same results bit for bit, a slower state pass --
+ * for comparisons */
+#define FDA_DESC_PLAIN_TABLE 1
+
 typedef struct fda_desc {
   int32_t K;            /* number of workers (rows of the slab), >= 1                      */
   int32_t dtype;        /* FDA_F32 or FDA_BF16                                              */
@@ -78,7 +83,7 @@ typedef struct fda_desc {
   int32_t variants;     /* FDA_VARIANT_* bit mask, non-zero                                 */
   int32_t l;            /* sketch rows,   1..FDA_MAX_SKETCH_ROWS (ignored without SKETCH)   */
   int32_t m;            /* sketch columns, >= 1                  (ignored without SKETCH)   */
-  int32_t reserved;     /* must be 0                                                        */
+  int32_t flags;        /* FDA_DESC_* bit mask, normally 0                                  */
   double  eps;          /* the epsilon of Thm 1: H = mean||u||^2 - M2 / (1 + eps)           */
   const uint32_t* hash_coef;
 } fda_desc;
@@ -125,6 +130,9 @@ typedef struct fda_plan_info {
   int64_t mean_lds_bytes;        /* LDS per workgroup                                        */
   int32_t sign_split_rows;  /* 1: the state pass keeps terms of sign -1 in LDS rows of their own */
   int32_t worker_slots;     /* worker slots of the state kernel that runs (>= workers_per_group)  */
+  int32_t placed_row_group; /* rows per placement group of the tabulated hash (0: every row keeps its slot): the
+                               slot of a record that holds a row is chosen per coordinate against LDS collisions */
+  int32_t reserved;
 } fda_plan_info;
 
 const char* fda_strerror(int code);

@@ -14,6 +14,7 @@ import numpy as np
 FDA_OK, FDA_EINVAL, FDA_ERANGE, FDA_ENOMEM, FDA_EHIP = 0, -1, -2, -3, -4
 FDA_F32, FDA_BF16 = 0, 1
 FDA_VARIANT_LINEAR, FDA_VARIANT_SKETCH = 1, 2
+FDA_DESC_PLAIN_TABLE = 1
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
 # FDA_LIBRARY: load another build of the library instead of the in-tree one (experiments)
@@ -30,7 +31,7 @@ class FdaError(RuntimeError):
 class FdaDesc(C.Structure):
     _fields_ = [("K", C.c_int32), ("dtype", C.c_int32), ("d", C.c_int64),
                 ("row_stride", C.c_int64), ("variants", C.c_int32), ("l", C.c_int32),
-                ("m", C.c_int32), ("reserved", C.c_int32), ("eps", C.c_double),
+                ("m", C.c_int32), ("flags", C.c_int32), ("eps", C.c_double),
                 ("hash_coef", C.POINTER(C.c_uint32))]
 
 
@@ -54,7 +55,8 @@ class FdaPlanInfo(C.Structure):
                 ("mean_row_groups", C.c_int32), ("mean_rows_per_group", C.c_int32),
                 ("mean_partitions", C.c_int32), ("mean_workgroups_per_cu", C.c_int32),
                 ("mean_chunk", C.c_int64), ("mean_lds_bytes", C.c_int64),
-                ("sign_split_rows", C.c_int32), ("worker_slots", C.c_int32)]
+                ("sign_split_rows", C.c_int32), ("worker_slots", C.c_int32),
+                ("placed_row_group", C.c_int32), ("reserved", C.c_int32)]
 
     def as_dict(self) -> dict:
         return {name: getattr(self, name) for name, _ in self._fields_}
@@ -126,12 +128,12 @@ def _check(rc: int, what: str) -> None:
         raise FdaError(rc, what)
 
 
-def make_desc(K, d, dtype, variants, l=0, m=0, eps=0.0, hash_coef=None, row_stride=None):
+def make_desc(K, d, dtype, variants, l=0, m=0, eps=0.0, hash_coef=None, row_stride=None, flags=0):
     """Fill an FdaDesc; returns (desc, keepalive) -- keepalive owns the coefficient array."""
     desc = FdaDesc()
     desc.K, desc.d, desc.dtype, desc.variants = int(K), int(d), int(dtype), int(variants)
     desc.row_stride = int(d if row_stride is None else row_stride)
-    desc.l, desc.m, desc.reserved, desc.eps = int(l), int(m), 0, float(eps)
+    desc.l, desc.m, desc.flags, desc.eps = int(l), int(m), int(flags), float(eps)
     keep = None
     if hash_coef is not None:
         keep = np.ascontiguousarray(hash_coef, dtype=np.uint32)

@@ -56,6 +56,7 @@ constexpr double kSignCost = 3.0;          // ... and into a sign and a bucket, 
 constexpr double kSelectCost = 1.0;        // choosing the term or its negative for one 32-bit cell
 constexpr double kAtomicCost = 7.5;        // one 32-bit LDS addition and the OR of what it returned
 constexpr double kPairAddCost = 13.0;      // one 64-bit LDS addition (two cells) and the OR of what it returned
+constexpr double kPlacedPairAddCost = 9.5; // ... when the table's row slots are placed against LDS collisions
 constexpr double kSharedByteCost = 0.25;   // per byte of w_t0 / xi / table read by one more workgroup
 constexpr int kMaxEstBlocksPerRow = 128;   // 32768 / 256: workgroups of estimate_kernel per sketch row
 constexpr int kScaleSamples = 16384;       // sampled coordinates per worker for the scale
@@ -85,6 +86,8 @@ struct Plan {
   MeanSplit mean;   // fda_mean_state
   int vec;          // elements per 16-byte slab load
   int fb;           // bits per field of the tabulated hash
+  int narrow_fb;    // ... of the table the 32-bit-cell pass streams (kPlacedFieldBits with placed rows)
+  int grp;          // rows per placement group of that table (1: rows keep their slots)
   int words;        // 16-bit words per record of the table the 32-bit-cell pass streams
   int mean_words;   // ... and of the mean-state pass's table
   bool shared_table;  // both passes split the rows alike and stream one table
@@ -101,7 +104,7 @@ int validate(const fda_desc* d) {
     return fail(FDA_ERANGE, "d must be below 2^31 - 1 - 64: coordinates are hash keys modulo 2^31 - 1");
   if (d->row_stride < d->d) return fail(FDA_EINVAL, "row_stride must be >= d");
   if (d->dtype != FDA_F32 && d->dtype != FDA_BF16) return fail(FDA_EINVAL, "unknown dtype %d", d->dtype);
-  if (d->reserved != 0) return fail(FDA_EINVAL, "reserved must be 0");
+  if ((d->flags & ~FDA_DESC_PLAIN_TABLE) != 0) return fail(FDA_EINVAL, "unknown flags");
   if ((d->variants & ~(FDA_VARIANT_LINEAR | FDA_VARIANT_SKETCH)) != 0 || d->variants == 0)
     return fail(FDA_EINVAL, "variants must be a non-empty mask of FDA_VARIANT_LINEAR | FDA_VARIANT_SKETCH");
   if (d->variants & FDA_VARIANT_SKETCH) {
@@ -170,7 +173,11 @@ int make_split(const fda_desc* d, int cus, int64_t lds_cu, int cell_bytes, Split
           // addition the select (unless split), the overflow OR and the LDS instruction itself.
           const double wg = (double)G * R;
           const double pairs = (KC % 2 == 0 && narrow) ? KC / 2 : KC;           // LDS instructions per row slot
-          const double per_add = (KC % 2 == 0 && narrow) ? (split ? kPairAddCost : kPairAddCost + 2.0 * kSelectCost)
+          // (a table with placed rows avoids about a third of the LDS collisions)
+          const bool placed = narrow && split && cells && fda::placed_kernel_exists(KC) &&
+                              !(d->flags & FDA_DESC_PLAIN_TABLE) && fda::placed_group_rows(rc, d->m) >= 2;
+          const double per_add = (KC % 2 == 0 && narrow) ? (placed ? kPlacedPairAddCost
+                                                            : split ? kPairAddCost : kPairAddCost + 2.0 * kSelectCost)
                                                          : kAtomicCost + kSelectCost;
           const double cost = wg * KC * (split ? kElementCost : kElementCost + kNegateCost) +
                               wg * LR * (split ? kDecodeCost : kDecodeCost + kSignCost) +
@@ -306,9 +313,18 @@ int make_plan(const fda_desc* d, int cus, int64_t lds_cu, Plan* pl) {
   pl->dpad = round_up(d->d, fda::kRecBlockCoords);      // the table comes in whole blocks
   // the tabulated hash: per row group one record per coordinate with a field per row slot
   pl->fb = fda::field_bits_for(sk ? d->m : 1);
-  pl->words = (pl->narrow.LR * pl->fb + 15) / 16;
+  // placed rows (slots chosen against LDS collisions): sign-split rows in an unskewed layout, when a
+  // placement group of at least two rows fits the wider field
+  pl->grp = 1;
+  pl->narrow_fb = pl->fb;
+  if (sk && pl->narrow.split && fda::placed_kernel_exists(pl->narrow.KC) &&
+      !(d->flags & FDA_DESC_PLAIN_TABLE)) {
+    const int g = fda::placed_group_rows(pl->narrow.rcnt_max, d->m);
+    if (g >= 2) { pl->grp = g; pl->narrow_fb = fda::kPlacedFieldBits; }
+  }
+  pl->words = (pl->narrow.LR * pl->narrow_fb + 15) / 16;
   pl->mean_words = (pl->mean.rcnt_max * pl->fb + 15) / 16;
-  pl->shared_table = pl->narrow.R == pl->mean.R && pl->narrow.LR == pl->mean.rcnt_max;
+  pl->shared_table = pl->grp == 1 && pl->narrow.R == pl->mean.R && pl->narrow.LR == pl->mean.rcnt_max;
   const int64_t table_bytes = sk ? (int64_t)pl->narrow.R * pl->dpad * pl->words * 2 : 0;
   const int64_t mean_table_bytes =
       sk && !pl->shared_table ? (int64_t)pl->mean.R * pl->dpad * pl->mean_words * 2 : 0;
@@ -336,6 +352,8 @@ void export_plan(const Plan& pl, fda_plan_info* out) {
   out->mean_lds_bytes = pl.mean.lds_bytes;
   out->sign_split_rows = pl.narrow.split;
   out->worker_slots = pl.narrow.KC;
+  out->placed_row_group = pl.grp >= 2 ? pl.grp : 0;
+  out->reserved = 0;
 }
 
 int device_shape(int* cus, int64_t* lds) {
@@ -493,13 +511,13 @@ int prof_end(fda_ctx* c, hipStream_t st, int slot) {
 
 // Before the first sketch of a context: the hash table and the cell counts.  Then, per call, the
 // fixed-point units from a sample of the drifts (this also clears the flags in *scale).
-int build_table(fda_ctx* ctx, int R, int slots, int words, int64_t off, hipStream_t st) {
+int build_table(fda_ctx* ctx, int R, int slots, int fb, int words, int grp, int64_t off, hipStream_t st) {
   const fda_desc& d = ctx->desc;
   const Plan& pl = ctx->plan;
   const long long groups = pl.dpad / 4;
   hipLaunchKernelGGL(fda::hash_table_kernel,
                      dim3((unsigned)((groups + fda::kSmallThreads - 1) / fda::kSmallThreads), (unsigned)R),
-                     dim3(fda::kSmallThreads), 0, st, ctx->coef, d.l, R, slots, d.m, pl.fb, words,
+                     dim3(fda::kSmallThreads), 0, st, ctx->coef, d.l, R, slots, d.m, fb, words, grp,
                      (long long)d.d, (long long)pl.dpad, reinterpret_cast<uint16_t*>(ctx->ws + off));
   FDA_HIP(hipGetLastError());
   return FDA_OK;
@@ -532,13 +550,13 @@ int prepare_sketch(fda_ctx* ctx, const void* w, const float* w_t0, fda::ScaleInf
   }
   // ... and the hash of every (row, coordinate), tabulated for the pass that is about to run
   if (!for_mean && !ctx->table_built) {
-    int rc = build_table(ctx, pl.narrow.R, pl.narrow.LR, pl.words, pl.off_table, st);
+    int rc = build_table(ctx, pl.narrow.R, pl.narrow.LR, pl.narrow_fb, pl.words, pl.grp, pl.off_table, st);
     if (rc != FDA_OK) return rc;
     ctx->table_built = true;
     if (pl.shared_table) ctx->mean_table_built = true;
   }
   if (for_mean && !ctx->mean_table_built) {
-    int rc = build_table(ctx, pl.mean.R, pl.mean.rcnt_max, pl.mean_words, pl.off_mean_table, st);
+    int rc = build_table(ctx, pl.mean.R, pl.mean.rcnt_max, pl.fb, pl.mean_words, 1, pl.off_mean_table, st);
     if (rc != FDA_OK) return rc;
     ctx->mean_table_built = true;
     if (pl.shared_table) ctx->table_built = true;
@@ -665,7 +683,7 @@ int fda_create(fda_ctx** ctx, const fda_desc* desc, void* workspace, size_t work
   Split narrow_max = pl.narrow, wide_max = pl.wide;
   MeanSplit mean_max = pl.mean;
   narrow_max.lds_bytes = wide_max.lds_bytes = mean_max.lds_bytes = lds;
-  rc = dispatch_any(desc->dtype, fda::kCellI32, narrow_max, pl.fb, nullptr, nullptr);
+  rc = dispatch_any(desc->dtype, fda::kCellI32, narrow_max, pl.narrow_fb, nullptr, nullptr);
   if (rc == FDA_OK) rc = dispatch_mean(desc->dtype, fda::kCellI64, mean_max, pl.fb, nullptr, nullptr);
   if (rc == FDA_OK && (desc->variants & FDA_VARIANT_SKETCH))
     rc = dispatch_mean(desc->dtype, fda::kCellF64, mean_max, pl.fb, nullptr, nullptr);
@@ -781,6 +799,7 @@ int fda_local_state(fda_ctx* ctx, const void* w, const float* w_t0, const float*
     prm.scale = reinterpret_cast<fda::ScaleInfo*>(ctx->ws + pl.off_scale);
     prm.table = reinterpret_cast<const uint16_t*>(ctx->ws + pl.off_table);
     prm.dpad = pl.dpad;
+    prm.grp = &sp == &pl.narrow ? pl.grp : 1;
     prm.coef = ctx->coef;
     return prm;
   };
@@ -794,7 +813,7 @@ int fda_local_state(fda_ctx* ctx, const void* w, const float* w_t0, const float*
   int slot = -1;
   rc = prof_begin(ctx, st, &slot);
   if (rc != FDA_OK) return rc;
-  rc = dispatch_any(d.dtype, fda::kCellI32, pl.narrow, pl.fb, &prm32, st);
+  rc = dispatch_any(d.dtype, fda::kCellI32, pl.narrow, pl.narrow_fb, &prm32, st);
   if (rc != FDA_OK) return rc;
   rc = prof_end(ctx, st, slot);
   if (rc != FDA_OK) return rc;

@@ -53,7 +53,7 @@ int main(int argc, char** argv) {
   fda_desc desc;
   desc.K = K; desc.d = d; desc.row_stride = d; desc.dtype = FDA_F32;
   desc.variants = FDA_VARIANT_LINEAR | FDA_VARIANT_SKETCH;
-  desc.l = l; desc.m = m; desc.reserved = 0; desc.eps = 0.06; desc.hash_coef = coef;
+  desc.l = l; desc.m = m; desc.flags = 0; desc.eps = 0.06; desc.hash_coef = coef;
 
   float* hw = (float*)malloc(sizeof(float) * (size_t)K * (size_t)d);
   float* h0 = (float*)malloc(sizeof(float) * (size_t)d);

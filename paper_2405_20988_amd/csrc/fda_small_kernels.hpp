@@ -24,25 +24,100 @@ namespace fda {
 // region (whatever bucket and sign they decode from it, the bucket stays below kDummyCells).
 // Layout [row group][block of 256 coordinates][dwords in load order]: the 2 * words dwords of the 4
 // records that a lane of the state kernels loads together are placed where load_rec_block() reads
-// them.  One thread writes one lane's share.
+// them.  One thread writes one lane's share; a workgroup of kSmallThreads covers 4 blocks.
+//
+// grp >= 2: placed rows (see kPlacedFieldBits).  The rows of the group come in placement groups of grp;
+// slot a of a placement group of n rows holds row (a + rot) % n of it, field = that row's number in the
+// group times 2 m plus the plain field, and rot is chosen per coordinate so that the additions one
+// instruction of the state kernel issues collide as little as the choice allows.  The model: the 16
+// lanes 16 g .. 16 g + 15 of a wave are served together, instruction (v, slot) takes coordinate 4 lane + v
+// of the block from each, and two of them collide when their cells' indices agree modulo 16 (8-byte
+// words 128 bytes apart; with 3 such words per bucket the word index is 3 times the cell index, the same
+// classes).  Cost of an instruction = the largest number of lanes in one class; per (16 lanes, v,
+// placement group) one thread places the 16 coordinates one after the other where the sum over the
+// slots grows least, then revisits each twice.  The result depends only on the hash and the shape.
+constexpr int kPlaceSweeps = 3;
 __global__ void __launch_bounds__(kSmallThreads)
-hash_table_kernel(const HashCoef hc, int l, int R, int slots, int m, int fb, int words, long long d,
+hash_table_kernel(const HashCoef hc, int l, int R, int slots, int m, int fb, int words, int grp, long long d,
                   long long dpad, uint16_t* __restrict__ table) {
+  __shared__ uint16_t fld[kSmallThreads][4][8];                // plain fields, by thread, coordinate, row
+  __shared__ uint8_t rotsel[kSmallThreads][4][4];              // chosen rotation, by thread, coordinate, placement group
+  __shared__ uint8_t hist[kSmallThreads / 64][16][8][16];      // by wave, (16 lanes, v), slot, class
   const int r = blockIdx.y;
-  const long long j4 = ((long long)blockIdx.x * blockDim.x + threadIdx.x) * 4;
-  if (j4 >= dpad) return;
+  const int tid = threadIdx.x;
+  const long long j4 = ((long long)blockIdx.x * blockDim.x + tid) * 4;
   int rstart, rcnt;
   group_range(l, R, r, &rstart, &rcnt);
+  const bool placed = grp >= 2;
+  const uint32_t mrow = 2u * (uint32_t)m;
+  for (int q = 0; q < 4; ++q) {
+    const long long j = j4 + q;
+    for (int i = 0; i < slots; ++i) {
+      uint32_t f = (uint32_t)(j + 17 * i) & (uint32_t)(kDummyCells - 1);
+      if (i < rcnt && j < d) {
+        const uint32_t h = hash_entry(hc, rstart + i, (uint32_t)j, (uint32_t)m);
+        f = (h & 0x7fffu) + (h >> 15) * (uint32_t)m;           // bucket + m * (sign is -1)
+      }
+      fld[tid][q][i] = (uint16_t)f;
+    }
+  }
+  if (placed) {                                                // (uniform over the workgroup)
+    const int ngroups = (rcnt + grp - 1) / grp;                // at most 4: grp >= 2, at most 8 rows
+    for (int q = 0; q < 4; ++q)
+      for (int g = 0; g < 4; ++g) rotsel[tid][q][g] = 0;
+    __syncthreads();
+    const int wave = tid >> 6, lane = tid & 63;
+    // problem (16 lanes gi, coordinate v) = lane & 15; placement groups lane >> 4, lane >> 4 + 4, ...
+    const int prob = lane & 15, gi = prob >> 2, v = prob & 3;
+    for (int g = lane >> 4; g < ngroups; g += 4) {
+      const int g0 = g * grp, n = rcnt - g0 < grp ? rcnt - g0 : grp;
+      if (n < 2) continue;
+      uint8_t (*h)[16] = &hist[wave][prob][g0];                // n slots of 16 classes
+      for (int a = 0; a < n; ++a)
+        for (int c = 0; c < 16; ++c) h[a][c] = 0;
+      const int member0 = wave * 64 + gi * 16;
+      // class of member t's entry of row `row` (within the placement group)
+      auto cls = [&](int t, int row) { return (int)(((uint32_t)row * mrow + fld[member0 + t][v][g0 + row]) & 15u); };
+      for (int sweep = 0; sweep < kPlaceSweeps; ++sweep) {
+        for (int t = 0; t < 16; ++t) {
+          if (sweep > 0) {
+            const int cur = rotsel[member0 + t][v][g];
+            for (int a = 0; a < n; ++a) { int row = a + cur; if (row >= n) row -= n; h[a][cls(t, row)] -= 1; }
+          }
+          int mx[8];
+          for (int a = 0; a < n; ++a) {
+            int top = 0;
+            for (int c = 0; c < 16; ++c) top = h[a][c] > top ? h[a][c] : top;
+            mx[a] = top;
+          }
+          int best = 1 << 30, brot = 0;
+          for (int rot = 0; rot < n; ++rot) {
+            int cost = 0;
+            for (int a = 0; a < n; ++a) {
+              int row = a + rot; if (row >= n) row -= n;
+              const int after = h[a][cls(t, row)] + 1;
+              cost += after > mx[a] ? after : mx[a];
+            }
+            if (cost < best) { best = cost; brot = rot; }
+          }
+          rotsel[member0 + t][v][g] = (uint8_t)brot;
+          for (int a = 0; a < n; ++a) { int row = a + brot; if (row >= n) row -= n; h[a][cls(t, row)] += 1; }
+        }
+      }
+    }
+    __syncthreads();
+  }
+  if (j4 >= dpad) return;
   uint32_t dw[16];                                             // 4 records of at most 8 words
   for (int t = 0; t < 16; ++t) dw[t] = 0u;
   for (int q = 0; q < 4; ++q) {
-    const long long j = j4 + q;
     unsigned long long bits[3] = {0ull, 0ull, 0ull};          // slots * fb <= 8 * 16 bits
     for (int i = 0; i < slots; ++i) {
-      unsigned long long f = (unsigned long long)((uint32_t)(j + 17 * i) & (uint32_t)(kDummyCells - 1));
-      if (i < rcnt && j < d) {
-        const uint32_t h = hash_entry(hc, rstart + i, (uint32_t)j, (uint32_t)m);
-        f = (unsigned long long)((h & 0x7fffu) + (h >> 15) * (uint32_t)m);      // bucket + m * (sign is -1)
+      unsigned long long f = fld[tid][q][i];
+      if (placed && i < rcnt) {
+        const int g = i / grp, g0 = g * grp, n = rcnt - g0 < grp ? rcnt - g0 : grp;
+        int row = i - g0 + rotsel[tid][q][g]; if (row >= n) row -= n;
+        f = (unsigned long long)((uint32_t)row * mrow + fld[tid][q][g0 + row]);
       }
       const int pos = i * fb, idx = pos >> 6, sh = pos & 63;
       bits[idx] |= f << sh;

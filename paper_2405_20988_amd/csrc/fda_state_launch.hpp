@@ -17,11 +17,14 @@ constexpr int kKCSet[] = {1, 2, 4, 6, 8};
 constexpr int kMaxLR = 8;
 constexpr int kMaxSlots = 32;
 constexpr bool narrow_kernel_exists(int KC, bool split) { return split ? KC % 2 == 0 : KC <= 2; }
+// ... and kernels for a table with placed rows (fields of kPlacedFieldBits bits) for the even KC whose
+// layout has no skew: there a field times the bucket stride is the cell's offset in the whole group
+constexpr bool placed_kernel_exists(int KC) { return KC % 2 == 0 && !cells32_skewed(KC); }
 // fallback passes (8-byte cells)
 constexpr int kWideKCSet[] = {1, 2, 4};
 constexpr int kWideLRSet[] = {1, 2, 4, 8};
 
-// FB: bits per field of the tabulated hash (field_bits_for(m)): 11 or 16; split: sign-split LDS rows
+// FB: bits per field of the tabulated hash (field_bits_for(m): 11 or 16; kPlacedFieldBits with placed rows); split: sign-split LDS rows
 // (even worker-slot counts only)
 #define FDA_NARROW_LAUNCHER(t, kc) \
   hipError_t launch_narrow_##t##_kc##kc(int LR, int FB, int split, const StateParams* prm, size_t lds, hipStream_t st)

@@ -14,7 +14,7 @@ _EST_OFFSETS = {"linear": B.FdaEstimate.sync_linear.offset, "sketch": B.FdaEstim
 
 class FdaMonitor:
     def __init__(self, K, d, dtype, variants, l=0, m=0, eps=0.0, hash_coef=None,
-                 row_stride=None, device="cuda:0"):
+                 row_stride=None, device="cuda:0", flags=0):
         if not torch.cuda.is_available():
             raise RuntimeError("FdaMonitor needs a HIP device (no CPU fallback exists)")
         self.device = torch.device(device)
@@ -22,7 +22,7 @@ class FdaMonitor:
         self.K, self.d = int(K), int(d)
         self.dtype = {"f32": B.FDA_F32, "bf16": B.FDA_BF16}.get(dtype, dtype)
         self.variants = int(variants)
-        self.desc, self._keep = B.make_desc(K, d, self.dtype, variants, l, m, eps, hash_coef, row_stride)
+        self.desc, self._keep = B.make_desc(K, d, self.dtype, variants, l, m, eps, hash_coef, row_stride, flags)
         nbytes = B.fda_workspace_bytes(self.desc)
         self.workspace = torch.empty(nbytes, dtype=torch.uint8, device=self.device)
         self.ctx = B.fda_create(self.desc, self.workspace.data_ptr(), nbytes)

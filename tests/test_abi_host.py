@@ -35,7 +35,7 @@ def test_struct_layouts_match_header():
     assert C.sizeof(F.FdaEstimate) == 64
     assert F.FdaEstimate.sync_linear.offset == 40 and F.FdaEstimate.sync_sketch.offset == 44
     assert C.sizeof(F.FdaDesc) == 56
-    assert C.sizeof(F.FdaPlanInfo) == 96
+    assert C.sizeof(F.FdaPlanInfo) == 104
 
 
 def test_strerror():
@@ -118,8 +118,8 @@ def test_plan_chooses_the_rows_the_lds_allows():
     worker groups would cost more than the selects they save, the rows stay plain."""
     coef = S.hash_coefficients(0, 16)
 
-    def plan(K, l, m, d=10**6, dt=F.FDA_F32):
-        desc, keep = make_desc(K, d, dt, 3, l, m, 0.06, coef[:l])
+    def plan(K, l, m, d=10**6, dt=F.FDA_F32, flags=0):
+        desc, keep = make_desc(K, d, dt, 3, l, m, 0.06, coef[:l], flags=flags)
         return F.fda_plan(desc, 256, 163840)
     p = plan(2, 3, 6_000)                  # 3 x 6000 x 2 slots: 144 KB plain, split would need 288
     assert (p.worker_groups, p.worker_slots, p.row_groups, p.sign_split_rows) == (1, 2, 1, 0)
@@ -127,12 +127,18 @@ def test_plan_chooses_the_rows_the_lds_allows():
     assert (p.worker_groups, p.worker_slots, p.sign_split_rows) == (2, 2, 1)
     p = plan(1, 5, 250)                    # a single worker: one slot, 32-bit additions, plain rows
     assert (p.worker_slots, p.sign_split_rows) == (1, 0)
-    p = plan(3, 5, 250)                    # three workers take a kernel of four slots (one spare)
-    assert (p.worker_groups, p.worker_slots, p.sign_split_rows) == (1, 4, 1)
+    p = plan(3, 5, 250)                    # three workers: two groups of two slots (one spare), whose layout
+    assert (p.worker_groups, p.worker_slots, p.sign_split_rows) == (2, 2, 1)     # allows placed rows
+    assert p.placed_row_group == 5
+    p = plan(3, 5, 250, flags=F.FDA_DESC_PLAIN_TABLE)    # ... without them a kernel of four slots (one spare)
+    assert (p.worker_groups, p.worker_slots, p.sign_split_rows, p.placed_row_group) == (1, 4, 1, 0)
     p = plan(3, 1, 19_000)                 # one slot per workgroup: the row fills the LDS
     assert (p.worker_groups, p.worker_slots, p.sign_split_rows) == (3, 1, 0)
     p = plan(8, 7, 1000, 350_000_000, F.FDA_BF16)       # cfg5: four groups of two, one round of 256 workgroups
     assert (p.worker_groups, p.worker_slots, p.partitions, p.sign_split_rows) == (4, 2, 64, 1)
+    assert p.placed_row_group == 4         # fields of 13 bits: four rows of 2000 buckets per placement group
+    p = plan(8, 7, 2049, 10**6, F.FDA_BF16)
+    assert p.placed_row_group == 0         # two rows of 4098 buckets are beyond 13 bits
     p = plan(30, 5, 250, 7_000_000)                       # cfg3: one round of 255 workgroups, not three of 760
     assert (p.worker_groups, p.worker_slots, p.partitions) == (5, 6, 51)
     assert p.lds_bytes <= 163840

@@ -34,10 +34,10 @@ def say(msg):
     sys.stdout.flush()
 
 
-def monitor_for(wl, variants=3, row_stride=None):
+def monitor_for(wl, variants=3, row_stride=None, flags=0):
     import paper_2405_20988_amd as F
     return F.FdaMonitor(wl.K, wl.d, wl.dtype, variants, wl.l, wl.m, wl.eps, wl.hash_coef,
-                        row_stride=row_stride, device=DEV)
+                        row_stride=row_stride, device=DEV, flags=flags)
 
 
 def oracle_state(wl, variants=3):
@@ -98,19 +98,20 @@ STATE_CASES = [
     ("cfg2", 30_011, {"K": 4, "l": 2, "m": 4_500}),     # two groups of two rather than four slots: split rows fit
     ("cfg2", 30_011, {"K": 5, "l": 6, "m": 64}),        # 6 slots x 6 rows are not built: groups of 2, 2, 1 workers
     ("cfg2", 30_011, {"K": 5, "l": 5, "m": 64}),        # five workers in six slots: a spare high half
-    ("cfg5", 40_009, {"K": 8, "l": 4, "m": 300}),       # bf16, eight slots
+    ("cfg5", 40_009, {"K": 8, "l": 4, "m": 300}),       # bf16, eight slots (with the plain table; else 4 x 2)
     ("cfg2", 20_011, {"K": 2, "l": 1, "m": 20_000}),    # about the widest sketch the LDS takes: 16-bit table fields up to 2 m - 1
 ]
 EXPECTED_ROWS = {(2, 3, 6_000): (2, 0), (4, 2, 4_500): (2, 1), (5, 6, 64): (2, 1), (5, 5, 64): (6, 1), (8, 4, 300): (8, 1)}
+PLAIN_TABLE_CASES = {(8, 4, 300)}       # planned without placed rows (FDA_DESC_PLAIN_TABLE), for the kernel they then get
 
 
 @pytest.mark.parametrize("name,d,over", STATE_CASES)
 def test_state_and_estimate_parity(name, d, over):
     say(f"[case] state parity {name} d={d} {over}")
     wl = S.make(name, device=DEV, seed=1, d=d, **over)
-    mon = monitor_for(wl)
-    say(f"       plan {mon.plan}")
     key = (wl.K, wl.l, wl.m)
+    mon = monitor_for(wl, flags=1 if key in PLAIN_TABLE_CASES else 0)
+    say(f"       plan {mon.plan}")
     if key in EXPECTED_ROWS and "K" in over:
         assert (mon.plan["worker_slots"], mon.plan["sign_split_rows"]) == EXPECTED_ROWS[key], mon.plan
     mon.local_state(wl.w, wl.w_t0, wl.xi)
@@ -552,6 +553,30 @@ def _apply_noise(w, latent, noise, dtype):
         latent = latent + noise
         return O.round_to_bf16_bits(latent.astype(np.float64)), latent
     return w + noise, None
+
+
+@pytest.mark.parametrize("name,d,over", [("cfg5", 700_003, {}), ("cfg4", 150_001, {}), ("cfg3", 300_007, {}),
+                                         ("cfg5", 5_001, {"K": 2, "l": 9, "m": 250}), ("cfg1", None, {"l": 3, "m": 1024}),
+                                         ("cfg2", 100_001, {"K": 2, "l": 8, "m": 500}),
+                                         ("cfg5", 9_001, {"K": 2, "l": 11, "m": 700}),
+                                         ("cfg5", 9_001, {"K": 6, "l": 7, "m": 2048})])
+def test_placed_rows_give_the_same_state(name, d, over):
+    """A table whose row slots are chosen per coordinate (against LDS collisions) and the plain table:
+    the same cells receive the same integer terms, so the states agree bit for bit -- and with the oracle."""
+    say(f"[case] placed rows vs plain table {name} d={d} {over}")
+    import paper_2405_20988_amd as F
+    wl = S.make(name, device=DEV, seed=21, d=d, **over)
+    placed = monitor_for(wl)
+    plain = F.FdaMonitor(wl.K, wl.d, wl.dtype, 3, wl.l, wl.m, wl.eps, wl.hash_coef, device=DEV,
+                         flags=F.FDA_DESC_PLAIN_TABLE)
+    assert placed.plan["placed_row_group"] >= 2 and plain.plan["placed_row_group"] == 0
+    for mon in (placed, plain):
+        mon.local_state(wl.w, wl.w_t0, wl.xi)
+    torch.cuda.synchronize()
+    assert torch.equal(placed.state.view(torch.int32), plain.state.view(torch.int32))
+    check_state(placed, oracle_state(wl))
+    placed.close()
+    plain.close()
 
 
 def test_state_is_bit_reproducible():
