@@ -308,8 +308,10 @@ def main():
         roofline["lds_cell_updates_per_clk_per_cu"] = round(
             updates / (kern_ms_avg * 1e-3) / props.multi_processor_count / (ghz * 1e9), 2)
         roofline["lds_cell_update_ceiling_per_clk_per_cu"] = round(rate * (2 if paired else 1), 2)
-        roofline["lds_ceiling_source"] = (f"fda_calib_lds_atomics({op}, random) x {2 if paired else 1} cells per "
-                                          "addition, measured in this run")
+        roofline["lds_ceiling_source"] = (f"fda_calib_lds_atomics({op}, random cells) x {2 if paired else 1} cells per "
+                                          "addition, measured in this run" +
+                                          ("; the table's placed rows collide less than random cells do"
+                                           if mon.plan.get("placed_row_group") else ""))
         roofline["clock_ghz"] = ghz
 
     # The same step with the average state computed directly (fda_mean_state: sketch of the mean
