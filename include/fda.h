@@ -182,7 +182,9 @@ int fda_get_plan(const fda_ctx* ctx, fda_plan_info* out);
  * more makes ||u_k||^2 overflow to infinity (reported as a non-finite estimate) where the plain
  * fp32 square would overflow only at 2^64.
  * The first call of a context also tabulates the hash into the workspace (one record per coordinate:
- * 11 bits per sketch row, 16 for m > 1024, rounded up to whole 16-bit words; 10 bytes for l = 7).
+ * 11 bits per sketch row, 16 for m > 1024, 13 where the rows are placed -- fda_plan_info.placed_row_group --
+ * rounded up to whole 16-bit words; 12 bytes for l = 7, m = 1000).  fda_mean_state tabulates a plain
+ * table of its own on its first call when this pass uses placed rows.
  */
 int fda_local_state(fda_ctx* ctx, const void* w, const float* w_t0, const float* xi,
                     float* state, void* stream);
