@@ -515,6 +515,9 @@ int build_table(fda_ctx* ctx, int R, int slots, int fb, int words, int grp, int6
   const fda_desc& d = ctx->desc;
   const Plan& pl = ctx->plan;
   const long long groups = pl.dpad / 4;
+  // what the kernel's arrays assume: at most 8 row slots, records of at most 8 words, placement groups of 2..8 rows
+  if (slots < 1 || slots > 8 || words < 1 || words > 8 || grp < 1 || grp > 8 || slots * fb > words * 16)
+    return fail(FDA_EINVAL, "table shape out of range: %d slots of %d bits in %d words, groups of %d", slots, fb, words, grp);
   hipLaunchKernelGGL(fda::hash_table_kernel,
                      dim3((unsigned)((groups + fda::kSmallThreads - 1) / fda::kSmallThreads), (unsigned)R),
                      dim3(fda::kSmallThreads), 0, st, ctx->coef, d.l, R, slots, d.m, fb, words, grp,
