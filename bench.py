@@ -281,6 +281,36 @@ def main():
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     value = K * d / (ms_per_step * 1e-3)
 
+    # the same step as ONE call (fda_step) captured in a HIP graph and replayed: what a training loop that
+    # replays its step pays, without the host's launch gaps -- reported beside `value`, never as it
+    graph_info = None
+    if args.variants & 2 or args.variants & 1:
+        by = "sketch" if args.variants & 2 else "linear"
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            mon.step(wl.w, wl.w_t0, w_prev, wl.xi if args.variants & 1 else None, theta, decide_by=by)
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            mon.step(wl.w, wl.w_t0, w_prev, wl.xi if args.variants & 1 else None, theta, decide_by=by)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        g0, g1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        g0.record()
+        for _ in range(args.steps):
+            graph.replay()
+        g1.record()
+        torch.cuda.synchronize()
+        est_g = mon.estimate_variance(theta)
+        assert (est_g.sync_sketch if args.variants & 2 else est_g.sync_linear) == 0
+        assert est_g.h_sketch == est.h_sketch and est_g.h_linear == est.h_linear
+        graph_info = {"ms_per_step": round(g0.elapsed_time(g1) / args.steps, 4), "replays": args.steps,
+                      "what": "fda_step (the same kernels, decision: no sync) captured once in a HIP graph"}
+        del graph
+
     abytes = algorithmic_bytes(K, d, esz, args.variants)
     kern_ms_avg = kernel_ms / max(launches, 1)
     achieved = abytes / (kern_ms_avg * 1e-3) / 1e9
@@ -451,6 +481,7 @@ def main():
                    "step": "fda_local_state + fda_estimate_variance + predicated fda_sync_xi "
                            "(decision: no sync)"},
         "roofline": roofline,
+        "graph_replay": graph_info,
         "mean_state_mode": mean_info,
         "sync": sync_info,
     }
