@@ -175,7 +175,7 @@ int make_split(const fda_desc* d, int cus, int64_t lds_cu, int cell_bytes, Split
           const double pairs = (KC % 2 == 0 && narrow) ? KC / 2 : KC;           // LDS instructions per row slot
           // (a table with placed rows avoids about a third of the LDS collisions)
           const bool placed = narrow && split && cells && fda::placed_kernel_exists(KC) &&
-                              !(d->flags & FDA_DESC_PLAIN_TABLE) && fda::placed_group_rows(rc, d->m) >= 2;
+                              !(d->flags & FDA_DESC_PLAIN_TABLE) && fda::placed_group_rows(rc, d->m, KC) >= 2;
           const double per_add = (KC % 2 == 0 && narrow) ? (placed ? kPlacedPairAddCost
                                                             : split ? kPairAddCost : kPairAddCost + 2.0 * kSelectCost)
                                                          : kAtomicCost + kSelectCost;
@@ -319,7 +319,7 @@ int make_plan(const fda_desc* d, int cus, int64_t lds_cu, Plan* pl) {
   pl->narrow_fb = pl->fb;
   if (sk && pl->narrow.split && fda::placed_kernel_exists(pl->narrow.KC) &&
       !(d->flags & FDA_DESC_PLAIN_TABLE)) {
-    const int g = fda::placed_group_rows(pl->narrow.rcnt_max, d->m);
+    const int g = fda::placed_group_rows(pl->narrow.rcnt_max, d->m, pl->narrow.KC);
     if (g >= 2) { pl->grp = g; pl->narrow_fb = fda::kPlacedFieldBits; }
   }
   pl->words = (pl->narrow.LR * pl->narrow_fb + 15) / 16;
@@ -511,7 +511,7 @@ int prof_end(fda_ctx* c, hipStream_t st, int slot) {
 
 // Before the first sketch of a context: the hash table and the cell counts.  Then, per call, the
 // fixed-point units from a sample of the drifts (this also clears the flags in *scale).
-int build_table(fda_ctx* ctx, int R, int slots, int fb, int words, int grp, int64_t off, hipStream_t st) {
+int build_table(fda_ctx* ctx, int R, int slots, int fb, int words, int grp, int KC, int64_t off, hipStream_t st) {
   const fda_desc& d = ctx->desc;
   const Plan& pl = ctx->plan;
   const long long groups = pl.dpad / 4;
@@ -520,7 +520,7 @@ int build_table(fda_ctx* ctx, int R, int slots, int fb, int words, int grp, int6
     return fail(FDA_EINVAL, "table shape out of range: %d slots of %d bits in %d words, groups of %d", slots, fb, words, grp);
   hipLaunchKernelGGL(fda::hash_table_kernel,
                      dim3((unsigned)((groups + fda::kSmallThreads - 1) / fda::kSmallThreads), (unsigned)R),
-                     dim3(fda::kSmallThreads), 0, st, ctx->coef, d.l, R, slots, d.m, fb, words, grp,
+                     dim3(fda::kSmallThreads), 0, st, ctx->coef, d.l, R, slots, d.m, fb, words, grp, KC,
                      (long long)d.d, (long long)pl.dpad, reinterpret_cast<uint16_t*>(ctx->ws + off));
   FDA_HIP(hipGetLastError());
   return FDA_OK;
@@ -553,13 +553,13 @@ int prepare_sketch(fda_ctx* ctx, const void* w, const float* w_t0, fda::ScaleInf
   }
   // ... and the hash of every (row, coordinate), tabulated for the pass that is about to run
   if (!for_mean && !ctx->table_built) {
-    int rc = build_table(ctx, pl.narrow.R, pl.narrow.LR, pl.narrow_fb, pl.words, pl.grp, pl.off_table, st);
+    int rc = build_table(ctx, pl.narrow.R, pl.narrow.LR, pl.narrow_fb, pl.words, pl.grp, pl.narrow.KC, pl.off_table, st);
     if (rc != FDA_OK) return rc;
     ctx->table_built = true;
     if (pl.shared_table) ctx->mean_table_built = true;
   }
   if (for_mean && !ctx->mean_table_built) {
-    int rc = build_table(ctx, pl.mean.R, pl.mean.rcnt_max, pl.fb, pl.mean_words, 1, pl.off_mean_table, st);
+    int rc = build_table(ctx, pl.mean.R, pl.mean.rcnt_max, pl.fb, pl.mean_words, 1, 1, pl.off_mean_table, st);
     if (rc != FDA_OK) return rc;
     ctx->mean_table_built = true;
     if (pl.shared_table) ctx->table_built = true;

@@ -229,20 +229,6 @@ __device__ __forceinline__ uint32_t hash_entry(const HashCoef& hc, int row, uint
 constexpr int kDummyCells = 64;              // cells of the dummy region (power of two)
 // field width for a sketch of m columns (a field is below 2 m): 11 bits while m <= 1024, else 16
 __host__ __device__ constexpr int field_bits_for(int m) { return m <= 1024 ? 11 : 16; }
-// A table with PLACED rows (sign-split LDS rows of 2 m buckets, unskewed layouts): the row slots of a record
-// come in groups of `grp` consecutive rows, and inside a group the builder of the table decides per
-// coordinate which slot holds which row (a rotation).  A field is then (row within the group) * 2 m + s,
-// the bucket index counted from the group's first row, in kPlacedFieldBits bits; the state kernel adds the
-// group's base and never learns the row.  What the builder gains by it: the 64-bit LDS additions of one
-// instruction are served 16 lanes at a time, lanes whose 8-byte words lie 128 bytes apart one after the
-// other, and with a choice of slots part of those collisions can be avoided (measured: 8.2 to 8.7 LDS
-// clocks per addition instead of 12.3).
-constexpr int kPlacedFieldBits = 13;
-__host__ __device__ constexpr int placed_group_rows(int rows, int m) {     // 0: no placement
-  const int fit = (1 << kPlacedFieldBits) / (2 * m);
-  const int g = rows < fit ? rows : fit;
-  return g >= 2 ? g : 0;
-}
 template <int LR, int FB>
 struct RecGeom {
   static constexpr int kWords = (LR * FB + 15) / 16;        // 16-bit words per coordinate record
@@ -373,11 +359,30 @@ __host__ __device__ constexpr bool cells32_skewed(int KC) { return KC % 4 == 0; 
 __host__ __device__ constexpr uint32_t cells32_bucket_word(uint32_t b, int KC) {   // first word of bucket b in its row
   return b * (uint32_t)KC + (cells32_skewed(KC) ? ((b >> 3) << 1) : 0u);
 }
+// buckets a row of m takes up: with the skew a whole number of groups of 8, so that the offset of bucket
+// number r * (that) + b of a run of rows is the r-th row's base plus the offset of b in its row
+__host__ __device__ constexpr int cells32_row_buckets(int m, int KC) {
+  return cells32_skewed(KC) ? (m + 7) / 8 * 8 : m;
+}
 __host__ __device__ constexpr uint32_t cells32_row_words(int m, int KC) {          // words of one row of m buckets
-  return cells32_bucket_word((uint32_t)m, KC) + (cells32_skewed(KC) ? 2u : 0u);     // even whenever KC is
+  return cells32_bucket_word((uint32_t)cells32_row_buckets(m, KC), KC);            // even whenever KC is
 }
 __host__ __device__ constexpr uint32_t cells32_words(int rows, int m, int KC) {    // rows plus the dummy region
   return (uint32_t)rows * cells32_row_words(m, KC) + cells32_row_words(kDummyCells, KC);
+}
+// A table with PLACED rows (sign-split LDS rows of 2 m buckets, an even number of worker slots): the row
+// slots of a record come in groups of `grp` consecutive rows, and inside a group the builder of the table
+// decides per coordinate which slot holds which row (a rotation).  A field is then (row within the group)
+// * (buckets a row takes up, cells32_row_buckets) + s, the bucket index counted from the group's first row,
+// in kPlacedFieldBits bits; the state kernel adds the group's base and never learns the row.  What the
+// builder gains by it: the 64-bit LDS additions of one instruction are served 16 lanes at a time, lanes
+// whose 8-byte words lie 128 bytes apart one after the other, and with a choice of slots part of those
+// collisions can be avoided (measured: 8.2 to 8.7 LDS clocks per addition instead of 12.3).
+constexpr int kPlacedFieldBits = 13;
+__host__ __device__ constexpr int placed_group_rows(int rows, int m, int KC) {     // 0: no placement
+  const int fit = (1 << kPlacedFieldBits) / cells32_row_buckets(2 * m, KC);
+  const int g = rows < fit ? rows : fit;
+  return g >= 2 ? g : 0;
 }
 // Sign-split rows (SPLIT): a row has 2 m buckets, the table field s itself is the bucket index -- terms
 // of sign -1 are ADDED to bucket m + b, and the flush takes (bucket b) - (bucket m + b).  The pass then

@@ -26,20 +26,20 @@ namespace fda {
 // records that a lane of the state kernels loads together are placed where load_rec_block() reads
 // them.  One thread writes one lane's share; a workgroup of kSmallThreads covers 4 blocks.
 //
-// grp >= 2: placed rows (see kPlacedFieldBits).  The rows of the group come in placement groups of grp;
-// slot a of a placement group of n rows holds row (a + rot) % n of it, field = that row's number in the
-// group times 2 m plus the plain field, and rot is chosen per coordinate so that the additions one
-// instruction of the state kernel issues collide as little as the choice allows.  The model: the 16
-// lanes 16 g .. 16 g + 15 of a wave are served together, instruction (v, slot) takes coordinate 4 lane + v
-// of the block from each, and two of them collide when their cells' indices agree modulo 16 (8-byte
-// words 128 bytes apart; with 3 such words per bucket the word index is 3 times the cell index, the same
-// classes).  Cost of an instruction = the largest number of lanes in one class; per (16 lanes, v,
+// grp >= 2: placed rows (see kPlacedFieldBits) for a state kernel of KC worker slots.  The rows of the
+// group come in placement groups of grp; slot a of a placement group of n rows holds row (a + rot) % n of
+// it, field = that row's number in the group times the buckets a row takes up (cells32_row_buckets) plus
+// the plain field, and rot is chosen per coordinate so that the additions one instruction of the state
+// kernel issues collide as little as the choice allows.  The model: the 16 lanes 16 g .. 16 g + 15 of a
+// wave are served together, instruction (v, slot) takes coordinate 4 lane + v of the block from each, and
+// two of them collide when the 8-byte words they address lie a multiple of 128 bytes apart: the word
+// index of a field (cells32_bucket_word / 2) modulo 16 is its class.  Cost of an instruction = the largest number of lanes in one class; per (16 lanes, v,
 // placement group) one thread places the 16 coordinates one after the other where the sum over the
 // slots grows least, then revisits each twice.  The result depends only on the hash and the shape.
 constexpr int kPlaceSweeps = 3;
 __global__ void __launch_bounds__(kSmallThreads)
-hash_table_kernel(const HashCoef hc, int l, int R, int slots, int m, int fb, int words, int grp, long long d,
-                  long long dpad, uint16_t* __restrict__ table) {
+hash_table_kernel(const HashCoef hc, int l, int R, int slots, int m, int fb, int words, int grp, int KC,
+                  long long d, long long dpad, uint16_t* __restrict__ table) {
   __shared__ uint16_t fld[kSmallThreads][4][8];                // plain fields, by thread, coordinate, row
   __shared__ uint8_t rotsel[kSmallThreads][4][4];              // chosen rotation, by thread, coordinate, placement group
   __shared__ uint8_t hist[kSmallThreads / 64][16][8][16];      // by wave, (16 lanes, v), slot, class
@@ -49,7 +49,7 @@ hash_table_kernel(const HashCoef hc, int l, int R, int slots, int m, int fb, int
   int rstart, rcnt;
   group_range(l, R, r, &rstart, &rcnt);
   const bool placed = grp >= 2;
-  const uint32_t mrow = 2u * (uint32_t)m;
+  const uint32_t mrow = placed ? (uint32_t)cells32_row_buckets(2 * m, KC) : 0u;   // buckets per LDS row, as a field counts them
   for (int q = 0; q < 4; ++q) {
     const long long j = j4 + q;
     for (int i = 0; i < slots; ++i) {
@@ -77,7 +77,10 @@ hash_table_kernel(const HashCoef hc, int l, int R, int slots, int m, int fb, int
         for (int c = 0; c < 16; ++c) h[a][c] = 0;
       const int member0 = wave * 64 + gi * 16;
       // class of member t's entry of row `row` (within the placement group)
-      auto cls = [&](int t, int row) { return (int)(((uint32_t)row * mrow + fld[member0 + t][v][g0 + row]) & 15u); };
+      auto cls = [&](int t, int row) {
+        const uint32_t field = (uint32_t)row * mrow + fld[member0 + t][v][g0 + row];
+        return (int)((cells32_bucket_word(field, KC) >> 1) & 15u);
+      };
       for (int sweep = 0; sweep < kPlaceSweeps; ++sweep) {
         for (int t = 0; t < 16; ++t) {
           if (sweep > 0) {

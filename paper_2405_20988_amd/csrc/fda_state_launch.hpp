@@ -17,9 +17,9 @@ constexpr int kKCSet[] = {1, 2, 4, 6, 8};
 constexpr int kMaxLR = 8;
 constexpr int kMaxSlots = 32;
 constexpr bool narrow_kernel_exists(int KC, bool split) { return split ? KC % 2 == 0 : KC <= 2; }
-// ... and kernels for a table with placed rows (fields of kPlacedFieldBits bits) for the even KC whose
-// layout has no skew: there a field times the bucket stride is the cell's offset in the whole group
-constexpr bool placed_kernel_exists(int KC) { return KC % 2 == 0 && !cells32_skewed(KC); }
+// ... and kernels for a table with placed rows (fields of kPlacedFieldBits bits) for the even KC: there a
+// field is a bucket number in a whole group of rows
+constexpr bool placed_kernel_exists(int KC) { return KC % 2 == 0; }
 // fallback passes (8-byte cells)
 constexpr int kWideKCSet[] = {1, 2, 4};
 constexpr int kWideLRSet[] = {1, 2, 4, 8};

@@ -127,10 +127,9 @@ def test_plan_chooses_the_rows_the_lds_allows():
     assert (p.worker_groups, p.worker_slots, p.sign_split_rows) == (2, 2, 1)
     p = plan(1, 5, 250)                    # a single worker: one slot, 32-bit additions, plain rows
     assert (p.worker_slots, p.sign_split_rows) == (1, 0)
-    p = plan(3, 5, 250)                    # three workers: two groups of two slots (one spare), whose layout
-    assert (p.worker_groups, p.worker_slots, p.sign_split_rows) == (2, 2, 1)     # allows placed rows
-    assert p.placed_row_group == 5
-    p = plan(3, 5, 250, flags=F.FDA_DESC_PLAIN_TABLE)    # ... without them a kernel of four slots (one spare)
+    p = plan(3, 5, 250)                    # three workers take a kernel of four slots (one spare), rows placed
+    assert (p.worker_groups, p.worker_slots, p.sign_split_rows, p.placed_row_group) == (1, 4, 1, 5)
+    p = plan(3, 5, 250, flags=F.FDA_DESC_PLAIN_TABLE)    # ... or not
     assert (p.worker_groups, p.worker_slots, p.sign_split_rows, p.placed_row_group) == (1, 4, 1, 0)
     p = plan(3, 1, 19_000)                 # one slot per workgroup: the row fills the LDS
     assert (p.worker_groups, p.worker_slots, p.sign_split_rows) == (3, 1, 0)

@@ -98,11 +98,11 @@ STATE_CASES = [
     ("cfg2", 30_011, {"K": 4, "l": 2, "m": 4_500}),     # two groups of two rather than four slots: split rows fit
     ("cfg2", 30_011, {"K": 5, "l": 6, "m": 64}),        # 6 slots x 6 rows are not built: groups of 2, 2, 1 workers
     ("cfg2", 30_011, {"K": 5, "l": 5, "m": 64}),        # five workers in six slots: a spare high half
-    ("cfg5", 40_009, {"K": 8, "l": 4, "m": 300}),       # bf16, eight slots (with the plain table; else 4 x 2)
+    ("cfg5", 40_009, {"K": 8, "l": 4, "m": 300}),       # bf16, eight slots
     ("cfg2", 20_011, {"K": 2, "l": 1, "m": 20_000}),    # about the widest sketch the LDS takes: 16-bit table fields up to 2 m - 1
 ]
 EXPECTED_ROWS = {(2, 3, 6_000): (2, 0), (4, 2, 4_500): (2, 1), (5, 6, 64): (2, 1), (5, 5, 64): (6, 1), (8, 4, 300): (8, 1)}
-PLAIN_TABLE_CASES = {(8, 4, 300)}       # planned without placed rows (FDA_DESC_PLAIN_TABLE), for the kernel they then get
+PLAIN_TABLE_CASES = {(5, 5, 64)}        # planned without placed rows (FDA_DESC_PLAIN_TABLE): the same kernel on the plain table
 
 
 @pytest.mark.parametrize("name,d,over", STATE_CASES)
@@ -559,7 +559,12 @@ def _apply_noise(w, latent, noise, dtype):
                                          ("cfg5", 5_001, {"K": 2, "l": 9, "m": 250}), ("cfg1", None, {"l": 3, "m": 1024}),
                                          ("cfg2", 100_001, {"K": 2, "l": 8, "m": 500}),
                                          ("cfg5", 9_001, {"K": 2, "l": 11, "m": 700}),
-                                         ("cfg5", 9_001, {"K": 6, "l": 7, "m": 2048})])
+                                         ("cfg5", 9_001, {"K": 6, "l": 7, "m": 2048}),
+                                         ("cfg2", 100_001, {}),                               # four slots: a layout with a skew
+                                         ("cfg5", 40_009, {"K": 8, "l": 4, "m": 300}),         # eight slots
+                                         ("cfg2", 50_001, {"K": 4, "l": 5, "m": 251}),         # rows of 502 buckets take up 504
+                                         ("cfg2", 50_001, {"K": 7, "l": 3, "m": 1023}),
+                                         ("cfg5", 20_001, {"K": 8, "l": 3, "m": 251})])
 def test_placed_rows_give_the_same_state(name, d, over):
     """A table whose row slots are chosen per coordinate (against LDS collisions) and the plain table:
     the same cells receive the same integer terms, so the states agree bit for bit -- and with the oracle."""
